@@ -1,0 +1,183 @@
+/*
+ * tofu.h -- C ABI of the shard hot path of Tofu's partition-n-reduce method
+ * (arXiv 1807.08887) for one AMD MI355X (gfx950).
+ *
+ * One worker's share of a partitioned operator is: derive the worker's
+ * coordinate ranges (Sec. 4.2, Case-1 / Case-2; Sec. 5.2 recursion), assemble
+ * the input region it needs from the blocks that hold it (Sec. 6, fused remote
+ * fetch), run the *same* operator on those smaller inputs (Sec. 3.1), and --
+ * when a reduction dimension was split -- sum the k partial outputs
+ * (Sec. 3.1 way 2; Sec. 6 output reduction).
+ *
+ * Conventions shared by every entry point
+ *   - Element type is IEEE fp32 everywhere on the device.
+ *   - A region is a half-open box [lo,hi) per dimension in the GLOBAL
+ *     coordinates of the unpartitioned tensor.  The paper writes inclusive
+ *     ranges [a,b]; that is [a,b+1) here.
+ *   - A tofu_tensor_t describes a caller-owned DEVICE buffer holding the box
+ *     `extent` of a global tensor.  stride[d] is the element stride of
+ *     dimension d inside that buffer; stride[] all zero means dense row-major
+ *     over the extent.  The library never allocates, frees or synchronises:
+ *     every call only validates on the host and enqueues kernels on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the null stream).
+ *   - Return value: TOFU_OK (0) or a negative tofu_status_t.  All argument
+ *     checks happen on the host before anything is launched; after a failure
+ *     tofu_last_error() returns a thread-local description.
+ *   - Layouts: matmul A[M,K], B[K,N], C[M,N] row-major.  conv2d x[N,C_in,H,W],
+ *     w[C_out,C_in,KH,KW] (output channel outermost), y[N,C_out,H_out,W_out].
+ *     The convolution is a cross-correlation (index x+dx, no filter flip) as in
+ *     the paper's conv1d loop nest (Fig. 1), with zero padding `pad`.
+ */
+#ifndef TOFU_H_
+#define TOFU_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TOFU_MAX_DIMS 6
+
+typedef enum {
+  TOFU_OK = 0,
+  TOFU_ERR_INVALID_ARG = -1,        /* null pointer, bad ndim, k<1, shard outside [0,k), k>extent, bad dim */
+  TOFU_ERR_REGION_MISMATCH = -2,    /* a tensor's extent does not contain the box the shard needs        */
+  TOFU_ERR_UNCOVERED = -3,          /* fetch sources leave part of dst->extent without data              */
+  TOFU_ERR_OVERLAP = -4,            /* two fetch sources both claim a coordinate of dst->extent          */
+  TOFU_ERR_WORKSPACE_TOO_SMALL = -5,
+  TOFU_ERR_UNSUPPORTED = -6,        /* operator parameters outside what the kernels implement            */
+  TOFU_ERR_HIP = -7                 /* a HIP runtime call failed; see tofu_last_error()                  */
+} tofu_status_t;
+
+/* Tensor region (Sec. 4.2: a partition strategy is given by the input regions
+ * each worker needs).  Half-open, global coordinates. */
+typedef struct {
+  int32_t ndim;
+  int64_t lo[TOFU_MAX_DIMS];
+  int64_t hi[TOFU_MAX_DIMS];
+} tofu_region_t;
+
+/* A device buffer that holds box `extent` of some global tensor. */
+typedef struct {
+  void* data;                       /* DEVICE pointer, fp32, caller-owned                     */
+  tofu_region_t extent;             /* which global box the buffer holds                      */
+  int64_t stride[TOFU_MAX_DIMS];    /* element strides; all 0 = dense row-major over extent   */
+} tofu_tensor_t;
+
+/* One basic partition step p_i (Appendix A.1): split ONE iteration dimension
+ * of the operator k ways and keep part `shard`.  A plan is a sequence of
+ * steps; each later step cuts the range left by the earlier ones (Sec. 5.2),
+ * so <(d,2,a),(d,2,b)> is the quarter 2a+b of d when 4 divides the extent. */
+typedef struct {
+  int32_t dim;                      /* one of the TOFU_*_DIM_* names below, per operator kind */
+  int32_t k;                        /* number of parts, >= 1                                  */
+  int32_t shard;                    /* which part, 0 <= shard < k                             */
+} tofu_split_t;
+
+typedef enum {
+  TOFU_OP_MATMUL = 0,               /* C[m,n]      = sum_k A[m,k] B[k,n]                                     */
+  TOFU_OP_CONV2D = 1,               /* y[n,co,h,w] = sum_{ci,kh,kw} x[n,ci,h*s+kh-p,w*s+kw-p] w[co,ci,kh,kw] */
+  TOFU_OP_CONV2D_WGRAD = 2          /* dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] x[n,ci,h*s+kh-p,w*s+kw-p]  */
+} tofu_op_kind_t;
+
+/* Iteration dimensions a split may name.  Output dimensions give Case-1
+ * (concatenate, Sec. 4.2); reduction dimensions give Case-2 (the shard's
+ * output is a full-size partial that tofu_partition_reduce must sum). */
+enum { TOFU_MM_DIM_M = 0, TOFU_MM_DIM_N = 1, TOFU_MM_DIM_K = 2 /* reduction */ };
+enum { TOFU_CONV_DIM_N = 0, TOFU_CONV_DIM_CO = 1, TOFU_CONV_DIM_H = 2, TOFU_CONV_DIM_W = 3,
+       TOFU_CONV_DIM_CI = 4 /* reduction */ };
+enum { TOFU_WGRAD_DIM_CO = 0, TOFU_WGRAD_DIM_CI = 1, TOFU_WGRAD_DIM_N = 2 /* reduction */ };
+
+/* Operator description with the shapes of the UNPARTITIONED operator. */
+typedef struct {
+  int32_t kind;                     /* tofu_op_kind_t */
+  int64_t M, N, K;                  /* matmul */
+  int64_t batch, c_in, c_out, H, W; /* conv: input is [batch,c_in,H,W] */
+  int64_t KH, KW, stride, pad;      /* conv: dilation 1, groups 1; output H_out = (H+2*pad-KH)/stride+1 */
+} tofu_op_desc_t;
+
+/* ---- host-only integer helpers (exact, no device work) ------------------ */
+
+/* Part `shard` of a k-way even split of [0,extent) (Sec. 4.2 halves, Sec. 5.2
+ * k_i-way steps): [floor(shard*extent/k), floor((shard+1)*extent/k)).  Parts
+ * are disjoint, ordered, cover the extent and differ in size by at most one.
+ * Errors: extent<0, k<1, shard outside [0,k), k>extent -> INVALID_ARG. */
+int tofu_shard_range(int64_t extent, int32_t k, int32_t shard, int64_t* lo, int64_t* hi);
+
+/* Regions of one shard (Sec. 4.2).  Applies `splits` in order to the
+ * operator's iteration space and returns
+ *   out_box      the box of the output tensor this shard writes (the whole
+ *                output when only reduction dimensions were split),
+ *   in_boxes[0]  the box of the first input it reads  (A | x | x),
+ *   in_boxes[1]  the box of the second input it reads (B | w | dy),
+ *   pad_lo/hi[2] conv only: rows/columns (index 0 = H, 1 = W) of the needed
+ *                window that fall outside the global input on the low/high
+ *                side and are therefore zeros; in_boxes[0] is already clipped,
+ *   is_partial   1 when a reduction dimension was split (Case-2), else 0.
+ * For conv spatial splits the input box is the output range widened by the
+ * filter window ("halo", Sec. 4.2).  Any of the out pointers may be NULL. */
+int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                    tofu_region_t* out_box, tofu_region_t* in_boxes,
+                    int64_t* pad_lo, int64_t* pad_hi, int32_t* is_partial);
+
+/* Bytes of device workspace the shard call for (op, splits) may use; the
+ * caller passes a buffer at least this large (0 means none is needed). */
+size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits);
+
+/* Thread-local text for the last non-zero status returned on this thread. */
+const char* tofu_last_error(void);
+
+/* ---- device entry points ------------------------------------------------ */
+
+/* Fused region fetch (Sec. 6, MultiFetch): assemble dst->extent from `nsrc`
+ * source blocks in ONE launch.  `srcs` is a HOST array of descriptors whose
+ * data pointers are device pointers; each source contributes the
+ * intersection of its extent with dst->extent.  The sources must tile
+ * dst->extent exactly: a hole -> UNCOVERED, a doubly-claimed coordinate ->
+ * OVERLAP (both detected on the host from the boxes alone).  All tensors
+ * must have the same ndim (1..TOFU_MAX_DIMS).  An empty dst->extent is a
+ * no-op.  nsrc is limited to 64.  dst must not alias any source. */
+int tofu_region_fetch(const tofu_tensor_t* dst, const tofu_tensor_t* srcs, int32_t nsrc,
+                      void* hip_stream);
+
+/* Shard of a matrix multiplication (Sec. 3.1: the same operator on smaller
+ * inputs).  A, B, C are addressed by GLOBAL coordinate through their extents,
+ * so the caller may pass the full tensors, owned blocks or freshly fetched
+ * regions; each extent must contain the box tofu_op_regions derives, else
+ * REGION_MISMATCH.  Writes C over the shard's output box only.  When K was
+ * split the values written are the partial sums over the shard's K range. */
+int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                      const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Shard of a 2-D convolution forward pass (Fig. 1 generalised to two spatial
+ * dimensions; Sec. 4.2 Case-1 for N/CO/H/W splits incl. halo, Case-2 for CI).
+ * Implemented for KH = KW = 3, stride 1, pad 0 or 1 -> otherwise UNSUPPORTED.
+ * Input rows/columns outside the GLOBAL tensor are zeros; rows inside the
+ * global tensor but outside x->extent are REGION_MISMATCH, never zeros. */
+int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                      const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Shard of the convolution's weight gradient.  The batch index is a
+ * reduction index of this operator, so a batch split is Case-2 (Sec. 4.2)
+ * and dw receives a full-size partial.  Same parameter limits as above. */
+int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                            const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Partition-n-reduce output step (Sec. 3.1 way 2; Sec. 6): dst[i] =
+ * partials[0][i] + partials[1][i] + ... + partials[k-1][i], summed in that
+ * order in fp32, for i in [0,count).  `partials` is a HOST array of k DEVICE
+ * pointers (1 <= k <= 16), each to `count` dense fp32 values.  dst may be
+ * partials[0] (in-place aggregation, Sec. 7.2); no other aliasing.  count = 0
+ * is a no-op. */
+int tofu_partition_reduce(void* dst, const void* const* partials, int32_t k, int64_t count,
+                          void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOFU_H_ */

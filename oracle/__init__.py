@@ -1,0 +1,10 @@
+"""CPU oracle of the partition-n-reduce shard path (arXiv 1807.08887).
+
+TEST INFRASTRUCTURE.  Only tests, the smoke check and the bench's cpu_baseline leg may
+import this package; the product path (paper_1807_08887_amd) never does, and this package
+never imports the product.  `regions` holds the integer range/region definitions and the
+fetch; `ops` wraps the fp64 loop nests of tofu_oracle.c.
+"""
+from . import regions  # noqa: F401
+from .ops import (build, conv2d_box, conv2d_pts, matmul_box, matmul_pts, reduce, threads,  # noqa: F401
+                  wgrad_box, wgrad_pts)

@@ -1,0 +1,370 @@
+"""Pins for the CPU oracle: it is checked against what the paper prints, against closed
+forms and invariants, against independent library routines (numpy matmul, torch conv2d and
+autograd in fp64) and against brute force on tiny shapes.  No GPU, no HIP library."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+import tofu_synth as synth
+from oracle import regions as R
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ------------------------------------------------------------------ split ranges
+def test_shift_two_example_from_paper():
+    """Sec. 4.2 worked example: halves of i in [0,9] need A over [2,6] and [7,11]."""
+    rows = [[int(v) for v in r] for r in _rows("shift_two.txt")]
+    extent = rows[-1][1] + 1
+    for shard, (olo, ohi, ilo, ihi) in enumerate(rows):
+        lo, hi = R.shard_range(extent, 2, shard)
+        assert (lo, hi - 1) == (olo, ohi)
+        # B[i] = A[i+2] is a window of size 1 shifted by +2 (pad = -2); A has extent+2 elements
+        (a, b), cut_lo, cut_hi = R._window(lo, hi, 1, 1, -2, extent + 2)
+        assert (a, b - 1) == (ilo, ihi) and cut_lo == 0 and cut_hi == 0
+
+
+def test_shard_range_brute_force():
+    for D in range(1, 65):
+        for k in range(1, min(D, 8) + 1):
+            parts = [R.shard_range(D, k, s) for s in range(k)]
+            assert parts[0][0] == 0 and parts[-1][1] == D
+            sizes = [hi - lo for lo, hi in parts]
+            assert all(parts[i][1] == parts[i + 1][0] for i in range(k - 1))  # ordered, disjoint, no holes
+            assert min(sizes) >= 1 and max(sizes) - min(sizes) <= 1
+            assert sorted(sizes) == sorted([D // k + (1 if i < D % k else 0) for i in range(k)])
+
+
+@pytest.mark.parametrize("bad", [(-1, 1, 0), (4, 0, 0), (4, 2, 2), (4, 2, -1), (3, 4, 0)])
+def test_shard_range_rejects(bad):
+    with pytest.raises(ValueError):
+        R.shard_range(*bad)
+
+
+def test_recursive_steps_make_grids():
+    """Sec. 5.2: row split then column split = 2x2 grid; row then row = four row strips."""
+    op = dict(kind="matmul", M=8, N=12, K=5)
+    seen = set()
+    for a, b in itertools.product(range(2), repeat=2):
+        box = R.op_regions(op, [("M", 2, a), ("N", 2, b)])["out_box"]
+        assert box == [(4 * a, 4 * a + 4), (6 * b, 6 * b + 6)]
+        seen.add(tuple(box))
+        strip = R.op_regions(op, [("M", 2, a), ("M", 2, b)])["out_box"]
+        assert strip == [(2 * (2 * a + b), 2 * (2 * a + b) + 2), (0, 12)]
+        assert strip[0] == R.shard_range(8, 4, 2 * a + b)
+    assert len(seen) == 4
+
+
+def test_after_i_steps_tensors_are_1_over_2_to_i():
+    """Appendix A.1: after i two-way steps the sub-tensors have 1/2^i of the elements."""
+    op = dict(kind="conv2d", batch=8, c_in=16, c_out=32, H=16, W=16, KH=1, KW=1, stride=1, pad=0)
+    full = 8 * 32 * 16 * 16
+    for dims in itertools.product(["N", "CO", "H", "W"], repeat=3):
+        for i in range(1, 4):
+            box = R.op_regions(op, [(d, 2, 1) for d in dims[:i]])["out_box"]
+            assert np.prod([hi - lo for lo, hi in box]) * 2 ** i == full
+
+
+def test_search_space_counts_from_paper():
+    """Sec. 5.2: 20 even partitions of a 4-D tensor over 8 workers; 20^6; 4^6; 3*4^6."""
+    gold = {k: int(v) for k, v in _rows("search_space_counts.txt")}
+    op = dict(kind="conv2d", batch=8, c_in=3, c_out=16, H=32, W=64, KH=1, KW=1, stride=1, pad=0)
+    shapes = set()
+    for dims in itertools.product(["N", "CO", "H", "W"], repeat=3):
+        box = R.op_regions(op, [(d, 2, 0) for d in dims])["out_box"]
+        shapes.add(tuple(hi - lo for lo, hi in box))
+    assert len(shapes) == gold["ways_4d_8workers"]
+    assert gold["ways_4d_8workers"] ** 6 == gold["configs_no_recursion"]
+    assert 4 ** 6 == gold["configs_per_step"] and 3 * 4 ** 6 == gold["configs_three_steps"]
+
+
+# ------------------------------------------------------------------ input regions
+def _touch_conv(op, ranges):
+    """Naive loop nest over one worker's iteration ranges marking every input coordinate it
+    reads (outside-tensor reads are the zero padding and are counted separately)."""
+    x = np.zeros((op["batch"], op["c_in"], op["H"], op["W"]), dtype=bool)
+    w = np.zeros((op["c_out"], op["c_in"], op["KH"], op["KW"]), dtype=bool)
+    s, p = op["stride"], op["pad"]
+    for n in range(*ranges["N"]):
+        for co in range(*ranges["CO"]):
+            for h in range(*ranges["H"]):
+                for wo in range(*ranges["W"]):
+                    for ci in range(*ranges["CI"]):
+                        for kh in range(op["KH"]):
+                            for kw in range(op["KW"]):
+                                w[co, ci, kh, kw] = True
+                                ih, iw = h * s + kh - p, wo * s + kw - p
+                                if 0 <= ih < op["H"] and 0 <= iw < op["W"]:
+                                    x[n, ci, ih, iw] = True
+    return x, w
+
+
+def _bbox(mask):
+    idx = np.argwhere(mask)
+    return [(int(a), int(b) + 1) for a, b in zip(idx.min(0), idx.max(0))]
+
+
+@pytest.mark.parametrize("stride,pad,ksz", [(1, 1, 3), (1, 0, 3), (2, 1, 3), (1, 2, 5), (2, 0, 2)])
+def test_conv_regions_match_touched_coordinates(stride, pad, ksz):
+    op = dict(kind="conv2d", batch=2, c_in=3, c_out=4, H=9, W=7, KH=ksz, KW=ksz, stride=stride, pad=pad)
+    for dim in ["N", "CO", "H", "W", "CI"]:
+        ext = R.iteration_extents(op)[dim]
+        for k in range(1, min(ext, 3) + 1):
+            for s in range(k):
+                reg = R.op_regions(op, [(dim, k, s)])
+                xm, wm = _touch_conv(op, reg["ranges"])
+                assert _bbox(xm) == [tuple(b) for b in reg["in_boxes"][0]]
+                assert _bbox(wm) == [tuple(b) for b in reg["in_boxes"][1]]
+                assert reg["is_partial"] == (dim == "CI" and k > 1)
+                # residual padding = rows of the needed window that are outside the tensor
+                (hlo, hhi) = reg["ranges"]["H"]
+                assert reg["pad_lo"][0] == max(0, pad - hlo * stride)
+                assert reg["pad_hi"][0] == max(0, (hhi - 1) * stride + ksz - 1 - pad - (op["H"] - 1))
+
+
+def test_conv1d_strategies_from_paper():
+    """Fig. 2 / Sec. 4.2: which part of data and filters each worker reads for a split of
+    b, ci, co, x.  conv1d is our conv2d with W = KW = 1 and no padding; the paper's filters
+    are indexed [ci,co,dx], ours [co,ci,dx,1]."""
+    X, DX = 12, 3
+    op = dict(kind="conv2d", batch=4, c_in=6, c_out=8, H=X + DX - 1, W=1, KH=DX, KW=1, stride=1, pad=0)
+    name = {"b": "N", "ci": "CI", "co": "CO", "x": "H"}
+    full_x = [(0, 4), (0, 6), (0, X + DX - 1), (0, 1)]
+    full_w = [(0, 8), (0, 6), (0, DX), (0, 1)]
+    for split, d_b, d_ci, d_x, f_ci, f_co, f_dx, combine in _rows("conv1d_strategies.txt"):
+        regs = [R.op_regions(op, [(name[split], 2, s)]) for s in range(2)]
+        assert all(r["is_partial"] == (combine == "sum") for r in regs)
+        for col, (dimidx, which) in {"data_b": (0, d_b), "data_ci": (1, d_ci), "data_x": (2, d_x)}.items():
+            parts = [r["in_boxes"][0][dimidx] for r in regs]
+            lo, hi = full_x[dimidx]
+            if which == "all":
+                assert parts == [(lo, hi)] * 2, col
+            elif which == "half":
+                assert parts == [(lo, hi // 2), (hi // 2, hi)], col
+            else:  # halo: the output half widened by the filter window (Fig. 1: x + dx)
+                assert parts == [(0, X // 2 + DX - 1), (X // 2, X + DX - 1)], col
+        for col, (dimidx, which) in {"filters_ci": (1, f_ci), "filters_co": (0, f_co), "filters_dx": (2, f_dx)}.items():
+            parts = [r["in_boxes"][1][dimidx] for r in regs]
+            lo, hi = full_w[dimidx]
+            assert parts == ([(lo, hi)] * 2 if which == "all" else [(lo, hi // 2), (hi // 2, hi)]), col
+
+
+def test_fetch_cost_fractions():
+    """Appendix A.3 (Lemma 1): per worker, fetching an input NOT indexed by the split
+    dimension moves half of it (the whole tensor is needed, half is local); an input that is
+    indexed by it needs only its own half.  Checked as region volumes for the matmul."""
+    op = dict(kind="matmul", M=16, N=24, K=32)
+    reg = R.op_regions(op, [("M", 2, 0)])
+    vol = lambda box: int(np.prod([hi - lo for lo, hi in box]))
+    assert vol(reg["in_boxes"][1]) == 32 * 24          # B not indexed by M: whole tensor needed
+    assert vol(reg["in_boxes"][0]) * 2 == 16 * 32      # A indexed by M: half
+    reg = R.op_regions(op, [("K", 2, 1)])
+    assert vol(reg["in_boxes"][0]) * 2 == 16 * 32 and vol(reg["in_boxes"][1]) * 2 == 32 * 24
+    assert reg["is_partial"] and reg["out_box"] == [(0, 16), (0, 24)]
+
+
+def test_wgrad_and_matmul_regions_brute_force():
+    op = dict(kind="conv2d_wgrad", batch=5, c_in=3, c_out=4, H=6, W=5, KH=3, KW=3, stride=1, pad=1)
+    for dim in ["CO", "CI", "N"]:
+        for s in range(2):
+            reg = R.op_regions(op, [(dim, 2, s)])
+            r = reg["ranges"]
+            assert reg["out_box"] == [r["CO"], r["CI"], (0, 3), (0, 3)]
+            assert reg["in_boxes"][0] == [r["N"], r["CI"], (0, 6), (0, 5)]      # x: every row is read
+            assert reg["in_boxes"][1] == [r["N"], r["CO"], (0, 6), (0, 5)]      # dy
+            assert reg["pad_lo"] == [1, 1] and reg["pad_hi"] == [1, 1]
+            assert reg["is_partial"] == (dim == "N")
+
+
+# ------------------------------------------------------------------ fetch
+def test_fetch_of_split_blocks_is_identity():
+    t = synth.small_int(7, 0, (4, 6, 9), -50, 50)
+    blocks = []
+    for s in range(3):
+        lo, hi = R.shard_range(9, 3, s)
+        blocks.append((t[:, :, lo:hi].copy(), [(0, 4), (0, 6), (lo, hi)]))
+    box = [(1, 4), (0, 6), (2, 8)]
+    got = R.fetch(box, blocks)
+    assert got.dtype == np.float32 and np.array_equal(got, t[1:4, :, 2:8])
+    with pytest.raises(ValueError, match="uncovered"):
+        R.fetch(box, blocks[:2])
+    with pytest.raises(ValueError, match="overlap"):
+        R.fetch(box, blocks + [blocks[1]])
+
+
+# ------------------------------------------------------------------ matmul
+def test_matmul_against_numpy_and_closed_forms():
+    A = synth.uniform(1, 0, (7, 13), -1, 1)
+    B = synth.uniform(1, 1, (13, 5), -1, 1)
+    v, s = oracle.matmul_box(A, B)
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    assert np.allclose(v, ref, rtol=0, atol=1e-13)
+    assert np.allclose(s, np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64), rtol=0, atol=1e-13)
+    # identity and all-ones
+    assert np.array_equal(oracle.matmul_box(A, np.eye(13, dtype=np.float32))[0], A.astype(np.float64))
+    assert np.array_equal(oracle.matmul_box(np.ones((3, 9), np.float32), np.ones((9, 4), np.float32))[0],
+                          np.full((3, 4), 9.0))
+    # small integers: exact against integer arithmetic
+    Ai = synth.small_int(2, 0, (6, 11), -8, 8)
+    Bi = synth.small_int(2, 1, (11, 9), -8, 8)
+    assert np.array_equal(oracle.matmul_box(Ai, Bi)[0], (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64))
+    # box / points / reduction range agree with slicing the full result
+    vb, _ = oracle.matmul_box(A, B, box=((2, 6), (1, 4)))
+    assert np.array_equal(vb, v[2:6, 1:4])
+    pts = [(0, 0), (6, 4), (3, 2)]
+    assert np.array_equal(oracle.matmul_pts(A, B, pts)[0], np.array([v[p] for p in pts]))
+    vk, sk = oracle.matmul_box(A, B, krange=(4, 9))
+    assert np.allclose(vk, A[:, 4:9].astype(np.float64) @ B[4:9].astype(np.float64), rtol=0, atol=1e-13)
+
+
+# ------------------------------------------------------------------ conv2d
+@pytest.mark.parametrize("stride,pad,kh,kw", [(1, 1, 3, 3), (1, 0, 3, 3), (2, 1, 3, 3), (1, 2, 5, 3), (2, 0, 2, 4)])
+def test_conv2d_against_torch_fp64(stride, pad, kh, kw):
+    x = synth.normal(3, 0, (2, 3, 9, 8), 1.0)
+    w = synth.normal(3, 1, (4, 3, kh, kw), 0.5)
+    v, s = oracle.conv2d_box(x, w, stride=stride, pad=pad)
+    ref = F.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), stride=stride, padding=pad).numpy()
+    assert v.shape == ref.shape and np.allclose(v, ref, rtol=0, atol=1e-12)
+    refs = F.conv2d(torch.from_numpy(x).double().abs(), torch.from_numpy(w).double().abs(), stride=stride,
+                    padding=pad).numpy()
+    assert np.allclose(s, refs, rtol=0, atol=1e-12)
+    pts = synth.coords(5, 0, 20, v.shape)
+    assert np.array_equal(oracle.conv2d_pts(x, w, pts, stride=stride, pad=pad)[0], v[tuple(pts.T)])
+
+
+def test_conv2d_closed_forms():
+    # delta kernel: centre tap 1 where co == ci -> y == x exactly
+    x = synth.normal(4, 0, (2, 5, 6, 7), 1.0)
+    w = np.zeros((5, 5, 3, 3), np.float32)
+    w[np.arange(5), np.arange(5), 1, 1] = 1.0
+    assert np.array_equal(oracle.conv2d_box(x, w, pad=1)[0], x.astype(np.float64))
+    # a single off-centre tap shifts the image the way cross-correlation (x+dx) does, not convolution
+    w2 = np.zeros((1, 1, 3, 3), np.float32); w2[0, 0, 0, 2] = 1.0     # reads x[h-1, w+1]
+    img = synth.small_int(4, 1, (1, 1, 5, 5), 0, 9)
+    y = oracle.conv2d_box(img, w2, pad=1)[0]
+    assert np.array_equal(y[0, 0, 1:, :-1], img[0, 0, :-1, 1:].astype(np.float64)) and not y[0, 0, 0].any()
+    # all ones: C_in * (9 interior, 6 edge, 4 corner)
+    y = oracle.conv2d_box(np.ones((1, 4, 5, 6), np.float32), np.ones((2, 4, 3, 3), np.float32), pad=1)[0]
+    assert (y[:, :, 1:-1, 1:-1] == 36).all() and (y[:, :, 0, 1:-1] == 24).all() and (y[:, :, 1:-1, 0] == 24).all()
+    assert y[0, 0, 0, 0] == y[0, 1, -1, -1] == y[0, 0, 0, -1] == 16
+    # 1x1 image with 3x3/pad 1 only sees the centre tap: reduces to a matmul
+    x1 = synth.normal(4, 2, (6, 5, 1, 1), 1.0)
+    w1 = synth.normal(4, 3, (7, 5, 3, 3), 1.0)
+    mm = oracle.matmul_box(x1[:, :, 0, 0], np.ascontiguousarray(w1[:, :, 1, 1].T))[0]
+    assert np.array_equal(oracle.conv2d_box(x1, w1, pad=1)[0][:, :, 0, 0], mm)
+
+
+# ------------------------------------------------------------------ wgrad
+@pytest.mark.parametrize("stride,pad,kh,kw", [(1, 1, 3, 3), (1, 0, 3, 3), (2, 1, 3, 3), (1, 1, 2, 3)])
+def test_wgrad_against_torch_autograd_fp64(stride, pad, kh, kw):
+    x = synth.normal(6, 0, (3, 2, 7, 6), 1.0)
+    w = torch.zeros(4, 2, kh, kw, dtype=torch.float64, requires_grad=True)
+    y = F.conv2d(torch.from_numpy(x).double(), w, stride=stride, padding=pad)
+    dy = synth.normal(6, 1, tuple(y.shape), 1.0)
+    (y * torch.from_numpy(dy).double()).sum().backward()
+    v, s = oracle.wgrad_box(x, dy, kh, kw, stride=stride, pad=pad)
+    assert np.allclose(v, w.grad.numpy(), rtol=0, atol=1e-12)
+    assert (s >= np.abs(v) - 1e-12).all()
+    pts = synth.coords(6, 2, 10, v.shape)
+    assert np.array_equal(oracle.wgrad_pts(x, dy, kh, kw, pts, stride=stride, pad=pad)[0], v[tuple(pts.T)])
+
+
+def test_wgrad_adjoint_identity_and_closed_form():
+    """<dy, conv(x,w)> == <wgrad(x,dy), w> ties the gradient to the forward definition."""
+    x = synth.normal(8, 0, (2, 3, 6, 5), 1.0)
+    w = synth.normal(8, 1, (4, 3, 3, 3), 1.0)
+    dy = synth.normal(8, 2, (2, 4, 6, 5), 1.0)
+    lhs = (dy.astype(np.float64) * oracle.conv2d_box(x, w, pad=1)[0]).sum()
+    rhs = (oracle.wgrad_box(x, dy, 3, 3, pad=1)[0] * w.astype(np.float64)).sum()
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    # all ones, N=2, 4x5 image: centre tap sees H*W, edge taps (H-1)*W or H*(W-1), corners (H-1)(W-1)
+    dw = oracle.wgrad_box(np.ones((2, 1, 4, 5), np.float32), np.ones((2, 1, 4, 5), np.float32), 3, 3, pad=1)[0][0, 0]
+    assert np.array_equal(dw, 2.0 * np.array([[12, 15, 12], [16, 20, 16], [12, 15, 12]]))
+
+
+# ------------------------------------------------------------------ reduce
+def test_reduce_pins():
+    parts = [synth.normal(9, j, (5, 33), 3.0) for j in range(8)]
+    v, s = oracle.reduce(parts)
+    assert np.allclose(v, np.sum(np.stack(parts).astype(np.float64), axis=0), rtol=0, atol=1e-13)
+    assert np.allclose(s, np.sum(np.abs(np.stack(parts)).astype(np.float64), axis=0), rtol=0, atol=1e-13)
+    assert np.array_equal(oracle.reduce(parts[:1])[0], parts[0].astype(np.float64))   # k = 1 is a copy
+    ints = [synth.small_int(9, 20 + j, (4, 4), -100, 100) for j in range(3)]
+    assert np.array_equal(oracle.reduce(ints)[0], (ints[0] + ints[1] + ints[2]).astype(np.float64))
+
+
+# ------------------------------------------------------------------ the partition-n-reduce invariant
+def _assemble(op, dim, k, evaluate):
+    """Concatenate (Case-1) or sum (Case-2) the k shards produced by evaluate(region)."""
+    full_box = R.op_regions(op, [])["out_box"]
+    out = np.zeros([hi - lo for lo, hi in full_box])
+    for s in range(k):
+        reg = R.op_regions(op, [(dim, k, s)])
+        part = evaluate(reg)
+        sl = R.box_slices(reg["out_box"])
+        out[sl] = out[sl] + part if reg["is_partial"] else part
+    return out
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 8])
+def test_pnr_invariant_on_the_oracle(k):
+    """Sec. 3.1: O is the concatenation or the element-wise sum of the workers' outputs.
+    Small-integer data keeps every fp64 sum exact, so equality is bit-exact."""
+    A = synth.small_int(10, 0, (8, 16), -4, 4); B = synth.small_int(10, 1, (16, 9), -4, 4)
+    op = dict(kind="matmul", M=8, N=9, K=16)
+    full = oracle.matmul_box(A, B)[0]
+    for dim in ["M", "N", "K"]:
+        got = _assemble(op, dim, k, lambda reg: oracle.matmul_box(A, B, box=reg["out_box"], krange=reg["ranges"]["K"])[0])
+        assert np.array_equal(got, full), dim
+    x = synth.small_int(10, 2, (8, 8, 9, 8), -3, 3); w = synth.small_int(10, 3, (8, 8, 3, 3), -3, 3)
+    op = dict(kind="conv2d", batch=8, c_in=8, c_out=8, H=9, W=8, KH=3, KW=3, stride=1, pad=1)
+    full = oracle.conv2d_box(x, w, pad=1)[0]
+    for dim in ["N", "CO", "H", "W", "CI"]:
+        got = _assemble(op, dim, k, lambda reg: oracle.conv2d_box(x, w, pad=1, box=reg["out_box"],
+                                                                  cirange=reg["ranges"]["CI"])[0])
+        assert np.array_equal(got, full), dim
+    dy = synth.small_int(10, 4, (8, 8, 9, 8), -3, 3)
+    op["kind"] = "conv2d_wgrad"
+    full = oracle.wgrad_box(x, dy, 3, 3, pad=1)[0]
+    for dim in ["CO", "CI", "N"]:
+        got = _assemble(op, dim, k, lambda reg: oracle.wgrad_box(x, dy, 3, 3, pad=1, box=reg["out_box"],
+                                                                 nrange=reg["ranges"]["N"])[0])
+        assert np.array_equal(got, full), dim
+
+
+def test_shard_computed_from_its_fetched_region_only():
+    """A worker must be able to compute its H-split shard from the fetched (halo-widened)
+    region alone, with the residual padding the regions report: run the unpartitioned
+    definition on the fetched block, padded by hand, and compare with the full result."""
+    x = synth.small_int(11, 0, (2, 3, 10, 6), -3, 3); w = synth.small_int(11, 1, (4, 3, 3, 3), -3, 3)
+    op = dict(kind="conv2d", batch=2, c_in=3, c_out=4, H=10, W=6, KH=3, KW=3, stride=1, pad=1)
+    full = oracle.conv2d_box(x, w, pad=1)[0]
+    own = [(x[:, :, lo:hi].copy(), [(0, 2), (0, 3), (lo, hi), (0, 6)]) for lo, hi in (R.shard_range(10, 2, s) for s in range(2))]
+    for s in range(2):
+        reg = R.op_regions(op, [("H", 2, s)])
+        block = R.fetch(reg["in_boxes"][0], own)
+        padded = np.pad(block, ((0, 0), (0, 0), (reg["pad_lo"][0], reg["pad_hi"][0]), (reg["pad_lo"][1], reg["pad_hi"][1])))
+        y = oracle.conv2d_box(padded, w, pad=0)[0]
+        assert np.array_equal(y, full[R.box_slices(reg["out_box"])])
+
+
+# ------------------------------------------------------------------ the input generator
+def test_synth_is_counter_based_and_plausible():
+    a = synth.normal(1, 0, (1000, 100), 2.0)
+    assert a.dtype == np.float32 and abs(a.mean()) < 0.02 and abs(a.std() - 2.0) < 0.02
+    assert np.array_equal(a, synth.normal(1, 0, (1000, 100), 2.0))
+    assert not np.array_equal(a, synth.normal(1, 1, (1000, 100), 2.0))
+    u = synth.uniform(1, 2, (100000,), -1 / 128, 1 / 128)
+    assert u.min() > -1 / 128 and u.max() < 1 / 128 and abs(u.var() * 3 * 128 * 128 - 1) < 0.02
+    i = synth.small_int(1, 3, (10000,), -3, 3)
+    assert set(np.unique(i)) == set(range(-3, 4))
