@@ -1,0 +1,208 @@
+"""ctypes binding of include/tofu.h: same names, argument marshalling only.
+
+The library is loaded from the in-tree build (paper_1807_08887_amd/libtofu.so).  If it has not
+been built this module builds it once with hipcc; if that is impossible it raises -- there is no
+CPU fallback for any entry point.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+TOFU_MAX_DIMS = 6
+OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD = 0, 1, 2
+MM_DIM_M, MM_DIM_N, MM_DIM_K = 0, 1, 2
+CONV_DIM_N, CONV_DIM_CO, CONV_DIM_H, CONV_DIM_W, CONV_DIM_CI = 0, 1, 2, 3, 4
+WGRAD_DIM_CO, WGRAD_DIM_CI, WGRAD_DIM_N = 0, 1, 2
+
+_i64x = ctypes.c_int64 * TOFU_MAX_DIMS
+
+
+class Region(ctypes.Structure):
+    _fields_ = [("ndim", ctypes.c_int32), ("lo", _i64x), ("hi", _i64x)]
+
+    def box(self):
+        return [(int(self.lo[d]), int(self.hi[d])) for d in range(self.ndim)]
+
+    @staticmethod
+    def from_box(box) -> "Region":
+        r = Region()
+        r.ndim = len(box)
+        for d, (lo, hi) in enumerate(box):
+            r.lo[d], r.hi[d] = lo, hi
+        return r
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("extent", Region), ("stride", _i64x)]
+
+
+class Split(ctypes.Structure):
+    _fields_ = [("dim", ctypes.c_int32), ("k", ctypes.c_int32), ("shard", ctypes.c_int32)]
+
+
+class OpDesc(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("batch", ctypes.c_int64), ("c_in", ctypes.c_int64), ("c_out", ctypes.c_int64), ("H", ctypes.c_int64),
+                ("W", ctypes.c_int64), ("KH", ctypes.c_int64), ("KW", ctypes.c_int64), ("stride", ctypes.c_int64),
+                ("pad", ctypes.c_int64)]
+
+
+class TofuError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"tofu status {status}: {message}")
+        self.status = status
+
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libtofu.so")
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libtofu.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    P = ctypes.POINTER
+    lib.tofu_last_error.restype = ctypes.c_char_p
+    lib.tofu_last_error.argtypes = []
+    lib.tofu_shard_range.argtypes = [i64, i32, i32, P(i64), P(i64)]
+    lib.tofu_op_regions.argtypes = [P(OpDesc), P(Split), i32, P(Region), P(Region), P(i64), P(i64), P(i32)]
+    lib.tofu_workspace_bytes.restype = sz
+    lib.tofu_workspace_bytes.argtypes = [P(OpDesc), P(Split), i32]
+    lib.tofu_region_fetch.argtypes = [P(Tensor), P(Tensor), i32, vp]
+    for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad"):
+        getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
+    lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
+    for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load().tofu_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise TofuError(status, last_error())
+
+
+def _splits(splits: Sequence) -> tuple:
+    arr = (Split * max(1, len(splits)))()
+    for i, s in enumerate(splits):
+        arr[i].dim, arr[i].k, arr[i].shard = (s.dim, s.k, s.shard) if isinstance(s, Split) else s
+    return arr, len(splits)
+
+
+def matmul_desc(M: int, N: int, K: int) -> OpDesc:
+    d = OpDesc()
+    d.kind, d.M, d.N, d.K = OP_MATMUL, M, N, K
+    return d
+
+
+def conv2d_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1, kind=OP_CONV2D) -> OpDesc:
+    d = OpDesc()
+    d.kind = kind
+    d.batch, d.c_in, d.c_out, d.H, d.W, d.KH, d.KW, d.stride, d.pad = batch, c_in, c_out, H, W, KH, KW, stride, pad
+    return d
+
+
+def wgrad_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1) -> OpDesc:
+    return conv2d_desc(batch, c_in, c_out, H, W, KH, KW, stride, pad, kind=OP_CONV2D_WGRAD)
+
+
+def tensor(t, lo: Optional[Sequence[int]] = None) -> Tensor:
+    """Descriptor of a CUDA float32 torch tensor holding the global box [lo, lo + t.shape)."""
+    import torch
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda:
+        raise TypeError("tofu tensors must be float32 torch tensors in device memory")
+    lo = list(lo) if lo is not None else [0] * t.dim()
+    if len(lo) != t.dim() or t.dim() > TOFU_MAX_DIMS:
+        raise ValueError("lo must give one coordinate per tensor dimension (at most 6)")
+    d = Tensor()
+    d.data = t.data_ptr()
+    d.extent.ndim = t.dim()
+    for i in range(t.dim()):
+        d.extent.lo[i] = lo[i]
+        d.extent.hi[i] = lo[i] + t.shape[i]
+        d.stride[i] = t.stride(i)
+    return d
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def shard_range(extent: int, k: int, shard: int):
+    lo, hi = ctypes.c_int64(), ctypes.c_int64()
+    _check(load().tofu_shard_range(extent, k, shard, ctypes.byref(lo), ctypes.byref(hi)))
+    return lo.value, hi.value
+
+
+def op_regions(op: OpDesc, splits: Sequence):
+    """-> dict(out_box, in_boxes, pad_lo, pad_hi, is_partial) with boxes as [(lo, hi), ...]."""
+    arr, n = _splits(splits)
+    out, ins = Region(), (Region * 2)()
+    plo, phi, part = (ctypes.c_int64 * 2)(), (ctypes.c_int64 * 2)(), ctypes.c_int32()
+    _check(load().tofu_op_regions(ctypes.byref(op), arr, n, ctypes.byref(out), ins, plo, phi, ctypes.byref(part)))
+    return dict(out_box=out.box(), in_boxes=[ins[0].box(), ins[1].box()], pad_lo=list(plo), pad_hi=list(phi),
+                is_partial=bool(part.value))
+
+
+def workspace_bytes(op: OpDesc, splits: Sequence) -> int:
+    arr, n = _splits(splits)
+    return int(load().tofu_workspace_bytes(ctypes.byref(op), arr, n))
+
+
+def region_fetch(dst: Tensor, srcs: Sequence[Tensor], stream=None) -> None:
+    arr = (Tensor * max(1, len(srcs)))(*srcs)
+    _check(load().tofu_region_fetch(ctypes.byref(dst), arr, len(srcs), _stream(stream)))
+
+
+def _shard(fn, op, splits, a, b, c, workspace, stream):
+    arr, n = _splits(splits)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    _check(fn(ctypes.byref(op), arr, n, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def shard_matmul(op, splits, A: Tensor, B: Tensor, C: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_matmul, op, splits, A, B, C, workspace, stream)
+
+
+def shard_conv2d(op, splits, x: Tensor, w: Tensor, y: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d, op, splits, x, w, y, workspace, stream)
+
+
+def shard_conv2d_wgrad(op, splits, x: Tensor, dy: Tensor, dw: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d_wgrad, op, splits, x, dy, dw, workspace, stream)
+
+
+def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, stream=None) -> None:
+    """dst, partials: CUDA float32 torch tensors (contiguous) or raw device addresses."""
+    def addr(t):
+        if isinstance(t, int):
+            return t
+        if not t.is_cuda or t.dtype.itemsize != 4 or not t.is_contiguous():
+            raise TypeError("partition_reduce needs contiguous float32 device tensors")
+        return t.data_ptr()
+    if count is None:
+        count = dst.numel()
+    ptrs = (ctypes.c_void_p * max(1, len(partials)))(*[addr(p) for p in partials])
+    _check(load().tofu_partition_reduce(ctypes.c_void_p(addr(dst)), ptrs, len(partials), count, _stream(stream)))

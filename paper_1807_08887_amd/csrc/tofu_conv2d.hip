@@ -1,0 +1,297 @@
+// Shard of a 3x3, stride-1 convolution forward pass (arXiv 1807.08887: Fig. 1 loop nest in two
+// spatial dimensions; Sec. 4.2 Case-1 for N / C_out / H / W splits -- H and W splits read a
+// halo-widened input region -- and Case-2 for a C_in split, which yields a partial output).
+//   y[n,co,h,w] = sum_{ci,kh,kw} x[n,ci,h+kh-pad,w+kw-pad] * wt[co,ci,kh,kw],  x = 0 outside the
+// GLOBAL tensor.  A shard whose box ends at an interior cut gets real halo rows there instead of
+// zeros, so the zero border is asymmetric ("residual padding") and is applied per side.
+//
+// Kernel: implicit GEMM  [co] x [(n,h,w)] over K = (ci, kh, kw) on fp32 MFMA 32x32x2 tiles.
+//   * A workgroup owns BM output channels x BN consecutive output positions (positions are
+//     numbered n-major over the shard's output box, so lanes stay dense for 14x14 or 7x14 boxes).
+//   * Per step of CK input channels it stages in LDS, through registers and double-buffered,
+//       - the weights wt[co, ci0..ci0+CK, :, :] transposed to k-major  Ws[(ci,tap)][co], and
+//       - for every input channel the input rows the tile's positions can touch, each row
+//         widened by the filter window and with the zero border materialised, so that the nine
+//         taps are nine shifted reads of the SAME staged rows (no im2col copy, 9x reuse in LDS).
+//     Rows are kept in "virtual row" order: image i, padded row u -> i*(BH+2)+u; a tile stages
+//     the virtual rows [T_a, T_b] its positions need.
+//   * One MFMA contracts the same tap of two adjacent input channels (lanes 0-31: ci, lanes
+//     32-63: ci+1); the B operand of a lane is one LDS read at (its position's row/col) + tap.
+#include <hip/hip_runtime.h>
+
+#include "tofu_internal.h"
+#include "tofu_mfma.h"
+
+namespace tofu {
+
+struct ConvArgs {
+  const float* x;   // element at the low corner of the (clipped) input box
+  const float* w;   // element (co_lo, ci_lo, 0, 0)
+  float* y;         // element at the low corner of the output box
+  int64_t xs[4], ws[4], ys[4];   // element strides (n, c, h, w) / (co, ci, kh, kw) / (n, co, h, w)
+  int NB, CO, CI;   // images, output channels and input channels of the shard
+  int BH, BW;       // output box rows / columns
+  int IH, IW;       // rows / columns of the clipped input box
+  int plh, plw;     // zero rows / columns in front of the input box (residual padding, low side)
+  int P;            // NB * BH * BW output positions
+  int tiles_m, tiles_n;
+  int LDW;          // floats per staged row  (BW + 2)
+  int PL;           // floats per staged channel plane
+  int E;            // staged floats per channel actually used (<= PL)
+  int w_fast;       // 1: weights dense over (ci,kh,kw) and 16-byte aligned -> vector loads
+};
+
+template <int BM, int BN, int CK, int WM, int WN, int XJ>
+struct ConvCfg {
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+  static constexpr int KK = CK * 9;            // GEMM-K per step
+  static constexpr int LDM = BM + 4;           // Ws[kk][m]
+  static constexpr int WV = (BM * KK / 4 + kThreads - 1) / kThreads;   // weight vectors per thread per step
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && CK % 4 == 0, "bad tile");
+};
+
+template <int BM, int BN, int CK, int WM, int WN, int XJ>
+__global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) {
+  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
+  constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
+  extern __shared__ float lds[];
+  float* Ws = lds;                           // [2][KK][LDM]
+  float* Xs = lds + 2 * KK * LDM;            // [2][CK][PL]
+  const int PL = p.PL, LDW = p.LDW;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // Compute units are handed workgroups round-robin over the 8 XCDs; renumber so that
+  // consecutive logical tiles (which share staged input rows) land on the same XCD's L2.
+  const int total = p.tiles_m * p.tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (lid >= total) return;                   // grid is padded to a multiple of 8
+  const int tile_n = lid / p.tiles_m, tile_m = lid % p.tiles_m;
+  const int m0 = tile_m * BM;
+  const int p_begin = tile_n * BN;
+  const int p_end = min(p.P, p_begin + BN);
+  const int img_rows = p.BH + 2;              // padded rows per image in virtual-row order
+  const int plane = p.BH * p.BW;
+
+  // virtual rows staged by this tile
+  const int ra = p_begin / p.BW, rb = (p_end - 1) / p.BW;
+  const int T_a = (ra / p.BH) * img_rows + ra % p.BH;
+  const int T_b = (rb / p.BH) * img_rows + rb % p.BH + 2;
+  const int nslots = T_b - T_a + 1;
+
+  // ---- per-thread staging lists (fixed for the whole K loop) ----
+  int x_goff[XJ], x_loff[XJ];
+  const int E = nslots * LDW;
+#pragma unroll
+  for (int j = 0; j < XJ; ++j) {
+    int idx = tid + j * NT;
+    int ci_l = idx / p.E, rem = idx - ci_l * p.E;   // p.E = host-side upper bound of E: fixed divisor for all tiles
+    int s = rem / LDW, c = rem - s * LDW;
+    int V = T_a + s;
+    int img = V / img_rows, u = V - img * img_rows;
+    int ih = u - p.plh, iw = c - p.plw;
+    bool live = ci_l < CK && rem < E;               // this thread writes LDS for that element
+    bool valid = live && img < p.NB && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
+    x_loff[j] = live ? ci_l * PL + rem : -1;
+    x_goff[j] = valid ? (int)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : -1;
+  }
+
+  float rx[XJ];
+  v4f32 rw[WV];
+  auto load_global = [&](int step) {
+    const int ci0 = step * CK;
+    const float* xb = p.x + (int64_t)ci0 * p.xs[1];
+    const bool ci_tail = ci0 + CK > p.CI;      // only the last step can run past the shard's channels
+#pragma unroll
+    for (int j = 0; j < XJ; ++j) {
+      int g = x_goff[j];
+      bool ok = g >= 0 && (!ci_tail || ci0 + (tid + j * NT) / p.E < p.CI);
+      rx[j] = ok ? xb[g] : 0.f;
+    }
+    if (p.w_fast && m0 + BM <= p.CO && ci0 + CK <= p.CI) {
+#pragma unroll
+      for (int i = 0; i < WV; ++i) {
+        int idx = tid + i * NT;
+        if (idx < BM * KK / 4) {
+          int row = idx / (KK / 4), q = idx - row * (KK / 4);
+          rw[i] = *reinterpret_cast<const v4f32*>(p.w + (int64_t)(m0 + row) * p.ws[0] + (int64_t)ci0 * 9 + 4 * q);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < WV; ++i) {
+        int idx = tid + i * NT;
+        int row = idx / (KK / 4), q = idx - row * (KK / 4);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          int kk = 4 * q + jj, ci_l = kk / 9, tap = kk - ci_l * 9, kh = tap / 3, kw = tap - kh * 3;
+          bool ok = idx < BM * KK / 4 && m0 + row < p.CO && ci0 + ci_l < p.CI;
+          rw[i][jj] = ok ? p.w[(int64_t)(m0 + row) * p.ws[0] + (int64_t)(ci0 + ci_l) * p.ws[1] + kh * p.ws[2] + kw * p.ws[3]] : 0.f;
+        }
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    float* xs = Xs + buf * CK * PL;
+    float* wsm = Ws + buf * KK * LDM;
+#pragma unroll
+    for (int j = 0; j < XJ; ++j)
+      if (x_loff[j] >= 0) xs[x_loff[j]] = rx[j];
+#pragma unroll
+    for (int i = 0; i < WV; ++i) {
+      int idx = tid + i * NT;
+      if (idx < BM * KK / 4) {
+        int row = idx / (KK / 4), q = idx - row * (KK / 4);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) wsm[(4 * q + jj) * LDM + row] = rw[i][jj];
+      }
+    }
+  };
+
+  // ---- per-lane position of each N block: LDS offset of tap (0,0) and output offset ----
+  int pos_l[FN];
+  int64_t y_off[FN];
+  bool pos_ok[FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    int pp = p_begin + wn * Cfg::TN + j * 32 + l32;
+    pos_ok[j] = pp < p_end;
+    if (!pos_ok[j]) pp = p_end - 1;          // keep the address inside the staged rows
+    int img = pp / plane, q = pp - img * plane, oh = q / p.BW, ow = q - oh * p.BW;
+    pos_l[j] = (img * img_rows + oh - T_a) * LDW + ow + half * PL;
+    y_off[j] = (int64_t)img * p.ys[0] + (int64_t)oh * p.ys[2] + (int64_t)ow * p.ys[3];
+  }
+
+  acc16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
+
+  const int steps = (p.CI + CK - 1) / CK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int t = 0; t < steps; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < steps) load_global(t + 1);
+    const float* wsm = Ws + buf * KK * LDM + wm * Cfg::TM + l32 + half * 9 * LDM;
+    const float* xs = Xs + buf * CK * PL;
+#pragma unroll
+    for (int cp = 0; cp < CK / 2; ++cp) {
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          const int tap = kh * 3 + kw;
+          float a[FM], b[FN];
+#pragma unroll
+          for (int i = 0; i < FM; ++i) a[i] = wsm[(cp * 18 + tap) * LDM + i * 32];
+#pragma unroll
+          for (int j = 0; j < FN; ++j) b[j] = xs[cp * 2 * PL + pos_l[j] + kh * LDW + kw];
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
+        }
+    }
+    if (t + 1 < steps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      if (!pos_ok[j]) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
+        if (co < p.CO) p.y[y_off[j] + (int64_t)co * p.ys[1]] = acc[i][j][v];
+      }
+    }
+}
+
+constexpr int cBM = 64, cBN = 128, cCK = 8, cWM = 2, cWN = 2, cXJ = 10;
+constexpr size_t kLdsLimit = 160 * 1024;
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  using namespace tofu;
+  (void)workspace; (void)workspace_bytes;
+  if (!op || op->kind != TOFU_OP_CONV2D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d");
+  tofu_region_t out_box, in_boxes[2];
+  int64_t pad_lo[2], pad_hi[2];
+  int32_t partial = 0;
+  int rc = tofu_op_regions(op, splits, nsplits, &out_box, in_boxes, pad_lo, pad_hi, &partial);
+  if (rc) return rc;
+  if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1)
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d kernels implement KH = KW = 3, stride 1, pad 0 or 1");
+  if ((rc = check_tensor("x", x, 4, &in_boxes[0]))) return rc;
+  if ((rc = check_tensor("w", w, 4, &in_boxes[1]))) return rc;
+  if ((rc = check_tensor("y", y, 4, &out_box))) return rc;
+  if (volume(&out_box) == 0) return TOFU_OK;
+
+  int64_t xs[4], ws[4], ys[4];
+  effective_strides(x, xs);
+  effective_strides(w, ws);
+  effective_strides(y, ys);
+  ConvArgs p;
+  p.x = element_ptr(x, xs, in_boxes[0].lo);
+  p.w = element_ptr(w, ws, in_boxes[1].lo);
+  p.y = const_cast<float*>(element_ptr(y, ys, out_box.lo));
+  for (int d = 0; d < 4; ++d) { p.xs[d] = xs[d]; p.ws[d] = ws[d]; p.ys[d] = ys[d]; }
+  const int64_t NB = out_box.hi[0] - out_box.lo[0], CO = out_box.hi[1] - out_box.lo[1];
+  const int64_t BH = out_box.hi[2] - out_box.lo[2], BW = out_box.hi[3] - out_box.lo[3];
+  const int64_t CI = in_boxes[0].hi[1] - in_boxes[0].lo[1];
+  const int64_t P = NB * BH * BW;
+  if (P >= (1 << 30) || CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
+  // per-thread input offsets are 32-bit: the input box must span fewer than 2^31 elements
+  int64_t span = 1;
+  for (int d = 0; d < 4; ++d) span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * (xs[d] < 0 ? -xs[d] : xs[d]);
+  if (span >= ((int64_t)1 << 31)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d input region spans 2^31 or more elements");
+  p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
+  p.IH = (int)(in_boxes[0].hi[2] - in_boxes[0].lo[2]);
+  p.IW = (int)(in_boxes[0].hi[3] - in_boxes[0].lo[3]);
+  p.plh = (int)pad_lo[0]; p.plw = (int)pad_lo[1];
+  p.tiles_m = (int)((CO + cBM - 1) / cBM);
+  p.tiles_n = (int)((P + cBN - 1) / cBN);
+  p.LDW = (int)BW + 2;
+  // most virtual rows any tile can touch: cBN consecutive positions
+  int64_t max_slots = 0;
+  for (int64_t t = 0; t < p.tiles_n; ++t) {
+    int64_t pb = t * cBN, pe = pb + cBN < P ? pb + cBN : P;
+    int64_t ra = pb / BW, rb = (pe - 1) / BW;
+    int64_t slots = ((rb / BH) * (BH + 2) + rb % BH + 2) - ((ra / BH) * (BH + 2) + ra % BH) + 1;
+    if (slots > max_slots) max_slots = slots;
+  }
+  p.E = (int)(max_slots * p.LDW);
+  p.PL = (p.E + 63) / 64 * 64 + 32;   // odd multiple of 32 floats: the two half-waves read different banks
+  using Cfg = ConvCfg<cBM, cBN, cCK, cWM, cWN, cXJ>;
+  if ((int64_t)cCK * p.E > (int64_t)cXJ * Cfg::kThreads)
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)p.E);
+  const size_t lds_bytes = sizeof(float) * 2 * ((size_t)Cfg::KK * Cfg::LDM + (size_t)cCK * p.PL);
+  if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
+  p.w_fast = ws[3] == 1 && ws[2] == 3 && ws[1] == 9 && ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
+
+  auto kern = conv2d_kernel<cBM, cBN, cCK, cWM, cWN, cXJ>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  const int total = p.tiles_m * p.tiles_n;
+  const int grid = (total + 7) / 8 * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), lds_bytes, static_cast<hipStream_t>(hip_stream), p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d launch failed: %s", hipGetErrorString(e));
+  return TOFU_OK;
+}

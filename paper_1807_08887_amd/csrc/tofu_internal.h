@@ -1,0 +1,56 @@
+// Internal declarations shared by the translation units of libtofu (not part of the C ABI).
+#ifndef TOFU_INTERNAL_H_
+#define TOFU_INTERNAL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tofu.h"
+
+namespace tofu {
+
+// Record a thread-local error message and return `code` (printf-style).
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Number of iteration dimensions of an operator kind (3 / 5 / 3), or 0 for an unknown kind.
+int iter_ndim(int32_t kind);
+
+// Index range of every iteration dimension left to one worker after applying the plan.
+// Order of the dimensions follows the TOFU_*_DIM_* enumerators.
+struct IterRanges {
+  int64_t lo[5];
+  int64_t hi[5];
+};
+int apply_splits(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, IterRanges* r,
+                 int32_t* is_partial);
+
+// Checks of the operator description itself (positive sizes, output extents >= 1).
+int check_op(const tofu_op_desc_t* op);
+int64_t conv_out_extent(int64_t size, int64_t ksize, int64_t stride, int64_t pad);
+
+// Element strides of a tensor: the given ones, or dense row-major over the extent when all are zero.
+void effective_strides(const tofu_tensor_t* t, int64_t* stride);
+
+// True when `outer` contains `inner` in every dimension (an empty inner box is contained in anything).
+bool contains(const tofu_region_t* outer, const tofu_region_t* inner);
+int64_t volume(const tofu_region_t* r);
+
+// Validate a tensor argument: non-null, ndim as expected, lo <= hi, and extent contains `need`.
+int check_tensor(const char* name, const tofu_tensor_t* t, int32_t ndim, const tofu_region_t* need);
+
+// Pointer to the element at global coordinate `coord` (which must lie inside the extent).
+const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const int64_t* coord);
+
+// ---- launch plans (shared by tofu_workspace_bytes and the entry points) ----
+// Number of K slices the matmul kernel cuts its own reduction into for an m x n x k shard.
+int matmul_split_k(int64_t m, int64_t n, int64_t k);
+// Number of batch slices the weight-gradient kernel cuts its reduction into.
+int wgrad_split_n(int64_t co, int64_t ci, int64_t nb, int64_t rows);
+
+// Enqueue dst[i] = sum_j parts[j][i] (fixed order j = 0..k-1); used by the public reduce and
+// by the kernels that split their own reduction.  Pointers are device pointers.
+int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, void* stream);
+
+}  // namespace tofu
+
+#endif  // TOFU_INTERNAL_H_

@@ -1,0 +1,263 @@
+// Shard of a matrix multiplication (arXiv 1807.08887 Sec. 3.1: each worker runs the same
+// operator on smaller inputs; Sec. 4.2: the smaller inputs are the regions of A and B the
+// worker's index ranges touch).  C[m,n] = sum_{k in shard} A[m,k] * B[k,n] for (m,n) in the
+// shard's output box.
+//
+// Kernel: a BM x BN output tile per workgroup, K walked in steps of BK.  Each step stages
+// A[BM x BK] (transposed to k-major) and B[BK x BN] in LDS through registers, double-buffered so
+// that the global loads of step t+1 are in flight while the matrix cores work on step t; one
+// barrier per step.  WM x WN wavefronts each own a (BM/WM) x (BN/WN) block of 32x32 MFMA tiles
+// and read their operands from LDS with conflict-free 32-lane rows.  Tall-skinny shards (the
+// M = 128 LSTM gate GEMM) do not have enough output tiles to fill 256 CUs, so the kernel cuts
+// its own K range into slices -- a partition-n-reduce inside the worker -- writes the slices to
+// the caller's workspace and sums them in fixed order with the reduce kernel.
+#include <hip/hip_runtime.h>
+
+#include "tofu_internal.h"
+#include "tofu_mfma.h"
+
+namespace tofu {
+
+struct MatmulArgs {
+  const float* A;   // element (m_lo, k_lo)
+  const float* B;   // element (k_lo, n_lo)
+  float* C;         // element (m_lo, n_lo) of the output, or slice 0 of the workspace
+  int64_t a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;   // row / column element strides
+  int64_t c_slice;  // element stride between K slices of the workspace
+  int m, n, k;      // shard extents
+  int k_slice;      // K elements per slice (multiple of BK); slices = gridDim.y
+  int tiles_n;      // number of tiles along n
+  int fast;         // 1: unit column strides and 16-byte aligned rows -> vector loads
+};
+
+template <int BM, int BN, int BK, int WM, int WN>
+struct MatmulCfg {
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int TM = BM / WM, TN = BN / WN;   // wavefront tile
+  static constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wavefront
+  static constexpr int LDA = BM + 4;                 // k-major A tile: As[k][m]
+  static constexpr int LDB = BN + 4;                 // Bs[k][n]
+  static constexpr int kLdsFloats = 2 * BK * (LDA + LDB);
+  static constexpr int AV = BM * BK / 4 / kThreads;  // 16-byte vectors of A per thread per step
+  static constexpr int BV = BK * BN / 4 / kThreads;
+  static_assert(TM % 32 == 0 && TN % 32 == 0, "wavefront tile must be made of 32x32 blocks");
+  static_assert(AV >= 1 && BV >= 1 && BM * BK / 4 % kThreads == 0 && BK * BN / 4 % kThreads == 0, "staging must divide evenly");
+  static_assert(BK % 4 == 0, "BK must hold whole vectors");
+};
+
+template <int BM, int BN, int BK, int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p) {
+  using Cfg = MatmulCfg<BM, BN, BK, WM, WN>;
+  constexpr int NT = Cfg::kThreads, LDA = Cfg::LDA, LDB = Cfg::LDB, FM = Cfg::FM, FN = Cfg::FN;
+  __shared__ float lds[Cfg::kLdsFloats];
+  float* As = lds;                      // [2][BK][LDA]
+  float* Bs = lds + 2 * BK * LDA;       // [2][BK][LDB]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN;
+  const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int k_begin = blockIdx.y * p.k_slice;
+  const int k_end = min(p.k, k_begin + p.k_slice);
+  const int steps = (k_end - k_begin + BK - 1) / BK;
+  const bool interior = p.fast && m0 + BM <= p.m && n0 + BN <= p.n;
+
+  v4f32 ra[Cfg::AV], rb[Cfg::BV];
+
+  auto load_global = [&](int step) {
+    const int k0 = k_begin + step * BK;
+    const bool full_k = k0 + BK <= k_end;
+    if (interior && full_k) {
+#pragma unroll
+      for (int i = 0; i < Cfg::AV; ++i) {
+        int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+        ra[i] = *reinterpret_cast<const v4f32*>(p.A + (int64_t)(m0 + row) * p.a_rs + k0 + 4 * q);
+      }
+#pragma unroll
+      for (int i = 0; i < Cfg::BV; ++i) {
+        int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+        rb[i] = *reinterpret_cast<const v4f32*>(p.B + (int64_t)(k0 + row) * p.b_rs + n0 + 4 * c);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < Cfg::AV; ++i) {
+        int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int mm = m0 + row, kk = k0 + 4 * q + j;
+          ra[i][j] = (mm < p.m && kk < k_end) ? p.A[(int64_t)mm * p.a_rs + (int64_t)kk * p.a_cs] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < Cfg::BV; ++i) {
+        int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int kk = k0 + row, nn = n0 + 4 * c + j;
+          rb[i][j] = (kk < k_end && nn < p.n) ? p.B[(int64_t)kk * p.b_rs + (int64_t)nn * p.b_cs] : 0.f;
+        }
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    float* as = As + buf * BK * LDA;
+    float* bs = Bs + buf * BK * LDB;
+#pragma unroll
+    for (int i = 0; i < Cfg::AV; ++i) {
+      int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) as[(4 * q + j) * LDA + row] = ra[i][j];
+    }
+#pragma unroll
+    for (int i = 0; i < Cfg::BV; ++i) {
+      int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+      *reinterpret_cast<v4f32*>(bs + row * LDB + 4 * c) = rb[i];
+    }
+  };
+
+  acc16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
+
+  if (steps > 0) {
+    load_global(0);
+    store_lds(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < steps; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < steps) load_global(t + 1);
+    const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32;
+    const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a[FM], b[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) a[i] = as[(kk + half) * LDA + i * 32];
+#pragma unroll
+      for (int j = 0; j < FN; ++j) b[j] = bs[(kk + half) * LDB + j * 32];
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
+    }
+    if (t + 1 < steps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  float* C = p.C + (int64_t)blockIdx.y * p.c_slice;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int col = n0 + wn * Cfg::TN + j * 32 + l32;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
+        if (row < p.m && col < p.n) C[(int64_t)row * p.c_rs + (int64_t)col * p.c_cs] = acc[i][j][v];
+      }
+    }
+}
+
+// Sum of the K slices held in the workspace ([slices][m][n], dense) into the output box, in
+// fixed order.  The output may be a strided block of a larger tensor.
+__global__ void __launch_bounds__(256) slice_sum_kernel(float* __restrict__ C, int64_t c_rs, int64_t c_cs, const float* __restrict__ ws,
+                                                         int slices, int m, int n, int vec) {
+  const int64_t per_row = n / vec, items = (int64_t)m * per_row, slice = (int64_t)m * n;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = i / per_row, col = (i - row * per_row) * vec;
+    const float* src = ws + row * n + col;
+    if (vec == 4) {
+      v4f32 acc = *reinterpret_cast<const v4f32*>(src);
+      for (int j = 1; j < slices; ++j) acc += *reinterpret_cast<const v4f32*>(src + j * slice);
+      *reinterpret_cast<v4f32*>(C + row * c_rs + col) = acc;
+    } else {
+      float acc = src[0];
+      for (int j = 1; j < slices; ++j) acc += src[j * slice];
+      C[row * c_rs + col * c_cs] = acc;
+    }
+  }
+}
+
+// ---- launch plan -------------------------------------------------------------------------
+constexpr int kBM = 128, kBN = 64, kBK = 16, kWM = 2, kWN = 2;
+constexpr int kTargetGroups = 512;   // two resident workgroups on each of the 256 compute units
+constexpr int kMaxSplit = 16;        // the reduce kernel sums at most 16 inputs
+
+int matmul_split_k(int64_t m, int64_t n, int64_t k) {
+  int64_t tiles = ((m + kBM - 1) / kBM) * ((n + kBN - 1) / kBN);
+  if (tiles >= kTargetGroups / 2 || k < 1024) return 1;
+  int64_t s = kTargetGroups / tiles;
+  if (s > kMaxSplit) s = kMaxSplit;
+  while (s > 1 && k / s < 512) --s;   // keep every slice long enough to amortise its prologue
+  return (int)s;
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  using namespace tofu;
+  if (!op || op->kind != TOFU_OP_MATMUL) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a matmul");
+  tofu_region_t out_box, in_boxes[2];
+  int32_t partial = 0;
+  int rc = tofu_op_regions(op, splits, nsplits, &out_box, in_boxes, nullptr, nullptr, &partial);
+  if (rc) return rc;
+  if ((rc = check_tensor("A", A, 2, &in_boxes[0]))) return rc;
+  if ((rc = check_tensor("B", B, 2, &in_boxes[1]))) return rc;
+  if ((rc = check_tensor("C", C, 2, &out_box))) return rc;
+  const int64_t m = out_box.hi[0] - out_box.lo[0], n = out_box.hi[1] - out_box.lo[1];
+  const int64_t k = in_boxes[0].hi[1] - in_boxes[0].lo[1];
+  if (m == 0 || n == 0) return TOFU_OK;
+  if (m >= (1 << 30) || n >= (1 << 30) || k >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "matmul shard extent exceeds 2^30");
+
+  int64_t as[2], bs[2], cs[2];
+  effective_strides(A, as);
+  effective_strides(B, bs);
+  effective_strides(C, cs);
+  MatmulArgs p;
+  p.A = element_ptr(A, as, in_boxes[0].lo);
+  p.B = element_ptr(B, bs, in_boxes[1].lo);
+  float* c_out = const_cast<float*>(element_ptr(C, cs, out_box.lo));
+  p.a_rs = as[0]; p.a_cs = as[1]; p.b_rs = bs[0]; p.b_cs = bs[1];
+  p.m = (int)m; p.n = (int)n; p.k = (int)k;
+  p.tiles_n = (int)((n + kBN - 1) / kBN);
+  const int tiles_m = (int)((m + kBM - 1) / kBM);
+  p.fast = as[1] == 1 && bs[1] == 1 && as[0] % 4 == 0 && bs[0] % 4 == 0 &&
+           (reinterpret_cast<uintptr_t>(p.A) & 15) == 0 && (reinterpret_cast<uintptr_t>(p.B) & 15) == 0;
+
+  const int split = matmul_split_k(m, n, k);
+  if (split > 1) {
+    const size_t need = (size_t)split * (size_t)m * (size_t)n * sizeof(float);
+    if (!workspace || workspace_bytes < need)
+      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "matmul shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    p.C = static_cast<float*>(workspace);
+    p.c_rs = n; p.c_cs = 1; p.c_slice = m * n;
+    p.k_slice = (int)(((k + split - 1) / split + kBK - 1) / kBK * kBK);
+  } else {
+    p.C = c_out;
+    p.c_rs = cs[0]; p.c_cs = cs[1]; p.c_slice = 0;
+    p.k_slice = (int)((k + kBK - 1) / kBK * kBK);
+  }
+  const int slices = (int)((k + p.k_slice - 1) / p.k_slice);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL((matmul_kernel<kBM, kBN, kBK, kWM, kWN>), dim3(tiles_m * p.tiles_n, slices > 0 ? slices : 1), dim3(64 * kWM * kWN), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "matmul launch failed: %s", hipGetErrorString(e));
+  if (split > 1) {
+    // sum the K slices in fixed order j = 0..slices-1 into the (possibly strided) output box
+    const int vec = (n % 4 == 0 && cs[1] == 1 && cs[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(c_out) & 15) == 0) ? 4 : 1;
+    const int64_t items = m * (n / vec);
+    const int blocks = (int)((items + 255) / 256 < 4096 ? (items + 255) / 256 : 4096);
+    hipLaunchKernelGGL(slice_sum_kernel, dim3(blocks), dim3(256), 0, s, c_out, cs[0], cs[1], static_cast<const float*>(workspace),
+                       slices, (int)m, (int)n, vec);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "matmul slice sum launch failed: %s", hipGetErrorString(e));
+  }
+  return TOFU_OK;
+}

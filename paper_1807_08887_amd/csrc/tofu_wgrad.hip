@@ -1,0 +1,279 @@
+// Shard of the weight gradient of a 3x3, stride-1 convolution (arXiv 1807.08887 Sec. 4.2).
+//   dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] * x[n,ci,h+kh-pad,w+kw-pad],  x = 0 outside the tensor.
+// C_out and C_in are output dimensions of this operator (Case-1: shards write disjoint blocks of
+// dw); the batch index is a reduction index (Case-2: a batch shard produces a full-size PARTIAL
+// dw that tofu_partition_reduce sums with the other workers' partials).
+//
+// Kernel: GEMM  [co] x [(ci,tap)] over K = (n,h,w) on fp32 MFMA 32x32x2 tiles.
+//   * A workgroup owns BM output channels x 32 input channels x all 9 taps; wavefront w owns 32 of
+//     the output channels and nine 32x32 accumulator blocks, one per tap (lane = input channel).
+//   * One step of the K loop is one output row (n,h): dy[n, co tile, h, :] is staged k-major
+//     (Ds[w][co]) and x[n, ci tile, h-pad .. h-pad+2, :] is staged with its zero border, so the
+//     nine taps are nine shifted reads of the same three staged rows.  One MFMA contracts two
+//     adjacent output columns (lanes 0-31: w, lanes 32-63: w+1).
+//   * The batch range of the shard is cut into slices (grid.y) so that enough workgroups exist
+//     to balance 256 compute units; slices are written tap-major to the caller's workspace and
+//     summed in fixed order by a second kernel that also restores the [co][ci][kh][kw] layout.
+#include <hip/hip_runtime.h>
+
+#include "tofu_internal.h"
+#include "tofu_mfma.h"
+
+namespace tofu {
+
+struct WgradArgs {
+  const float* x;    // element at the low corner of the (clipped) input box
+  const float* dy;   // element (n_lo, co_lo, 0, 0)
+  float* out;        // dw element (co_lo, ci_lo, 0, 0), or the workspace when slices > 1
+  int64_t xs[4], ds[4], os[4];   // element strides: x (n,c,h,w), dy (n,co,h,w), out (co,ci,kh,kw)
+  int64_t slice_stride;          // floats between slices in the workspace
+  int NB, CO, CI;    // images, output channels, input channels of the shard
+  int HO, WO;        // output rows / columns
+  int IH, IW;        // rows / columns of the clipped input box
+  int plh, plw;      // zero rows / columns in front of the input box
+  int n_per_slice;   // images per slice
+  int tiles_m, tiles_n;
+  int CW;            // output columns per K step (<= 32, multiple of 4 unless WO itself is not)
+  int chunks;        // column chunks per output row
+  int to_workspace;  // 1: write [tap][co][ci] slices to the workspace
+  int fast;          // 1: rows of dy are contiguous and 16-byte aligned -> vector loads
+};
+
+// LDS geometry is fixed so that every staging index splits with compile-time divisors.
+constexpr int kKR = 32;              // dy positions per K step (a chunk of one output row)
+constexpr int kLDW = kKR + 2;        // staged x columns per row: chunk widened by the filter window
+constexpr int kPLX = 3 * kLDW + 1;   // staged floats per input channel; odd -> 32 channels hit 32 banks
+
+template <int BM, int BCI>
+__global__ void __launch_bounds__(64 * (BM / 32)) wgrad_kernel(const WgradArgs p) {
+  constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 4;
+  constexpr int D_ITEMS = BM * (kKR / 4), X_ITEMS = BCI * 3 * kLDW;
+  constexpr int DJ = (D_ITEMS + NT - 1) / NT, XJ = (X_ITEMS + NT - 1) / NT;
+  static_assert(BCI == 32, "one 32-lane block of input channels per workgroup");
+  __shared__ float Ds[2][kKR][LDD];        // dy chunk, k-major: Ds[column][co]
+  __shared__ float Xs[2][BCI * kPLX];      // x rows h-pad..h-pad+2 of the chunk, zero border included
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int total = p.tiles_m * p.tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;   // keep neighbouring tiles on one XCD
+  if (lid >= total) return;
+  const int tile_n = lid / p.tiles_m, tile_m = lid % p.tiles_m;
+  const int m0 = tile_m * BM, c0 = tile_n * BCI;
+  const int n_begin = blockIdx.y * p.n_per_slice;
+  const int n_end = min(p.NB, n_begin + p.n_per_slice);
+  const int steps = (n_end - n_begin) * p.HO * p.chunks;
+  const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
+
+  v4f32 rd[DJ];
+  float rx[XJ];
+  auto load_global = [&](int step) {
+    const int row_id = step / p.chunks, chunk = step - row_id * p.chunks;
+    const int n = n_begin + row_id / p.HO, oh = row_id - (row_id / p.HO) * p.HO;
+    const int cw0 = chunk * p.CW;
+    const float* db = p.dy + (int64_t)n * p.ds[0] + (int64_t)m0 * p.ds[1] + (int64_t)oh * p.ds[2] + (int64_t)cw0 * p.ds[3];
+    const float* xb = p.x + (int64_t)n * p.xs[0] + (int64_t)c0 * p.xs[1];
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+      const int idx = tid + j * NT, row = idx / (kKR / 4), q = idx % (kKR / 4);
+      const bool row_ok = idx < D_ITEMS && m0 + row < p.CO;
+      const int col = 4 * q;                   // first of four columns, relative to the chunk
+      if (p.fast && row_ok && col + 3 < p.CW && cw0 + col + 3 < p.WO) {
+        rd[j] = *reinterpret_cast<const v4f32*>(db + (int64_t)row * p.ds[1] + col);
+      } else {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const bool ok = row_ok && col + jj < p.CW && cw0 + col + jj < p.WO;
+          rd[j][jj] = ok ? db[(int64_t)row * p.ds[1] + (int64_t)(col + jj) * p.ds[3]] : 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < XJ; ++j) {
+      const int idx = tid + j * NT, ci_l = idx / (3 * kLDW), rem = idx % (3 * kLDW), r = rem / kLDW, c = rem % kLDW;
+      const int ih = oh + r - p.plh, iw = cw0 + c - p.plw;
+      const bool ok = idx < X_ITEMS && c0 + ci_l < p.CI && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
+      rx[j] = ok ? xb[(int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]] : 0.f;
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+      const int idx = tid + j * NT, row = idx / (kKR / 4), q = idx % (kKR / 4);
+      if (idx < D_ITEMS) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) Ds[buf][4 * q + jj][row] = rd[j][jj];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < XJ; ++j) {
+      const int idx = tid + j * NT, ci_l = idx / (3 * kLDW), rem = idx % (3 * kLDW);
+      if (idx < X_ITEMS) Xs[buf][ci_l * kPLX + rem] = rx[j];
+    }
+  };
+
+  acc16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = acc_zero();
+
+  if (steps > 0) {
+    load_global(0);
+    store_lds(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < steps; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < steps) load_global(t + 1);
+    const float* dsm = &Ds[buf][half][wave * 32 + l32];
+    const float* xsm = &Xs[buf][l32 * kPLX + half];
+    // operands of column pair kp+1 are fetched while the nine MFMAs of pair kp run
+    float a_next = dsm[0], b_next[9];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) b_next[tap] = xsm[(tap / 3) * kLDW + tap % 3];
+    for (int kp = 0; kp < KP; ++kp) {
+      const float a = a_next;
+      float b[9];
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) b[tap] = b_next[tap];
+      if (kp + 1 < KP) {
+        a_next = dsm[2 * (kp + 1) * LDD];
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) b_next[tap] = xsm[2 * (kp + 1) + (tap / 3) * kLDW + tap % 3];
+      }
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
+    }
+    if (t + 1 < steps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  const int ci = c0 + l32;
+  if (p.to_workspace) {
+    // [slice][tap][co][ci]: a lane row of 32 input channels is one contiguous 128-byte store
+    float* o = p.out + (int64_t)blockIdx.y * p.slice_stride;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = m0 + wave * 32 + acc_row(v, half);
+        if (co < p.CO && ci < p.CI) o[((int64_t)tap * p.CO + co) * p.CI + ci] = acc[tap][v];
+      }
+  } else {
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = m0 + wave * 32 + acc_row(v, half);
+        if (co < p.CO && ci < p.CI)
+          p.out[(int64_t)co * p.os[0] + (int64_t)ci * p.os[1] + (tap / 3) * p.os[2] + (tap % 3) * p.os[3]] = acc[tap][v];
+      }
+  }
+}
+
+// dw[co][ci][tap] = sum_j ws[j][tap][co][ci], j in fixed order.  One thread per (co, ci): its nine
+// reads per slice are coalesced across lanes (ci fastest); its nine writes cover 36 contiguous bytes.
+__global__ void __launch_bounds__(256) wgrad_slice_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
+                                                               const float* __restrict__ ws, int slices, int64_t slice_stride, int CO, int CI) {
+  const int64_t items = (int64_t)CO * CI;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t co = i / CI, ci = i - co * CI;
+    float acc[9];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) acc[tap] = ws[(int64_t)tap * items + i];
+    for (int j = 1; j < slices; ++j)
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) acc[tap] += ws[j * slice_stride + (int64_t)tap * items + i];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) dw[co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw] = acc[tap];
+  }
+}
+
+constexpr int gBM = 128, gBCI = 32;
+constexpr int kTargetGroupsW = 6144;   // ~12 rounds of two workgroups per compute unit
+constexpr int kMaxSlices = 16;
+
+int wgrad_split_n(int64_t co, int64_t ci, int64_t nb, int64_t rows) {
+  (void)rows;
+  int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
+  if (tiles >= 1024 || nb < 2) return 1;
+  int64_t want = (kTargetGroupsW + tiles - 1) / tiles;
+  if (want > kMaxSlices) want = kMaxSlices;
+  if (want > nb) want = nb;
+  int64_t per = (nb + want - 1) / want;
+  return (int)((nb + per - 1) / per);
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  using namespace tofu;
+  if (!op || op->kind != TOFU_OP_CONV2D_WGRAD) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d weight gradient");
+  tofu_region_t out_box, in_boxes[2];
+  int64_t pad_lo[2], pad_hi[2];
+  int32_t partial = 0;
+  int rc = tofu_op_regions(op, splits, nsplits, &out_box, in_boxes, pad_lo, pad_hi, &partial);
+  if (rc) return rc;
+  if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1)
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d weight-gradient kernels implement KH = KW = 3, stride 1, pad 0 or 1");
+  if ((rc = check_tensor("x", x, 4, &in_boxes[0]))) return rc;
+  if ((rc = check_tensor("dy", dy, 4, &in_boxes[1]))) return rc;
+  if ((rc = check_tensor("dw", dw, 4, &out_box))) return rc;
+  if (volume(&out_box) == 0) return TOFU_OK;
+
+  int64_t xs[4], ds[4], os[4];
+  effective_strides(x, xs);
+  effective_strides(dy, ds);
+  effective_strides(dw, os);
+  WgradArgs p;
+  p.x = element_ptr(x, xs, in_boxes[0].lo);
+  p.dy = element_ptr(dy, ds, in_boxes[1].lo);
+  float* dw_out = const_cast<float*>(element_ptr(dw, os, out_box.lo));
+  for (int d = 0; d < 4; ++d) { p.xs[d] = xs[d]; p.ds[d] = ds[d]; p.os[d] = os[d]; }
+  const int64_t CO = out_box.hi[0] - out_box.lo[0], CI = out_box.hi[1] - out_box.lo[1];
+  const int64_t NB = in_boxes[0].hi[0] - in_boxes[0].lo[0];
+  const int64_t HO = in_boxes[1].hi[2] - in_boxes[1].lo[2], WO = in_boxes[1].hi[3] - in_boxes[1].lo[3];
+  if (CO >= (1 << 30) || CI >= (1 << 30) || NB * HO >= (1 << 30) || WO >= (1 << 20))
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d weight-gradient shard extent too large");
+  p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.HO = (int)HO; p.WO = (int)WO;
+  p.IH = (int)(in_boxes[0].hi[2] - in_boxes[0].lo[2]);
+  p.IW = (int)(in_boxes[0].hi[3] - in_boxes[0].lo[3]);
+  p.plh = (int)pad_lo[0]; p.plw = (int)pad_lo[1];
+  p.tiles_m = (int)((CO + gBM - 1) / gBM);
+  p.tiles_n = (int)((CI + gBCI - 1) / gBCI);
+  // cut an output row into equal chunks of at most 32 columns, whole 16-byte vectors when possible
+  p.chunks = (int)((WO + kKR - 1) / kKR);
+  p.CW = (int)((WO + p.chunks - 1) / p.chunks);
+  if (p.chunks > 1) p.CW = (p.CW + 3) / 4 * 4;
+  p.fast = ds[3] == 1 && ds[1] % 4 == 0 && ds[2] % 4 == 0 && ds[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
+  const int NT = 64 * (gBM / 32);
+  const int slices = wgrad_split_n(CO, CI, NB, HO);
+  p.n_per_slice = (int)((NB + slices - 1) / slices);
+  p.to_workspace = slices > 1;
+  p.slice_stride = CO * CI * 9;
+  if (slices > 1) {
+    const size_t need = (size_t)slices * (size_t)p.slice_stride * sizeof(float);
+    if (!workspace || workspace_bytes < need)
+      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    p.out = static_cast<float*>(workspace);
+  } else {
+    p.out = dw_out;
+  }
+  auto kern = wgrad_kernel<gBM, gBCI>;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int total = p.tiles_m * p.tiles_n;
+  hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8, slices), dim3(NT), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
+  if (slices > 1) {
+    const int64_t items = CO * CI;
+    const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
+    hipLaunchKernelGGL(wgrad_slice_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
+                       static_cast<const float*>(workspace), slices, p.slice_stride, (int)CO, (int)CI);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient slice sum launch failed: %s", hipGetErrorString(e));
+  }
+  return TOFU_OK;
+}

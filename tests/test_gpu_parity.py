@@ -1,0 +1,355 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element,
+on seeded inputs.  Sizes here are small enough for the oracle to evaluate every element while
+still spanning several tiles and ragged tails; the full-size workloads are in
+test_gpu_workloads.py.
+
+Bars: indices, regions and copies are bit-exact; fp32 results satisfy
+|gpu - oracle| <= 1e-5 * S per element, S = sum |a*b| (for the reduce: sum_j |p_j|); with
+small-integer inputs every sum is exact in fp32 and fp64, so equality is bit-exact.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1807_08887_amd as tofu
+import tofu_synth as synth
+from oracle import regions as R
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+DEV = "cuda:0"
+
+MM_DIMS = {"M": tofu.MM_DIM_M, "N": tofu.MM_DIM_N, "K": tofu.MM_DIM_K}
+CONV_DIMS = {"N": tofu.CONV_DIM_N, "CO": tofu.CONV_DIM_CO, "H": tofu.CONV_DIM_H, "W": tofu.CONV_DIM_W, "CI": tofu.CONV_DIM_CI}
+WGRAD_DIMS = {"CO": tofu.WGRAD_DIM_CO, "CI": tofu.WGRAD_DIM_CI, "N": tofu.WGRAD_DIM_N}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def assert_close(got, val, absum, what=""):
+    got = got.astype(np.float64)
+    err = np.abs(got - val)
+    bound = TOL * absum
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} elements off, worst ratio {np.max(err / np.maximum(absum, 1e-300)):.3e}"
+    assert (got[absum == 0] == 0).all()
+
+
+def workspace(op, splits):
+    n = tofu.workspace_bytes(op, splits)
+    return torch.empty(max(n, 16) // 4, dtype=torch.float32, device=DEV) if n else None
+
+
+# ----------------------------------------------------------------------------- reduce
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("count", [1, 3, 1000, 4097, (1 << 20) + 5])
+def test_partition_reduce(k, count):
+    parts = [synth.normal(11, j, (count,), 2.0) for j in range(k)]
+    d = [dev(p) for p in parts]
+    out = torch.empty(count, dtype=torch.float32, device=DEV)
+    tofu.partition_reduce(out, d)
+    val, absum = oracle.reduce(parts)
+    assert_close(out.cpu().numpy(), val, absum, f"reduce k={k} count={count}")
+    # fixed left-to-right fp32 order: identical to the same order on the host, bit for bit
+    ref = parts[0].copy()
+    for p in parts[1:]:
+        ref = ref + p
+    assert np.array_equal(out.cpu().numpy(), ref)
+    # in place: dst == partials[0]
+    tofu.partition_reduce(d[0], d)
+    assert np.array_equal(d[0].cpu().numpy(), ref)
+
+
+def test_partition_reduce_edge_cases():
+    out = torch.zeros(8, dtype=torch.float32, device=DEV)
+    tofu.partition_reduce(out, [out], count=0)                      # empty: no-op
+    ints = [synth.small_int(12, j, (1001,), -1000, 1000) for j in range(8)]
+    buf = [torch.empty(1004, dtype=torch.float32, device=DEV) for _ in range(8)]
+    for b, a in zip(buf, ints):
+        b[1:1002] = dev(a)                                          # 4-byte aligned only
+    dst = torch.empty(1004, dtype=torch.float32, device=DEV)
+    tofu.partition_reduce(dst[1:1002].data_ptr(), [b[1:1002].data_ptr() for b in buf], count=1001)
+    assert np.array_equal(dst[1:1002].cpu().numpy().astype(np.float64), oracle.reduce(ints)[0])
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.partition_reduce(buf[1], buf)                          # dst aliases partials[1]
+    assert e.value.status == -1
+    with pytest.raises(tofu.TofuError):
+        tofu.partition_reduce(dst, buf * 3)                         # k = 24 > 16
+
+
+# ----------------------------------------------------------------------------- fetch
+def _fetch_case(shape, box, cuts_dim, k, dtype_int=True, strided=False):
+    t = synth.small_int(21, 0, shape, -99, 99)
+    blocks, descs, keep = [], [], []
+    for s in range(k):
+        lo, hi = R.shard_range(shape[cuts_dim], k, s)
+        bbox = [(0, e) for e in shape]
+        bbox[cuts_dim] = (lo, hi)
+        blk = t[R.box_slices(bbox)]
+        blocks.append((blk, bbox))
+        if strided:   # block lives inside a larger allocation: non-dense strides
+            big = torch.full([e + 3 for e in blk.shape], -7.0, dtype=torch.float32, device=DEV)
+            view = big[tuple(slice(1, 1 + e) for e in blk.shape)]
+            view.copy_(dev(blk))
+        else:
+            view = dev(blk)
+        keep.append(view)
+        descs.append(tofu.tensor(view, [b[0] for b in bbox]))
+    want = R.fetch(box, blocks)
+    out = torch.full([hi - lo for lo, hi in box], -5.0, dtype=torch.float32, device=DEV)
+    tofu.region_fetch(tofu.tensor(out, [lo for lo, _ in box]), descs)
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("strided", [False, True])
+def test_region_fetch_shapes(strided):
+    _fetch_case((40,), [(3, 37)], 0, 3, strided=strided)
+    _fetch_case((9, 16), [(2, 9), (4, 12)], 0, 2, strided=strided)                 # 16-byte vectors possible
+    _fetch_case((5, 6, 14), [(0, 5), (1, 6), (0, 14)], 1, 3, strided=strided)      # 8-byte vectors
+    _fetch_case((4, 6, 9, 7), [(1, 4), (0, 6), (2, 8), (0, 7)], 2, 3, strided=strided)   # scalar runs
+    _fetch_case((3, 2, 4, 5, 3, 2), [(0, 3), (0, 2), (1, 4), (0, 5), (1, 3), (0, 2)], 3, 5, strided=strided)
+
+
+def test_region_fetch_halo_of_h_split():
+    """The conv workload's fetch in small: own rows + one halo row of the neighbour (Sec. 4.2)."""
+    op = dict(kind="conv2d", batch=6, c_in=20, c_out=4, H=14, W=14, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(22, 0, (6, 20, 14, 14), 1.0)
+    own = [(x[:, :, lo:hi].copy(), [(0, 6), (0, 20), (lo, hi), (0, 14)]) for lo, hi in (R.shard_range(14, 2, s) for s in range(2))]
+    for s in range(2):
+        box = R.op_regions(op, [("H", 2, s)])["in_boxes"][0]
+        assert box[2] == ((0, 8) if s == 0 else (6, 14))
+        srcs = [dev(b) for b, _ in own]
+        out = torch.empty([hi - lo for lo, hi in box], dtype=torch.float32, device=DEV)
+        tofu.region_fetch(tofu.tensor(out, [lo for lo, _ in box]), [tofu.tensor(t, [b[0] for b in bb]) for t, (_, bb) in zip(srcs, own)])
+        assert np.array_equal(out.cpu().numpy(), R.fetch(box, own))
+
+
+def test_region_fetch_empty_destination():
+    src = torch.zeros(4, 4, dtype=torch.float32, device=DEV)
+    out = torch.zeros(0, 4, dtype=torch.float32, device=DEV)
+    tofu.region_fetch(tofu.tensor(out, [2, 0]), [tofu.tensor(src)])
+
+
+# ----------------------------------------------------------------------------- shard runners
+def run_matmul(A, B, splits, names=MM_DIMS, a_full=None, b_full=None):
+    """Run one matmul shard on full-size device tensors; returns (C device tensor, regions)."""
+    M, K = A.shape
+    N = B.shape[1]
+    op = tofu.matmul_desc(M, N, K)
+    sp = [(names[d], k, s) for d, k, s in splits]
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_matmul(op, sp, tofu.tensor(a_full), tofu.tensor(b_full), tofu.tensor(C), workspace(op, sp))
+    return C
+
+
+def assemble(op_dict, dim, k, run):
+    full_box = R.op_regions(op_dict, [])["out_box"]
+    shape = [hi - lo for lo, hi in full_box]
+    total = np.zeros(shape, dtype=np.float32)
+    partials = []
+    for s in range(k):
+        reg = R.op_regions(op_dict, [(dim, k, s)])
+        out = run([(dim, k, s)]).cpu().numpy()
+        sl = R.box_slices(reg["out_box"])
+        inside = np.zeros(shape, dtype=bool)
+        inside[sl] = True
+        assert not np.isnan(out[inside]).any() and np.isnan(out[~inside]).all(), "shard must write exactly its output box"
+        if reg["is_partial"]:
+            partials.append(out)
+        else:
+            total[sl] = out[sl]
+    if partials:
+        d = [dev(p) for p in partials]
+        res = torch.empty_like(d[0])
+        tofu.partition_reduce(res, d)
+        total = res.cpu().numpy()
+    return total
+
+
+# ----------------------------------------------------------------------------- matmul
+def test_tiny_matmul_workload():
+    """Workload 1: C[64,96] = A[64,128] B[128,96]; 2-way K split (partials summed) and 2-way N
+    split (concatenated) both reproduce the unpartitioned oracle."""
+    cfg = synth.CONFIGS["tiny_matmul"]
+    A = synth.draw(cfg["a"], cfg["seed"], 0, (cfg["M"], cfg["K"]))
+    B = synth.draw(cfg["b"], cfg["seed"], 1, (cfg["K"], cfg["N"]))
+    dA, dB = dev(A), dev(B)
+    val, absum = oracle.matmul_box(A, B)
+    op = dict(kind="matmul", M=cfg["M"], N=cfg["N"], K=cfg["K"])
+    for dim in ["K", "N", "M"]:
+        got = assemble(op, dim, 2, lambda sp: run_matmul(A, B, sp, a_full=dA, b_full=dB))
+        assert_close(got, val, absum, f"tiny matmul split {dim}")
+    # a single worker's K partial against the oracle restricted to its K range
+    part = run_matmul(A, B, [("K", 2, 1)], a_full=dA, b_full=dB).cpu().numpy()
+    pv, ps = oracle.matmul_box(A, B, krange=(64, 128))
+    assert_close(part, pv, ps, "tiny matmul K partial")
+
+
+@pytest.mark.parametrize("M,N,K", [(70, 130, 77), (128, 256, 4096), (1, 1, 1), (33, 65, 1030), (257, 64, 16)])
+def test_matmul_shapes_unpartitioned(M, N, K):
+    A = synth.uniform(31, 0, (M, K), -1, 1)
+    B = synth.uniform(31, 1, (K, N), -1, 1)
+    got = run_matmul(A, B, [], a_full=dev(A), b_full=dev(B)).cpu().numpy()
+    val, absum = oracle.matmul_box(A, B)
+    assert_close(got, val, absum, f"matmul {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 8])
+def test_matmul_pnr_invariant_bit_exact(k):
+    A = synth.small_int(32, 0, (72, 200), -4, 4)
+    B = synth.small_int(32, 1, (200, 136), -4, 4)
+    dA, dB = dev(A), dev(B)
+    want = oracle.matmul_box(A, B)[0]
+    op = dict(kind="matmul", M=72, N=136, K=200)
+    for dim in ["M", "N", "K"]:
+        got = assemble(op, dim, k, lambda sp: run_matmul(A, B, sp, a_full=dA, b_full=dB))
+        assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_matmul_recursive_plan_and_blocks():
+    """A two-step plan <N/2, K/2> on owned blocks: A and B are passed as the blocks a worker
+    holds (extent != whole tensor), C as the worker's own output block."""
+    A = synth.small_int(33, 0, (64, 96), -4, 4)
+    B = synth.small_int(33, 1, (96, 80), -4, 4)
+    op_d = dict(kind="matmul", M=64, N=80, K=96)
+    op = tofu.matmul_desc(64, 80, 96)
+    want = oracle.matmul_box(A, B)[0]
+    total = np.zeros((64, 80))
+    for a, b in itertools.product(range(2), repeat=2):
+        plan = [("N", 2, a), ("K", 2, b)]
+        reg = R.op_regions(op_d, plan)
+        (m0, m1), (k0, k1) = reg["in_boxes"][0]
+        (_, _), (n0, n1) = reg["in_boxes"][1]
+        blkA, blkB = dev(A[m0:m1, k0:k1]), dev(B[k0:k1, n0:n1])
+        C = torch.zeros(64, n1 - n0, dtype=torch.float32, device=DEV)
+        sp = [(MM_DIMS[d], k, s) for d, k, s in plan]
+        tofu.shard_matmul(op, sp, tofu.tensor(blkA, [m0, k0]), tofu.tensor(blkB, [k0, n0]), tofu.tensor(C, [0, n0]), workspace(op, sp))
+        total[:, n0:n1] += C.cpu().numpy()
+    assert np.array_equal(total, want)
+
+
+def test_matmul_strided_views():
+    A = synth.uniform(34, 0, (64, 300), -1, 1)
+    B = synth.uniform(34, 1, (300, 200), -1, 1)
+    val, absum = oracle.matmul_box(A, B)
+    At = dev(A.T.copy()).t()            # column-major view: unit stride along m
+    Bt = dev(B.T.copy()).t()
+    op = tofu.matmul_desc(64, 200, 300)
+    C = torch.empty(64, 200, dtype=torch.float32, device=DEV)
+    tofu.shard_matmul(op, [], tofu.tensor(At), tofu.tensor(Bt), tofu.tensor(C))
+    assert_close(C.cpu().numpy(), val, absum, "column-major operands")
+    # output written into a column block of a wider row-major buffer
+    wide = torch.zeros(64, 512, dtype=torch.float32, device=DEV)
+    dA, dB = dev(A), dev(B)              # keep the device buffers alive: descriptors only hold addresses
+    tofu.shard_matmul(op, [], tofu.tensor(dA), tofu.tensor(dB), tofu.tensor(wide[:, 100:300]))
+    assert_close(wide[:, 100:300].cpu().numpy(), val, absum, "strided output")
+    assert (wide[:, :100] == 0).all() and (wide[:, 300:] == 0).all()
+
+
+# ----------------------------------------------------------------------------- conv2d
+def run_conv(opd, splits, dx, dw, x_lo=None):
+    op = tofu.conv2d_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["H"], opd["W"], pad=opd["pad"])
+    sp = [(CONV_DIMS[d], k, s) for d, k, s in splits]
+    ho, wo = opd["H"] + 2 * opd["pad"] - 2, opd["W"] + 2 * opd["pad"] - 2
+    y = torch.full((opd["batch"], opd["c_out"], ho, wo), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_conv2d(op, sp, tofu.tensor(dx, x_lo), tofu.tensor(dw), tofu.tensor(y), workspace(op, sp))
+    return y
+
+
+@pytest.mark.parametrize("batch,c_in,c_out,H,W,pad", [(3, 10, 70, 14, 14, 1), (2, 5, 33, 9, 11, 1), (2, 16, 64, 8, 8, 0),
+                                                      (1, 3, 5, 1, 1, 1), (2, 9, 40, 30, 28, 1)])
+def test_conv2d_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
+    opd = dict(kind="conv2d", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=pad)
+    x = synth.normal(41, 0, (batch, c_in, H, W), 1.0)
+    w = synth.normal(41, 1, (c_out, c_in, 3, 3), 0.3)
+    got = run_conv(opd, [], dev(x), dev(w)).cpu().numpy()
+    val, absum = oracle.conv2d_box(x, w, pad=pad)
+    assert_close(got, val, absum, f"conv2d {opd}")
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_conv2d_pnr_invariant_bit_exact(k):
+    opd = dict(kind="conv2d", batch=4, c_in=12, c_out=72, H=12, W=10, KH=3, KW=3, stride=1, pad=1)
+    x = synth.small_int(42, 0, (4, 12, 12, 10), -3, 3)
+    w = synth.small_int(42, 1, (72, 12, 3, 3), -3, 3)
+    dx, dw = dev(x), dev(w)
+    want = oracle.conv2d_box(x, w, pad=1)[0]
+    for dim in ["N", "CO", "H", "W", "CI"]:
+        got = assemble(opd, dim, k, lambda sp: run_conv(opd, sp, dx, dw))
+        assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_conv2d_on_fetched_halo_region():
+    """Plan <CO/2, H/2>: the worker fetches its halo-widened input rows from the two owners'
+    blocks, then convolves the fetched buffer (whose extent is the region, not the tensor)."""
+    opd = dict(kind="conv2d", batch=5, c_in=16, c_out=64, H=14, W=14, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(43, 0, (5, 16, 14, 14), 1.0)
+    w = synth.normal(43, 1, (64, 16, 3, 3), 0.2)
+    val, absum = oracle.conv2d_box(x, w, pad=1)
+    own = [(x[:, :, lo:hi].copy(), [(0, 5), (0, 16), (lo, hi), (0, 14)]) for lo, hi in (R.shard_range(14, 2, s) for s in range(2))]
+    d_own = [dev(b) for b, _ in own]
+    dw = dev(w)
+    op = tofu.conv2d_desc(5, 16, 64, 14, 14)
+    for a, b in itertools.product(range(2), repeat=2):
+        plan = [("CO", 2, a), ("H", 2, b)]
+        reg = R.op_regions(opd, plan)
+        lib = tofu.op_regions(op, [(CONV_DIMS[d], k, s) for d, k, s in plan])
+        assert lib["in_boxes"][0] == [tuple(t) for t in reg["in_boxes"][0]] and lib["pad_lo"] == reg["pad_lo"] and lib["pad_hi"] == reg["pad_hi"]
+        box = reg["in_boxes"][0]
+        region = torch.empty([hi - lo for lo, hi in box], dtype=torch.float32, device=DEV)
+        tofu.region_fetch(tofu.tensor(region, [lo for lo, _ in box]), [tofu.tensor(t, [q[0] for q in bb]) for t, (_, bb) in zip(d_own, own)])
+        y = run_conv(opd, plan, region, dw, x_lo=[lo for lo, _ in box]).cpu().numpy()
+        sl = R.box_slices(reg["out_box"])
+        assert_close(y[sl], val[sl], absum[sl], f"conv on fetched region {plan}")
+    # a region that misses a needed interior row is an error, never silent zero padding
+    short = torch.zeros(5, 16, 7, 14, dtype=torch.float32, device=DEV)
+    with pytest.raises(tofu.TofuError) as e:
+        run_conv(opd, [("H", 2, 0)], short, dw, x_lo=[0, 0, 0, 0])
+    assert e.value.status == -2
+
+
+# ----------------------------------------------------------------------------- wgrad
+def run_wgrad(opd, splits, dx, ddy):
+    op = tofu.wgrad_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["H"], opd["W"], pad=opd["pad"])
+    sp = [(WGRAD_DIMS[d], k, s) for d, k, s in splits]
+    dw = torch.full((opd["c_out"], opd["c_in"], 3, 3), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_conv2d_wgrad(op, sp, tofu.tensor(dx), tofu.tensor(ddy), tofu.tensor(dw), workspace(op, sp))
+    return dw
+
+
+@pytest.mark.parametrize("batch,c_in,c_out,H,W,pad", [(3, 40, 130, 28, 28, 1), (2, 5, 33, 9, 11, 1), (4, 32, 64, 8, 8, 0),
+                                                      (1, 3, 5, 1, 1, 1), (2, 9, 20, 6, 70, 1)])
+def test_wgrad_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
+    opd = dict(kind="conv2d_wgrad", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=pad)
+    ho, wo = H + 2 * pad - 2, W + 2 * pad - 2
+    x = synth.normal(51, 0, (batch, c_in, H, W), 1.0)
+    dy = synth.normal(51, 1, (batch, c_out, ho, wo), 1.0)
+    got = run_wgrad(opd, [], dev(x), dev(dy)).cpu().numpy()
+    val, absum = oracle.wgrad_box(x, dy, 3, 3, pad=pad)
+    assert_close(got, val, absum, f"wgrad {opd}")
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_wgrad_pnr_invariant_bit_exact(k):
+    opd = dict(kind="conv2d_wgrad", batch=8, c_in=36, c_out=130, H=12, W=10, KH=3, KW=3, stride=1, pad=1)
+    x = synth.small_int(52, 0, (8, 36, 12, 10), -3, 3)
+    dy = synth.small_int(52, 1, (8, 130, 12, 10), -3, 3)
+    dx, ddy = dev(x), dev(dy)
+    want = oracle.wgrad_box(x, dy, 3, 3, pad=1)[0]
+    for dim in ["CO", "CI", "N"]:
+        got = assemble(opd, dim, k, lambda sp: run_wgrad(opd, sp, dx, ddy))
+        assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_runs_are_bit_identical():
+    """No atomics anywhere: two runs of the same call give the same bits."""
+    A = synth.normal(61, 0, (128, 4096), 1.0); B = synth.normal(61, 1, (4096, 256), 1.0)
+    dA, dB = dev(A), dev(B)
+    c1 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
+    c2 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
+    assert np.array_equal(c1, c2)

@@ -1,0 +1,186 @@
+"""CPU tests of the C-ABI library's host side: it loads, exports every symbol the header
+declares, its integer arithmetic (shard ranges, plans, regions, residual padding) is bit-exact
+against the oracle's independent Python definitions, and every host-checked error path
+returns its status before anything could be launched.  No compute call is made."""
+import ctypes
+import itertools
+import os
+import re
+
+import pytest
+
+import paper_1807_08887_amd as tofu
+from oracle import regions as R
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000        # a non-null "device pointer"; nothing below ever dereferences it
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tofu.h")).read()
+    names = set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", header))
+    assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
+            "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
+            "tofu_last_error"} <= names
+    lib = ctypes.CDLL(tofu.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in tofu.h but not exported"
+
+
+def test_shard_range_matches_oracle_exhaustively():
+    for D in range(1, 65):
+        for k in range(1, min(D, 9) + 1):
+            for s in range(k):
+                assert tofu.shard_range(D, k, s) == R.shard_range(D, k, s)
+    big = (1 << 62) + 12345          # shard * extent overflows 64 bits without a wide multiply
+    assert tofu.shard_range(big, 7, 6) == R.shard_range(big, 7, 6)
+    for bad in [(-1, 1, 0), (4, 0, 0), (4, 2, 2), (4, 2, -1), (3, 4, 0)]:
+        with pytest.raises(tofu.TofuError) as e:
+            tofu.shard_range(*bad)
+        assert e.value.status == -1
+
+
+def _desc(op):
+    if op["kind"] == "matmul":
+        return tofu.matmul_desc(op["M"], op["N"], op["K"]), {"M": 0, "N": 1, "K": 2}
+    args = (op["batch"], op["c_in"], op["c_out"], op["H"], op["W"], op["KH"], op["KW"], op["stride"], op["pad"])
+    if op["kind"] == "conv2d":
+        return tofu.conv2d_desc(*args), {"N": 0, "CO": 1, "H": 2, "W": 3, "CI": 4}
+    return tofu.wgrad_desc(*args), {"CO": 0, "CI": 1, "N": 2}
+
+
+def _same(lib, ref):
+    assert lib["out_box"] == [tuple(b) for b in ref["out_box"]]
+    assert lib["in_boxes"] == [[tuple(b) for b in box] for box in ref["in_boxes"]]
+    assert lib["pad_lo"] == ref["pad_lo"] and lib["pad_hi"] == ref["pad_hi"]
+    assert lib["is_partial"] == ref["is_partial"]
+
+
+OPS = [
+    dict(kind="matmul", M=13, N=9, K=21),
+    dict(kind="conv2d", batch=5, c_in=7, c_out=6, H=11, W=9, KH=3, KW=3, stride=1, pad=1),
+    dict(kind="conv2d", batch=4, c_in=4, c_out=4, H=12, W=13, KH=5, KW=3, stride=2, pad=2),
+    dict(kind="conv2d", batch=4, c_in=4, c_out=4, H=9, W=9, KH=3, KW=3, stride=1, pad=0),
+    dict(kind="conv2d_wgrad", batch=6, c_in=5, c_out=7, H=8, W=10, KH=3, KW=3, stride=1, pad=1),
+    dict(kind="conv2d_wgrad", batch=6, c_in=5, c_out=7, H=9, W=10, KH=3, KW=2, stride=2, pad=0),
+]
+
+
+@pytest.mark.parametrize("op", OPS, ids=lambda o: f"{o['kind']}-{o.get('stride', 0)}-{o.get('pad', 0)}")
+def test_regions_match_oracle_for_one_and_two_step_plans(op):
+    desc, dims = _desc(op)
+    ext = R.iteration_extents(op)
+    _same(tofu.op_regions(desc, []), R.op_regions(op, []))
+    steps = [(d, k, s) for d in dims for k in range(1, min(ext[d], 4) + 1) for s in range(k)]
+    for st in steps:
+        _same(tofu.op_regions(desc, [(dims[st[0]], st[1], st[2])]), R.op_regions(op, [st]))
+    for a, b in itertools.product(steps, repeat=2):
+        try:
+            ref = R.op_regions(op, [a, b])
+        except ValueError:
+            with pytest.raises(tofu.TofuError):
+                tofu.op_regions(desc, [(dims[a[0]], a[1], a[2]), (dims[b[0]], b[1], b[2])])
+            continue
+        _same(tofu.op_regions(desc, [(dims[a[0]], a[1], a[2]), (dims[b[0]], b[1], b[2])]), ref)
+
+
+def test_workload_regions():
+    """The five workloads' ranges: 128->64, 96->48; 32768->4096, 16384->2048, 2560->320, 128->16; 14->7 with halo."""
+    mm = tofu.matmul_desc(128, 32768, 16384)
+    assert tofu.op_regions(mm, [(tofu.MM_DIM_N, 8, 3)])["in_boxes"][1] == [(0, 16384), (12288, 16384)]
+    r = tofu.op_regions(mm, [(tofu.MM_DIM_K, 8, 3)])
+    assert r["in_boxes"] == [[(0, 128), (6144, 8192)], [(6144, 8192), (0, 32768)]] and r["is_partial"]
+    cv = tofu.conv2d_desc(128, 2560, 2560, 14, 14)
+    r0 = tofu.op_regions(cv, [(tofu.CONV_DIM_CO, 8, 3), (tofu.CONV_DIM_H, 2, 0)])
+    r1 = tofu.op_regions(cv, [(tofu.CONV_DIM_CO, 8, 3), (tofu.CONV_DIM_H, 2, 1)])
+    assert r0["in_boxes"][0][2] == (0, 8) and (r0["pad_lo"][0], r0["pad_hi"][0]) == (1, 0)
+    assert r1["in_boxes"][0][2] == (6, 14) and (r1["pad_lo"][0], r1["pad_hi"][0]) == (0, 1)
+    assert r0["out_box"] == [(0, 128), (960, 1280), (0, 7), (0, 14)]
+    wg = tofu.wgrad_desc(128, 1280, 1280, 28, 28)
+    r = tofu.op_regions(wg, [(tofu.WGRAD_DIM_N, 8, 3)])
+    assert r["is_partial"] and r["out_box"] == [(0, 1280), (0, 1280), (0, 3), (0, 3)] and r["in_boxes"][0][0] == (48, 64)
+    # three 2-way steps on one dimension equal one 8-way step when 8 divides the extent
+    for s in range(8):
+        plan = [(tofu.MM_DIM_N, 2, (s >> 2) & 1), (tofu.MM_DIM_N, 2, (s >> 1) & 1), (tofu.MM_DIM_N, 2, s & 1)]
+        assert tofu.op_regions(mm, plan)["out_box"] == tofu.op_regions(mm, [(tofu.MM_DIM_N, 8, s)])["out_box"]
+
+
+def _t(box, data=FAKE, stride=None):
+    t = tofu.Tensor()
+    t.data = data
+    t.extent = tofu.Region.from_box(box)
+    for i, s in enumerate(stride or []):
+        t.stride[i] = s
+    return t
+
+
+def test_fetch_error_paths_are_checked_on_the_host():
+    dst = _t([(0, 4), (0, 8)])
+    left, right = _t([(0, 4), (0, 4)], FAKE + (1 << 20)), _t([(0, 4), (4, 8)], FAKE + (2 << 20))
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(dst, [left], stream=0)
+    assert e.value.status == -3 and "16 of the 32" in str(e.value)               # UNCOVERED
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(dst, [left, right, _t([(2, 4), (3, 5)], FAKE + (3 << 20))], stream=0)
+    assert e.value.status == -4                                                   # OVERLAP
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(dst, [left, _t([(0, 4), (4, 8), (0, 1)], FAKE + (2 << 20))], stream=0)
+    assert e.value.status == -1                                                   # ndim mismatch
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(dst, [left, _t([(0, 4), (4, 8)], FAKE + 16)], stream=0)
+    assert e.value.status == -1 and "overlaps" in str(e.value)                    # dst aliases a source
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(dst, [left] * 17, stream=0)
+    assert e.value.status == -1                                                   # too many sources
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.region_fetch(_t([(0, 4), (0, 8)], data=None), [left, right], stream=0)
+    assert e.value.status == -1
+
+
+def test_shard_call_error_paths_are_checked_on_the_host():
+    mm = tofu.matmul_desc(64, 96, 128)
+    A, B, C = _t([(0, 64), (0, 128)]), _t([(0, 128), (0, 96)], FAKE + (1 << 20)), _t([(0, 64), (0, 96)], FAKE + (2 << 20))
+    with pytest.raises(tofu.TofuError) as e:      # B block lacks the K range this shard reads
+        tofu.shard_matmul(mm, [(tofu.MM_DIM_K, 2, 1)], A, _t([(0, 64), (0, 96)], FAKE + (1 << 20)), C, stream=0)
+    assert e.value.status == -2 and "B does not hold" in str(e.value)
+    with pytest.raises(tofu.TofuError) as e:      # split names a dimension the operator does not have
+        tofu.shard_matmul(mm, [(3, 2, 0)], A, B, C, stream=0)
+    assert e.value.status == -1
+    with pytest.raises(tofu.TofuError) as e:      # wrong operator kind for the entry point
+        tofu.shard_conv2d(mm, [], A, B, C, stream=0)
+    assert e.value.status == -1
+    big = tofu.matmul_desc(128, 4096, 16384)      # needs split-K workspace
+    assert tofu.workspace_bytes(big, []) > 0
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_matmul(big, [], _t([(0, 128), (0, 16384)]), _t([(0, 16384), (0, 4096)], FAKE + (1 << 30)),
+                          _t([(0, 128), (0, 4096)], FAKE + (2 << 30)), stream=0)
+    assert e.value.status == -5
+    cv = tofu.conv2d_desc(2, 4, 4, 8, 8, KH=5, KW=5, pad=2)
+    x, w, y = _t([(0, 2), (0, 4), (0, 8), (0, 8)]), _t([(0, 4), (0, 4), (0, 5), (0, 5)], FAKE + (1 << 20)), _t([(0, 2), (0, 4), (0, 8), (0, 8)], FAKE + (2 << 20))
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_conv2d(cv, [], x, w, y, stream=0)
+    assert e.value.status == -6                   # UNSUPPORTED filter size
+    cv = tofu.conv2d_desc(2, 4, 4, 8, 8)
+    with pytest.raises(tofu.TofuError) as e:      # halo row 4 missing from a 4-row block
+        tofu.shard_conv2d(cv, [(tofu.CONV_DIM_H, 2, 0)], _t([(0, 2), (0, 4), (0, 4), (0, 8)]),
+                          _t([(0, 4), (0, 4), (0, 3), (0, 3)], FAKE + (1 << 20)), y, stream=0)
+    assert e.value.status == -2
+    wg = tofu.wgrad_desc(16, 64, 64, 8, 8)
+    assert tofu.workspace_bytes(wg, []) > 0
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_conv2d_wgrad(wg, [], _t([(0, 16), (0, 64), (0, 8), (0, 8)]), _t([(0, 16), (0, 64), (0, 8), (0, 8)], FAKE + (1 << 20)),
+                                _t([(0, 64), (0, 64), (0, 3), (0, 3)], FAKE + (2 << 20)), stream=0)
+    assert e.value.status == -5
+
+
+def test_reduce_error_paths_are_checked_on_the_host():
+    import ctypes as C
+    lib = tofu.load()
+    ptrs = (C.c_void_p * 17)(*[FAKE + i * 4096 for i in range(17)])
+    assert lib.tofu_partition_reduce(C.c_void_p(FAKE + (1 << 20)), ptrs, 0, 16, None) == -1
+    assert lib.tofu_partition_reduce(C.c_void_p(FAKE + (1 << 20)), ptrs, 17, 16, None) == -1
+    assert lib.tofu_partition_reduce(C.c_void_p(FAKE + (1 << 20)), ptrs, 2, -1, None) == -1
+    assert lib.tofu_partition_reduce(C.c_void_p(FAKE + 4096 + 8), ptrs, 2, 16, None) == -1     # overlaps partials[1]
+    assert lib.tofu_partition_reduce(None, ptrs, 2, 16, None) == -1
+    assert lib.tofu_partition_reduce(None, ptrs, 2, 0, None) == 0                              # empty is a no-op
+    assert "k = 17" in tofu.last_error() or tofu.last_error()
