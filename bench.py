@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Benchmark of the shard hot path on one MI355X.
+
+One "step" is one pass over every leg of the hot path at full workload size (see
+tofu_workloads.py): two shard GEMMs, two shard convolutions, one shard weight gradient, the
+halo region fetch and the two 8-way partition-n-reduce sums.  All inputs are resident in HBM
+before the timed region; every leg is one call through the C ABI on torch's current stream.
+
+Prints ONE JSON line.  `value` is the algorithmic FLOP of the contraction legs divided by the
+wall time of the whole step (fetch and reduce legs included).  `legs` gives every leg's own
+TFLOP/s or GB/s and roofline fraction from HIP events recorded between the legs; `roofline`
+repeats the figures of the leg whose single kernel has the longest average duration.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 matrix peak, HBM3E peak
+METRIC = "shard GEMM/conv TFLOP/s (% fp32 MFMA peak); partition-n-reduce GB/s (% HBM)"
+
+
+def cpu_baseline(legs):
+    """Time the fp64 oracle on a bounded sample of the contraction legs' outputs (host cores)."""
+    import numpy as np
+    import oracle
+    import tofu_synth as synth
+    oracle.build(force=False)
+    flop, secs, parts = 0.0, 0.0, []
+    for leg in legs:
+        h = leg.host
+        if leg.bound != "mfma" or "kind" not in h:
+            continue
+        if h["kind"] == "matmul":
+            box = h["box"]
+            n = 1 << 14
+            pts = synth.coords(900, 1, n, [b[1] - b[0] for b in box])
+            k0, k1 = h["krange"]
+            t = time.perf_counter()
+            if "b_col0" in h:      # B is the worker's column block: local columns
+                oracle.matmul_pts(h["A"], h["B"], pts, krange=(k0, k1))
+            else:                  # B is the worker's row block: local rows, A columns shifted
+                oracle.matmul_pts(np.ascontiguousarray(h["A"][:, k0:k1]), h["B"], pts)
+            secs += time.perf_counter() - t
+            flop += 2.0 * n * (k1 - k0)
+            parts.append(f"{leg.name}: {n} outputs")
+        elif h["kind"] == "conv2d" and leg.name == "conv_cout":
+            n = 1 << 14
+            shape = [b[1] - b[0] for b in h["box"]]
+            pts = synth.coords(900, 2, n, shape)
+            t = time.perf_counter()
+            oracle.conv2d_pts(h["x"], h["w"], pts, stride=1, pad=1)
+            secs += time.perf_counter() - t
+            flop += leg.work * n / float(np.prod(shape))
+            parts.append(f"{leg.name}: {n} outputs")
+        elif h["kind"] == "wgrad":
+            n = 1 << 12
+            c = h["x"].shape[1]
+            pts = synth.coords(900, 3, n, (c, c, 3, 3))
+            t = time.perf_counter()
+            oracle.wgrad_pts(h["x"], h["dy"], 3, 3, pts, stride=1, pad=1)
+            secs += time.perf_counter() - t
+            flop += leg.work * n / float(c * c * 9)
+            parts.append(f"{leg.name}: {n} outputs")
+    return {"value": flop / secs * 1e-12 if secs > 0 else None, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "seconds": round(secs, 3), "sample": "seeded output coordinates, every term of each sum: " + "; ".join(parts)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--legs", type=str, default="", help="comma-separated subset of legs (default: all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one worker's shard on ONE GPU; --gpus > 1 is not supported "
+              "(other workers' partials and halo blocks are generated into the same GPU's HBM).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1807_08887_amd as tofu
+    import tofu_workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    tofu.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    which = [s for s in args.legs.split(",") if s] or None
+    legs = tofu_workloads.build(dev, which, keep_host=not args.no_cpu_baseline)
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        for i, leg in enumerate(legs):
+            if events is not None:
+                events[i].record()
+            leg.run()
+        if events is not None:
+            events[len(legs)].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(legs) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    leg_ms = [sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps for i in range(len(legs))]
+    leg_out = []
+    for leg, ms in zip(legs, leg_ms):
+        peak, unit = PEAK[leg.bound]
+        scale = 1e-9 if leg.bound == "mfma" else 1e-6           # FLOP/ms -> TFLOP/s, B/ms -> GB/s
+        achieved = leg.work / ms * scale
+        entry = {"leg": leg.name, "bound": leg.bound, "ms": round(ms, 4), "achieved": round(achieved, 2), "unit": unit,
+                 "frac": round(achieved / peak, 4)}
+        if leg.conventional_flop:
+            entry["conventional_tflops"] = round(leg.conventional_flop / ms * 1e-9, 2)
+        leg_out.append(entry)
+    flop = sum(l.work for l in legs if l.bound == "mfma")
+    single_kernel = [e for e in leg_out if e["leg"] in ("conv_cout", "conv_cout_h", "gemm_ksplit")] or leg_out
+    dom = max(single_kernel, key=lambda e: e["ms"])
+    out = {
+        "metric": METRIC, "value": round(flop / (ms_per_step * 1e-3) * 1e-12, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "one step = every leg of the shard path at full size: " + ", ".join(l.name for l in legs),
+                   "shapes": "LSTM gate GEMM 128x32768x16384 (8-way N and K shards); 3x3 conv 2560ch 14x14 batch 128 "
+                             "(C_out/8 and C_out/8 x H/2 shards, halo fetch); 3x3 wgrad 1280ch 28x28 (batch/8 shard); 8-way reduces"},
+        "roofline": {"kernel": dom["leg"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": PEAK[dom["bound"]][0],
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
+        "legs": leg_out,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(legs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+"""The timed workloads: one worker's share of each partitioned operator, at full size.
+
+Builds, from the seeded generator, the device buffers of the four large workloads and the
+"legs" of one step of the hot path (each leg is one call through the C ABI):
+
+  gemm_nsplit   LSTM gate GEMM, shard 3 of an 8-way split of N:  X[128,16384] . W[:,12288:16384]
+  gemm_ksplit   same GEMM, shard 3 of an 8-way split of K -> partial [128,32768]
+  reduce_gates  that partial + 7 remote partials -> gates                       (partition-n-reduce)
+  conv_cout     3x3 conv 2560->2560 @14x14, batch 128: shard 3 of an 8-way C_out split
+  fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
+  conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
+  wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
+  reduce_dw     that partial + 7 remote partials -> dW                           (partition-n-reduce)
+
+This module holds no arithmetic of the method (ranges and regions come from the library) and
+does not import the oracle; tests and the bench's baseline leg bring the oracle themselves and
+use the host copies kept in `Leg.host` to evaluate expected values.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List
+
+import numpy as np
+import torch
+
+import paper_1807_08887_amd as tofu
+import tofu_synth as synth
+
+
+@dataclass
+class Leg:
+    name: str
+    bound: str                 # "mfma" or "hbm"
+    work: float                # algorithmic FLOP (mfma) or bytes (hbm) per launch
+    run: Callable[[], None]
+    out: torch.Tensor          # device tensor the leg writes (full buffer)
+    host: Dict[str, object] = field(default_factory=dict)   # host arrays / parameters for checking
+    conventional_flop: float = 0.0                            # dense 9-tap count, for reference
+
+
+def _conv_valid_taps(h_lo, h_hi, w_lo, w_hi, H, W, pad=1):
+    """Number of (position, tap) pairs of a 3x3 stride-1 conv that read inside the input."""
+    rows = sum(sum(1 for kh in range(3) if 0 <= h + kh - pad < H) for h in range(h_lo, h_hi))
+    cols = sum(sum(1 for kw in range(3) if 0 <= w + kw - pad < W) for w in range(w_lo, w_hi))
+    return rows * cols
+
+
+def _call(fn, *args):
+    """Bind the arguments now (the builder reuses local names for several legs)."""
+    return lambda: fn(*args)
+
+
+def _ws(op, splits, dev):
+    n = tofu.workspace_bytes(op, splits)
+    return torch.empty(n // 4, dtype=torch.float32, device=dev) if n else None
+
+
+def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
+    which = set(which) if which else None
+    want = lambda *names: which is None or any(n in which for n in names)
+    legs: List[Leg] = []
+    up = lambda a: torch.from_numpy(a).to(dev)
+
+    # ------------------------------------------------------------------ LSTM gate GEMM
+    if want("gemm_nsplit", "gemm_ksplit", "reduce_gates"):
+        M, N, K, k = 128, 32768, 16384, 8
+        op = tofu.matmul_desc(M, N, K)
+    if want("gemm_nsplit"):
+        cfg = synth.CONFIGS["lstm_gates_nsplit"]
+        s = cfg["shard"]
+        splits = [(tofu.MM_DIM_N, k, s)]
+        reg = tofu.op_regions(op, splits)
+        (n0, n1) = reg["out_box"][1]
+        X = synth.draw(cfg["a"], cfg["seed"], 0, (M, K))
+        Ws = synth.draw(cfg["b"], cfg["seed"], 1, (K, n1 - n0))          # the worker's own dense block of W
+        dX, dW, C = up(X), up(Ws), torch.zeros(M, N, dtype=torch.float32, device=dev)
+        ws = _ws(op, splits, dev)
+        tA, tB, tC = tofu.tensor(dX), tofu.tensor(dW, [0, n0]), tofu.tensor(C)
+        legs.append(Leg("gemm_nsplit", "mfma", 2.0 * M * (n1 - n0) * K,
+                        _call(tofu.shard_matmul, op, splits, tA, tB, tC, ws), C,
+                        dict(kind="matmul", A=X, B=Ws, box=reg["out_box"], krange=(0, K), b_col0=n0, keep=(dX, dW, ws)) if keep_host else dict(keep=(dX, dW, ws))))
+    if want("gemm_ksplit", "reduce_gates"):
+        cfg = synth.CONFIGS["lstm_gates_ksplit"]
+        s = cfg["shard"]
+        splits = [(tofu.MM_DIM_K, k, s)]
+        reg = tofu.op_regions(op, splits)
+        (k0, k1) = reg["in_boxes"][0][1]
+        X = synth.draw(cfg["a"], cfg["seed"], 0, (M, K))
+        Wr = synth.draw(cfg["b"], cfg["seed"], 1, (k1 - k0, N))           # the worker's own rows of W
+        dX, dW = up(X), up(Wr)
+        part = torch.zeros(M, N, dtype=torch.float32, device=dev)
+        ws = _ws(op, splits, dev)
+        tA, tB, tC = tofu.tensor(dX), tofu.tensor(dW, [k0, 0]), tofu.tensor(part)   # X is read strided, in place
+        legs.append(Leg("gemm_ksplit", "mfma", 2.0 * M * N * (k1 - k0),
+                        _call(tofu.shard_matmul, op, splits, tA, tB, tC, ws), part,
+                        dict(kind="matmul", A=X, B=Wr, box=reg["out_box"], krange=(k0, k1), b_row0=k0, keep=(dX, dW, ws)) if keep_host else dict(keep=(dX, dW, ws))))
+        if want("reduce_gates"):
+            remote = [synth.normal(cfg["seed"], 10 + j, (M, N), cfg["partial_std"]) for j in range(k - 1)]
+            d_remote = [up(r) for r in remote]
+            gates = torch.zeros(M, N, dtype=torch.float32, device=dev)
+            order = d_remote[:s] + [part] + d_remote[s:]                  # worker s's partial sits at position s
+            legs.append(Leg("reduce_gates", "hbm", 4.0 * M * N * (k + 1),
+                            _call(tofu.partition_reduce, gates, order), gates,
+                            dict(kind="reduce", remote=remote, own_index=s, own=part, keep=order) if keep_host else dict(keep=order)))
+
+    # ------------------------------------------------------------------ Wide-ResNet conv forward
+    if want("conv_cout", "fetch_halo", "conv_cout_h"):
+        cfg = synth.CONFIGS["wresnet_conv_fwd"]
+        NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
+        op = tofu.conv2d_desc(NB, C, C, H, W)
+        x = synth.draw(cfg["x"], cfg["seed"], 0, (NB, C, H, W))
+        sp_co = [(tofu.CONV_DIM_CO, k, s)]
+        reg = tofu.op_regions(op, sp_co)
+        (co0, co1) = reg["out_box"][1]
+        w_s = synth.draw(cfg["w"], cfg["seed"], 1, (co1 - co0, C, 3, 3))  # the worker's own filters
+        dx, dw = up(x), up(w_s)
+        tw = tofu.tensor(dw, [co0, 0, 0, 0])
+        host_common = dict(kind="conv2d", x=x, w=w_s, co0=co0) if keep_host else {}
+    if want("conv_cout"):
+        y = torch.zeros(NB, co1 - co0, H, W, dtype=torch.float32, device=dev)
+        tx, ty = tofu.tensor(dx), tofu.tensor(y, [0, co0, 0, 0])
+        taps = _conv_valid_taps(0, H, 0, W, H, W)
+        legs.append(Leg("conv_cout", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
+                        _call(tofu.shard_conv2d, op, sp_co, tx, tw, ty), y,
+                        dict(host_common, box=reg["out_box"], keep=(dx, dw)), conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * H * W))
+    if want("fetch_halo", "conv_cout_h"):
+        sp = sp_co + [(tofu.CONV_DIM_H, cfg["k_h"], cfg["shard_h"])]
+        reg2 = tofu.op_regions(op, sp)
+        box = reg2["in_boxes"][0]                                       # rows [0,8) of the input
+        _, h_cut = tofu.shard_range(H, cfg["k_h"], cfg["shard_h"])           # rows [0, h_cut) are this worker's own block
+        own = dx[:, :, :h_cut].contiguous()                               # rows this worker owns
+        halo = dx[:, :, h_cut:h_cut + 1].contiguous()                     # the neighbour's block (only its first row is needed)
+        region = torch.zeros([hi - lo for lo, hi in box], dtype=torch.float32, device=dev)
+        t_region = tofu.tensor(region, [lo for lo, _ in box])
+        srcs = [tofu.tensor(own, [0, 0, 0, 0]), tofu.tensor(halo, [0, 0, h_cut, 0])]
+        nbytes = 2.0 * 4.0 * region.numel()
+        if want("fetch_halo"):
+            legs.append(Leg("fetch_halo", "hbm", nbytes, _call(tofu.region_fetch, t_region, srcs), region,
+                            dict(kind="fetch", x=x if keep_host else None, box=box, keep=(own, halo))))
+        if want("conv_cout_h"):
+            (h0, h1) = reg2["out_box"][2]
+            y2 = torch.zeros(NB, co1 - co0, h1 - h0, W, dtype=torch.float32, device=dev)
+            ty2 = tofu.tensor(y2, [0, co0, h0, 0])
+            taps = _conv_valid_taps(h0, h1, 0, W, H, W)
+            if not want("fetch_halo"):
+                tofu.region_fetch(t_region, srcs)
+            legs.append(Leg("conv_cout_h", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
+                            _call(tofu.shard_conv2d, op, sp, t_region, tw, ty2), y2,
+                            dict(host_common, box=reg2["out_box"], keep=(region, dw, own, halo)),
+                            conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
+
+    # ------------------------------------------------------------------ Wide-ResNet conv weight gradient
+    if want("wgrad_batch", "reduce_dw"):
+        cfg = synth.CONFIGS["wresnet_conv_wgrad"]
+        NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
+        opw = tofu.wgrad_desc(NB, C, C, H, W)
+        splits_w = [(tofu.WGRAD_DIM_N, k, s)]
+        regw = tofu.op_regions(opw, splits_w)
+        (n0, n1) = regw["in_boxes"][0][0]
+        xs_ = synth.draw(cfg["x"], cfg["seed"], 0, (n1 - n0, C, H, W))   # the worker's own images
+        dys = synth.draw(cfg["dy"], cfg["seed"], 1, (n1 - n0, C, H, W))
+        dxs, ddys = up(xs_), up(dys)
+        part_w = torch.zeros(C, C, 3, 3, dtype=torch.float32, device=dev)
+        wsw = _ws(opw, splits_w, dev)
+        txw, tdy, tdw = tofu.tensor(dxs, [n0, 0, 0, 0]), tofu.tensor(ddys, [n0, 0, 0, 0]), tofu.tensor(part_w)
+        taps = _conv_valid_taps(0, H, 0, W, H, W)
+        legs.append(Leg("wgrad_batch", "mfma", 2.0 * (n1 - n0) * C * C * taps,
+                        _call(tofu.shard_conv2d_wgrad, opw, splits_w, txw, tdy, tdw, wsw), part_w,
+                        dict(kind="wgrad", x=xs_, dy=dys, n0=n0, keep=(dxs, ddys, wsw)) if keep_host else dict(keep=(dxs, ddys, wsw)),
+                        conventional_flop=2.0 * (n1 - n0) * C * C * 9 * H * W))
+        if want("reduce_dw"):
+            remote = [synth.normal(cfg["seed"], 10 + j, (C, C, 3, 3), cfg["partial_std"]) for j in range(k - 1)]
+            d_remote = [up(r) for r in remote]
+            dw_full = torch.zeros(C, C, 3, 3, dtype=torch.float32, device=dev)
+            order = d_remote[:s] + [part_w] + d_remote[s:]
+            legs.append(Leg("reduce_dw", "hbm", 4.0 * C * C * 9 * (k + 1),
+                            _call(tofu.partition_reduce, dw_full, order), dw_full,
+                            dict(kind="reduce", remote=remote, own_index=s, own=part_w, keep=order) if keep_host else dict(keep=order)))
+    return legs
