@@ -29,6 +29,7 @@ struct ConvArgs {
   const float* w;   // element (co_lo, ci_lo, 0, 0)
   float* y;         // element at the low corner of the output box
   int64_t xs[4], ws[4], ys[4];   // element strides (n, c, h, w) / (co, ci, kh, kw) / (n, co, h, w)
+  uint32_t x_bytes, w_bytes;     // bytes spanned by the input box / the filter box (buffer bounds)
   int NB, CO, CI;   // images, output channels and input channels of the shard
   int BH, BW;       // output box rows / columns
   int IH, IW;       // rows / columns of the clipped input box
@@ -37,7 +38,7 @@ struct ConvArgs {
   int tiles_m, tiles_n;
   int LDW;          // floats per staged row  (BW + 2)
   int PL;           // floats per staged channel plane
-  int E;            // staged floats per channel actually used (<= PL)
+  int E;            // upper bound over all tiles of the staged floats per channel (<= PL)
   int w_fast;       // 1: weights dense over (ci,kh,kw) and 16-byte aligned -> vector loads
 };
 
@@ -46,19 +47,39 @@ struct ConvCfg {
   static constexpr int kThreads = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
   static constexpr int KK = CK * 9;            // GEMM-K per step
-  static constexpr int LDM = BM + 4;           // Ws[kk][m]
+  static constexpr int LDM = BM + 1;           // Ws[kk][m]; odd pitch keeps the transposing writes spread over the banks
   static constexpr int WV = (BM * KK / 4 + kThreads - 1) / kThreads;   // weight vectors per thread per step
+  // each LDS buffer ends with scratch floats that absorb the writes of idle staging slots
+  static constexpr int WB = KK * LDM + 3 * LDM + 64;                   // floats per weight buffer
+  static int xb(int PL) { return CK * PL + 64; }                       // floats per input buffer
   static_assert(TM % 32 == 0 && TN % 32 == 0 && CK % 4 == 0, "bad tile");
+  static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
+// Raw buffer loads: the descriptor carries base and size, a lane supplies a 32-bit byte offset
+// and an out-of-range offset (0xFFFFFFFF marks zero padding and idle slots) reads as 0 without
+// a branch; a scalar offset moves the whole wavefront to the current channel step.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ v4f32 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(v4f32, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+}
+
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
-__global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) {
+__global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
+  constexpr uint32_t kNone = 0xFFFFFFFFu;
   extern __shared__ float lds[];
-  float* Ws = lds;                           // [2][KK][LDM]
-  float* Xs = lds + 2 * KK * LDM;            // [2][CK][PL]
   const int PL = p.PL, LDW = p.LDW;
+  constexpr int WB = Cfg::WB;
+  const int XB = CK * PL + 64;
+  float* Ws = lds;                           // [2][WB]: KK rows of LDM floats + scratch
+  float* Xs = lds + 2 * WB;                  // [2][XB]: CK planes of PL floats + scratch
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -68,7 +89,7 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) 
   // consecutive logical tiles (which share staged input rows) land on the same XCD's L2.
   const int total = p.tiles_m * p.tiles_n;
   const int per_xcd = (total + 7) / 8;
-  int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (lid >= total) return;                   // grid is padded to a multiple of 8
   const int tile_n = lid / p.tiles_m, tile_m = lid % p.tiles_m;
   const int m0 = tile_m * BM;
@@ -81,75 +102,78 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) 
   const int ra = p_begin / p.BW, rb = (p_end - 1) / p.BW;
   const int T_a = (ra / p.BH) * img_rows + ra % p.BH;
   const int T_b = (rb / p.BH) * img_rows + rb % p.BH + 2;
-  const int nslots = T_b - T_a + 1;
+  const int E = (T_b - T_a + 1) * LDW;        // staged floats per channel for this tile
 
-  // ---- per-thread staging lists (fixed for the whole K loop) ----
-  int x_goff[XJ], x_loff[XJ];
-  const int E = nslots * LDW;
+  // ---- per-thread staging lists, fixed for the whole K loop ----
+  uint32_t x_voff[XJ];   // byte offset of the element inside channel step 0, kNone = reads as zero
+  int x_loff[XJ];        // LDS float index inside one x buffer (or its scratch tail)
 #pragma unroll
   for (int j = 0; j < XJ; ++j) {
-    int idx = tid + j * NT;
-    int ci_l = idx / p.E, rem = idx - ci_l * p.E;   // p.E = host-side upper bound of E: fixed divisor for all tiles
-    int s = rem / LDW, c = rem - s * LDW;
-    int V = T_a + s;
-    int img = V / img_rows, u = V - img * img_rows;
-    int ih = u - p.plh, iw = c - p.plw;
-    bool live = ci_l < CK && rem < E;               // this thread writes LDS for that element
-    bool valid = live && img < p.NB && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
-    x_loff[j] = live ? ci_l * PL + rem : -1;
-    x_goff[j] = valid ? (int)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : -1;
+    const int idx = tid + j * NT;
+    const int ci_l = idx / p.E, rem = idx - ci_l * p.E;
+    const int s = rem / LDW, c = rem - s * LDW;
+    const int V = T_a + s;
+    const int img = V / img_rows, u = V - img * img_rows;
+    const int ih = u - p.plh, iw = c - p.plw;
+    const bool live = ci_l < CK && rem < E;
+    const bool valid = live && img < p.NB && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
+    x_loff[j] = live ? ci_l * PL + rem : CK * PL + lane;
+    x_voff[j] = valid ? 4u * (uint32_t)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : kNone;
   }
+  uint32_t w_voff[WV];
+  int w_loff[WV];
+#pragma unroll
+  for (int i = 0; i < WV; ++i) {
+    const int idx = tid + i * NT, row = idx / (KK / 4), q = idx - row * (KK / 4);
+    const bool live = idx < BM * KK / 4;
+    w_loff[i] = live ? 4 * q * LDM + row : KK * LDM + lane;
+    w_voff[i] = (live && m0 + row < p.CO) ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ws[0] + 4 * q) : kNone;
+  }
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.w, p.w_bytes);
 
   float rx[XJ];
   v4f32 rw[WV];
   auto load_global = [&](int step) {
     const int ci0 = step * CK;
-    const float* xb = p.x + (int64_t)ci0 * p.xs[1];
-    const bool ci_tail = ci0 + CK > p.CI;      // only the last step can run past the shard's channels
+    const bool whole = ci0 + CK <= p.CI;        // only the last step can run past the shard's channels
+    const uint32_t x_soff = 4u * (uint32_t)((int64_t)ci0 * p.xs[1]);
+    if (whole) {
 #pragma unroll
-    for (int j = 0; j < XJ; ++j) {
-      int g = x_goff[j];
-      bool ok = g >= 0 && (!ci_tail || ci0 + (tid + j * NT) / p.E < p.CI);
-      rx[j] = ok ? xb[g] : 0.f;
-    }
-    if (p.w_fast && m0 + BM <= p.CO && ci0 + CK <= p.CI) {
+      for (int j = 0; j < XJ; ++j) rx[j] = buf_load(x_rsrc, x_voff[j], x_soff);
+    } else {
 #pragma unroll
-      for (int i = 0; i < WV; ++i) {
-        int idx = tid + i * NT;
-        if (idx < BM * KK / 4) {
-          int row = idx / (KK / 4), q = idx - row * (KK / 4);
-          rw[i] = *reinterpret_cast<const v4f32*>(p.w + (int64_t)(m0 + row) * p.ws[0] + (int64_t)ci0 * 9 + 4 * q);
-        }
+      for (int j = 0; j < XJ; ++j) {
+        const bool ok = ci0 + (tid + j * NT) / p.E < p.CI;
+        rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNone, x_soff);
       }
+    }
+    if (p.w_fast && whole) {
+      const uint32_t w_soff = 36u * (uint32_t)ci0;
+#pragma unroll
+      for (int i = 0; i < WV; ++i) rw[i] = buf_load4(w_rsrc, w_voff[i], w_soff);
     } else {
 #pragma unroll
       for (int i = 0; i < WV; ++i) {
-        int idx = tid + i * NT;
-        int row = idx / (KK / 4), q = idx - row * (KK / 4);
+        const int idx = tid + i * NT, row = idx / (KK / 4), q = idx - row * (KK / 4);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          int kk = 4 * q + jj, ci_l = kk / 9, tap = kk - ci_l * 9, kh = tap / 3, kw = tap - kh * 3;
-          bool ok = idx < BM * KK / 4 && m0 + row < p.CO && ci0 + ci_l < p.CI;
+          const int kk = 4 * q + jj, ci_l = kk / 9, tap = kk - ci_l * 9, kh = tap / 3, kw = tap - kh * 3;
+          const bool ok = idx < BM * KK / 4 && m0 + row < p.CO && ci0 + ci_l < p.CI;
           rw[i][jj] = ok ? p.w[(int64_t)(m0 + row) * p.ws[0] + (int64_t)(ci0 + ci_l) * p.ws[1] + kh * p.ws[2] + kw * p.ws[3]] : 0.f;
         }
       }
     }
   };
   auto store_lds = [&](int buf) {
-    float* xs = Xs + buf * CK * PL;
-    float* wsm = Ws + buf * KK * LDM;
+    float* xs = Xs + buf * XB;
+    float* wsm = Ws + buf * WB;
 #pragma unroll
-    for (int j = 0; j < XJ; ++j)
-      if (x_loff[j] >= 0) xs[x_loff[j]] = rx[j];
+    for (int j = 0; j < XJ; ++j) xs[x_loff[j]] = rx[j];
 #pragma unroll
-    for (int i = 0; i < WV; ++i) {
-      int idx = tid + i * NT;
-      if (idx < BM * KK / 4) {
-        int row = idx / (KK / 4), q = idx - row * (KK / 4);
+    for (int i = 0; i < WV; ++i)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) wsm[(4 * q + jj) * LDM + row] = rw[i][jj];
-      }
-    }
+      for (int jj = 0; jj < 4; ++jj) wsm[w_loff[i] + jj * LDM] = rw[i][jj];
   };
 
   // ---- per-lane position of each N block: LDS offset of tap (0,0) and output offset ----
@@ -161,7 +185,7 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) 
     int pp = p_begin + wn * Cfg::TN + j * 32 + l32;
     pos_ok[j] = pp < p_end;
     if (!pos_ok[j]) pp = p_end - 1;          // keep the address inside the staged rows
-    int img = pp / plane, q = pp - img * plane, oh = q / p.BW, ow = q - oh * p.BW;
+    const int img = pp / plane, q = pp - img * plane, oh = q / p.BW, ow = q - oh * p.BW;
     pos_l[j] = (img * img_rows + oh - T_a) * LDW + ow + half * PL;
     y_off[j] = (int64_t)img * p.ys[0] + (int64_t)oh * p.ys[2] + (int64_t)ow * p.ys[3];
   }
@@ -179,8 +203,8 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) 
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
     if (t + 1 < steps) load_global(t + 1);
-    const float* wsm = Ws + buf * KK * LDM + wm * Cfg::TM + l32 + half * 9 * LDM;
-    const float* xs = Xs + buf * CK * PL;
+    const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * 9 * LDM;
+    const float* xs = Xs + buf * XB;
 #pragma unroll
     for (int cp = 0; cp < CK / 2; ++cp) {
 #pragma unroll
@@ -216,8 +240,42 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_kernel(const ConvArgs p) 
     }
 }
 
-constexpr int cBM = 64, cBN = 128, cCK = 8, cWM = 2, cWN = 2, cXJ = 10;
 constexpr size_t kLdsLimit = 160 * 1024;
+
+// Most floats per channel any tile of BN consecutive positions stages (rows touched + halo rows).
+static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN) {
+  int64_t max_slots = 0;
+  for (int64_t pb = 0; pb < P; pb += BN) {
+    const int64_t pe = pb + BN < P ? pb + BN : P;
+    const int64_t ra = pb / BW, rb = (pe - 1) / BW;
+    const int64_t slots = ((rb / BH) * (BH + 2) + rb % BH + 2) - ((ra / BH) * (BH + 2) + ra % BH) + 1;
+    if (slots > max_slots) max_slots = slots;
+  }
+  return max_slots * (BW + 2);
+}
+
+template <int BM, int BN, int CK, int WM, int WN, int XJ>
+static int launch_conv(ConvArgs p, int64_t E, hipStream_t stream) {
+  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
+  p.tiles_m = (p.CO + BM - 1) / BM;
+  p.tiles_n = (p.P + BN - 1) / BN;
+  p.E = (int)E;
+  p.PL = (p.E + 63) / 64 * 64 + 32;
+  const size_t lds_bytes = sizeof(float) * Cfg::lds_floats(p.PL);
+  if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
+  auto kern = conv2d_kernel<BM, BN, CK, WM, WN, XJ>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  const int total = p.tiles_m * p.tiles_n;
+  hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d launch failed: %s", hipGetErrorString(e));
+  return TOFU_OK;
+}
 
 }  // namespace tofu
 
@@ -253,45 +311,32 @@ extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* s
   const int64_t CI = in_boxes[0].hi[1] - in_boxes[0].lo[1];
   const int64_t P = NB * BH * BW;
   if (P >= (1 << 30) || CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
-  // per-thread input offsets are 32-bit: the input box must span fewer than 2^31 elements
-  int64_t span = 1;
-  for (int d = 0; d < 4; ++d) span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * (xs[d] < 0 ? -xs[d] : xs[d]);
-  if (span >= ((int64_t)1 << 31)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d input region spans 2^31 or more elements");
+  // lanes address the input and the filters with 32-bit byte offsets from the boxes' low corners
+  int64_t x_span = 1, w_span = 1;
+  for (int d = 0; d < 4; ++d) {
+    if (xs[d] < 0 || ws[d] < 0) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: negative strides are not supported");
+    x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
+    w_span += (in_boxes[1].hi[d] - in_boxes[1].lo[d] - 1) * ws[d];
+  }
+  if (x_span >= ((int64_t)1 << 29) || w_span >= ((int64_t)1 << 29))
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: an operand region spans 2 GiB or more");
+  p.x_bytes = (uint32_t)(4 * x_span);
+  p.w_bytes = (uint32_t)(4 * w_span);
   p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
   p.IH = (int)(in_boxes[0].hi[2] - in_boxes[0].lo[2]);
   p.IW = (int)(in_boxes[0].hi[3] - in_boxes[0].lo[3]);
   p.plh = (int)pad_lo[0]; p.plw = (int)pad_lo[1];
-  p.tiles_m = (int)((CO + cBM - 1) / cBM);
-  p.tiles_n = (int)((P + cBN - 1) / cBN);
   p.LDW = (int)BW + 2;
-  // most virtual rows any tile can touch: cBN consecutive positions
-  int64_t max_slots = 0;
-  for (int64_t t = 0; t < p.tiles_n; ++t) {
-    int64_t pb = t * cBN, pe = pb + cBN < P ? pb + cBN : P;
-    int64_t ra = pb / BW, rb = (pe - 1) / BW;
-    int64_t slots = ((rb / BH) * (BH + 2) + rb % BH + 2) - ((ra / BH) * (BH + 2) + ra % BH) + 1;
-    if (slots > max_slots) max_slots = slots;
-  }
-  p.E = (int)(max_slots * p.LDW);
-  p.PL = (p.E + 63) / 64 * 64 + 32;   // odd multiple of 32 floats: the two half-waves read different banks
-  using Cfg = ConvCfg<cBM, cBN, cCK, cWM, cWN, cXJ>;
-  if ((int64_t)cCK * p.E > (int64_t)cXJ * Cfg::kThreads)
-    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)p.E);
-  const size_t lds_bytes = sizeof(float) * 2 * ((size_t)Cfg::KK * Cfg::LDM + (size_t)cCK * p.PL);
-  if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
   p.w_fast = ws[3] == 1 && ws[2] == 3 && ws[1] == 9 && ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-  auto kern = conv2d_kernel<cBM, cBN, cCK, cWM, cWN, cXJ>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
-    attr_set = true;
-  }
-  const int total = p.tiles_m * p.tiles_n;
-  const int grid = (total + 7) / 8 * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), lds_bytes, static_cast<hipStream_t>(hip_stream), p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d launch failed: %s", hipGetErrorString(e));
-  return TOFU_OK;
+  // Tile choice: 256 positions per workgroup (64x64 per wavefront) when that still leaves about two
+  // workgroups for each of the 256 compute units, else 128 positions; fewer channels per step
+  // when the staged rows are wide.
+  const int64_t tiles_m = (CO + 63) / 64;
+  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
+  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, E256, stream);
+  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, E128, stream);
+  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, E128, stream);
+  return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)E128);
 }
