@@ -56,24 +56,11 @@ struct ConvCfg {
   static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
-// Raw buffer loads: the descriptor carries base and size, a lane supplies a 32-bit byte offset
-// and an out-of-range offset (0xFFFFFFFF marks zero padding and idle slots) reads as 0 without
-// a branch; a scalar offset moves the whole wavefront to the current channel step.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
-}
-__device__ __forceinline__ v4f32 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-  return __builtin_bit_cast(v4f32, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
-}
-
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
-  constexpr uint32_t kNone = 0xFFFFFFFFu;
+  constexpr uint32_t kNone = kNoOffset;
   extern __shared__ float lds[];
   const int PL = p.PL, LDW = p.LDW;
   constexpr int WB = Cfg::WB;

@@ -27,6 +27,7 @@ struct WgradArgs {
   float* out;        // dw element (co_lo, ci_lo, 0, 0), or the workspace when slices > 1
   int64_t xs[4], ds[4], os[4];   // element strides: x (n,c,h,w), dy (n,co,h,w), out (co,ci,kh,kw)
   int64_t slice_stride;          // floats between slices in the workspace
+  uint32_t x_bytes, dy_bytes;    // bytes spanned by the two input boxes (buffer bounds, fast path)
   int NB, CO, CI;    // images, output channels, input channels of the shard
   int HO, WO;        // output rows / columns
   int IH, IW;        // rows / columns of the clipped input box
@@ -36,20 +37,27 @@ struct WgradArgs {
   int CW;            // output columns per K step (<= 32, multiple of 4 unless WO itself is not)
   int chunks;        // column chunks per output row
   int to_workspace;  // 1: write [tap][co][ci] slices to the workspace
-  int fast;          // 1: rows of dy are contiguous and 16-byte aligned -> vector loads
+  int vec;           // 1: rows of dy are contiguous and 16-byte aligned -> vector loads (generic path)
 };
 
 // LDS geometry is fixed so that every staging index splits with compile-time divisors.
 constexpr int kKR = 32;              // dy positions per K step (a chunk of one output row)
 constexpr int kLDW = kKR + 2;        // staged x columns per row: chunk widened by the filter window
-constexpr int kPLX = 3 * kLDW + 1;   // staged floats per input channel; odd -> 32 channels hit 32 banks
+constexpr int kPLX = 3 * kLDW + 3;   // staged floats per input channel; odd -> 32 channels hit 32 banks
 
-template <int BM, int BCI>
-__global__ void __launch_bounds__(64 * (BM / 32)) wgrad_kernel(const WgradArgs p) {
-  constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 4;
+// FAST: one chunk per output row, dy rows are whole aligned vectors, every operand offset fits
+// 32 bits.  Then each lane's staging addresses are fixed byte offsets, a step only changes a
+// scalar offset, and all padding comes from out-of-range buffer reads -- no branches, no
+// per-step index arithmetic.  Otherwise a generic guarded path is used.
+template <int BM, int BCI, bool FAST>
+__global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(const WgradArgs p) {
+  constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 2;
   constexpr int D_ITEMS = BM * (kKR / 4), X_ITEMS = BCI * 3 * kLDW;
   constexpr int DJ = (D_ITEMS + NT - 1) / NT, XJ = (X_ITEMS + NT - 1) / NT;
-  static_assert(BCI == 32, "one 32-lane block of input channels per workgroup");
+  constexpr int TPC = NT / BCI;                 // threads that stage one input channel (fast path)
+  constexpr int XF = (3 * kLDW + TPC - 1) / TPC;  // elements per such thread
+  static_assert(BCI == 32 && NT % BCI == 0 && D_ITEMS % NT == 0, "staging maps assume 32 input channels and whole passes");
+  static_assert(XF * TPC <= kPLX, "idle fast-path slots must land in the plane's padding");
   __shared__ float Ds[2][kKR][LDD];        // dy chunk, k-major: Ds[column][co]
   __shared__ float Xs[2][BCI * kPLX];      // x rows h-pad..h-pad+2 of the chunk, zero border included
 
@@ -66,20 +74,56 @@ __global__ void __launch_bounds__(64 * (BM / 32)) wgrad_kernel(const WgradArgs p
   const int steps = (n_end - n_begin) * p.HO * p.chunks;
   const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
 
+  // ---- fast-path staging maps ----
+  // dy: thread -> (row = tid/8 + 32*j, columns 4*(tid%8) .. +3); x: thread -> (channel tid/TPC, elements tid%TPC + TPC*j)
+  const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
+  const int x_ci = tid / TPC, x_sub = tid % TPC;
+  uint32_t d_voff[DJ], x_voff[XF];
+  int x_r[XF];
+  if (FAST) {
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+      const int row = d_row + j * (NT / (kKR / 4));
+      d_voff[j] = (m0 + row < p.CO && 4 * d_q < p.WO) ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ds[1] + 4 * d_q) : kNoOffset;
+    }
+#pragma unroll
+    for (int j = 0; j < XF; ++j) {
+      const int e = x_sub + TPC * j, r = e / kLDW, c = e - r * kLDW, iw = c - p.plw;
+      const bool ok = e < 3 * kLDW && c0 + x_ci < p.CI && iw >= 0 && iw < p.IW;
+      x_r[j] = r;
+      // row offset r*xs2 is relative to input row (oh - plh); the buffer base is moved back by plh rows
+      x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)iw * p.xs[3]) : kNoOffset;
+    }
+  }
+  const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x - (int64_t)p.plh * p.xs[2], p.x_bytes + 4u * (uint32_t)(p.plh * p.xs[2]));
+
   v4f32 rd[DJ];
-  float rx[XJ];
+  float rx[FAST ? XF : XJ];
   auto load_global = [&](int step) {
     const int row_id = step / p.chunks, chunk = step - row_id * p.chunks;
     const int n = n_begin + row_id / p.HO, oh = row_id - (row_id / p.HO) * p.HO;
+    if (FAST) {
+      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
+      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
+#pragma unroll
+      for (int j = 0; j < DJ; ++j) rd[j] = buf_load4(d_rsrc, d_voff[j], d_soff);
+#pragma unroll
+      for (int j = 0; j < XF; ++j) {
+        const bool row_ok = (unsigned)(oh + x_r[j] - p.plh) < (unsigned)p.IH;
+        rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
+      }
+      return;
+    }
     const int cw0 = chunk * p.CW;
     const float* db = p.dy + (int64_t)n * p.ds[0] + (int64_t)m0 * p.ds[1] + (int64_t)oh * p.ds[2] + (int64_t)cw0 * p.ds[3];
     const float* xb = p.x + (int64_t)n * p.xs[0] + (int64_t)c0 * p.xs[1];
 #pragma unroll
     for (int j = 0; j < DJ; ++j) {
       const int idx = tid + j * NT, row = idx / (kKR / 4), q = idx % (kKR / 4);
-      const bool row_ok = idx < D_ITEMS && m0 + row < p.CO;
+      const bool row_ok = m0 + row < p.CO;
       const int col = 4 * q;                   // first of four columns, relative to the chunk
-      if (p.fast && row_ok && col + 3 < p.CW && cw0 + col + 3 < p.WO) {
+      if (p.vec && row_ok && col + 3 < p.CW && cw0 + col + 3 < p.WO) {
         rd[j] = *reinterpret_cast<const v4f32*>(db + (int64_t)row * p.ds[1] + col);
       } else {
 #pragma unroll
@@ -90,7 +134,7 @@ __global__ void __launch_bounds__(64 * (BM / 32)) wgrad_kernel(const WgradArgs p
       }
     }
 #pragma unroll
-    for (int j = 0; j < XJ; ++j) {
+    for (int j = 0; j < (FAST ? 0 : XJ); ++j) {
       const int idx = tid + j * NT, ci_l = idx / (3 * kLDW), rem = idx % (3 * kLDW), r = rem / kLDW, c = rem % kLDW;
       const int ih = oh + r - p.plh, iw = cw0 + c - p.plw;
       const bool ok = idx < X_ITEMS && c0 + ci_l < p.CI && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
@@ -100,16 +144,19 @@ __global__ void __launch_bounds__(64 * (BM / 32)) wgrad_kernel(const WgradArgs p
   auto store_lds = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < DJ; ++j) {
-      const int idx = tid + j * NT, row = idx / (kKR / 4), q = idx % (kKR / 4);
-      if (idx < D_ITEMS) {
+      const int row = d_row + j * (NT / (kKR / 4));
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) Ds[buf][4 * q + jj][row] = rd[j][jj];
-      }
+      for (int jj = 0; jj < 4; ++jj) Ds[buf][4 * d_q + jj][row] = rd[j][jj];
     }
+    if (FAST) {
 #pragma unroll
-    for (int j = 0; j < XJ; ++j) {
-      const int idx = tid + j * NT, ci_l = idx / (3 * kLDW), rem = idx % (3 * kLDW);
-      if (idx < X_ITEMS) Xs[buf][ci_l * kPLX + rem] = rx[j];
+      for (int j = 0; j < XF; ++j) Xs[buf][x_ci * kPLX + x_sub + TPC * j] = rx[j];   // slots past 3*kLDW fall in the plane's padding
+    } else {
+#pragma unroll
+      for (int j = 0; j < (FAST ? 0 : XJ); ++j) {
+        const int idx = tid + j * NT, ci_l = idx / (3 * kLDW), rem = idx % (3 * kLDW);
+        if (idx < X_ITEMS) Xs[buf][ci_l * kPLX + rem] = rx[j];
+      }
     }
   };
 
@@ -247,8 +294,19 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   p.chunks = (int)((WO + kKR - 1) / kKR);
   p.CW = (int)((WO + p.chunks - 1) / p.chunks);
   if (p.chunks > 1) p.CW = (p.CW + 3) / 4 * 4;
-  p.fast = ds[3] == 1 && ds[1] % 4 == 0 && ds[2] % 4 == 0 && ds[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
+  p.vec = ds[3] == 1 && ds[1] % 4 == 0 && ds[2] % 4 == 0 && ds[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
   const int NT = 64 * (gBM / 32);
+  // fast path: buffer loads with 32-bit byte offsets from the boxes' low corners
+  int64_t x_span = 1, d_span = 1;
+  bool nonneg = true;
+  for (int d = 0; d < 4; ++d) {
+    nonneg = nonneg && xs[d] >= 0 && ds[d] >= 0;
+    x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
+    d_span += (in_boxes[1].hi[d] - in_boxes[1].lo[d] - 1) * ds[d];
+  }
+  const bool fast = nonneg && p.vec && p.chunks == 1 && WO % 4 == 0 && x_span + p.plh * xs[2] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
+  p.x_bytes = fast ? (uint32_t)(4 * x_span) : 0;
+  p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
   const int slices = wgrad_split_n(CO, CI, NB, HO);
   p.n_per_slice = (int)((NB + slices - 1) / slices);
   p.to_workspace = slices > 1;
@@ -261,7 +319,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   } else {
     p.out = dw_out;
   }
-  auto kern = wgrad_kernel<gBM, gBCI>;
+  auto kern = fast ? wgrad_kernel<gBM, gBCI, true> : wgrad_kernel<gBM, gBCI, false>;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int total = p.tiles_m * p.tiles_n;
   hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8, slices), dim3(NT), 0, s, p);
