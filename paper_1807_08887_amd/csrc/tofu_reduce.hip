@@ -18,6 +18,23 @@ struct ReducePtrs {
   const float* p[kMaxReduceK];
 };
 
+#ifndef TOFU_REDUCE_NT_LOAD
+#define TOFU_REDUCE_NT_LOAD 1
+#endif
+#ifndef TOFU_REDUCE_MAX_BLOCKS
+#define TOFU_REDUCE_MAX_BLOCKS 16384
+#endif
+#ifndef TOFU_REDUCE_UNROLL8
+#define TOFU_REDUCE_UNROLL8 2
+#endif
+__device__ __forceinline__ v4f ld_stream(const v4f* p) {
+#if TOFU_REDUCE_NT_LOAD
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+
 template <int K, int UNROLL>
 __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, ReducePtrs src, int64_t n_vec, int64_t count) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -28,7 +45,7 @@ __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, Re
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-      for (int j = 0; j < K; ++j) v[u][j] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src.p[j]) + i + u * stride);
+      for (int j = 0; j < K; ++j) v[u][j] = ld_stream(reinterpret_cast<const v4f*>(src.p[j]) + i + u * stride);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       v4f acc = v[u][0];
@@ -38,9 +55,9 @@ __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, Re
     }
   }
   for (; i < n_vec; i += stride) {
-    v4f acc = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src.p[0]) + i);
+    v4f acc = ld_stream(reinterpret_cast<const v4f*>(src.p[0]) + i);
 #pragma unroll
-    for (int j = 1; j < K; ++j) acc += __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src.p[j]) + i);
+    for (int j = 1; j < K; ++j) acc += ld_stream(reinterpret_cast<const v4f*>(src.p[j]) + i);
     __builtin_nontemporal_store(acc, reinterpret_cast<v4f*>(dst) + i);
   }
   // scalar tail (count not a multiple of 4, or the whole array when pointers are not 16-byte aligned)
@@ -57,7 +74,7 @@ static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t c
   if (K <= 4)
     hipLaunchKernelGGL((reduce_kernel<K, 4>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
   else if (K <= 8)
-    hipLaunchKernelGGL((reduce_kernel<K, 2>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
+    hipLaunchKernelGGL((reduce_kernel<K, TOFU_REDUCE_UNROLL8>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
   else
     hipLaunchKernelGGL((reduce_kernel<K, 1>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
 }
@@ -74,7 +91,7 @@ int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, v
   // Enough resident lanes to cover HBM latency, few enough that every lane streams several vectors.
   int64_t work = n_vec > 0 ? n_vec : count;
   int64_t want = (work + 255) / 256;
-  int blocks = (int)(want < 4096 ? (want < 1 ? 1 : want) : 4096);
+  int blocks = (int)(want < TOFU_REDUCE_MAX_BLOCKS ? (want < 1 ? 1 : want) : TOFU_REDUCE_MAX_BLOCKS);
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (k) {
 #define TOFU_CASE(K) case K: launch_k<K>(dst, src, n_vec, count, blocks, s); break;
