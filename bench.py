@@ -34,7 +34,7 @@ def cpu_baseline(legs):
             continue
         if h["kind"] == "matmul":
             box = h["box"]
-            n = 1 << 14
+            n = 1 << 17 if "b_col0" in h else 1 << 19
             pts = synth.coords(900, 1, n, [b[1] - b[0] for b in box])
             k0, k1 = h["krange"]
             t = time.perf_counter()
@@ -46,7 +46,7 @@ def cpu_baseline(legs):
             flop += 2.0 * n * (k1 - k0)
             parts.append(f"{leg.name}: {n} outputs")
         elif h["kind"] == "conv2d" and leg.name == "conv_cout":
-            n = 1 << 14
+            n = 1 << 18
             shape = [b[1] - b[0] for b in h["box"]]
             pts = synth.coords(900, 2, n, shape)
             t = time.perf_counter()
@@ -55,7 +55,7 @@ def cpu_baseline(legs):
             flop += leg.work * n / float(np.prod(shape))
             parts.append(f"{leg.name}: {n} outputs")
         elif h["kind"] == "wgrad":
-            n = 1 << 12
+            n = 1 << 17
             c = h["x"].shape[1]
             pts = synth.coords(900, 3, n, (c, c, 3, 3))
             t = time.perf_counter()
