@@ -194,6 +194,10 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     const float* xs = Xs + buf * XB;
 #pragma unroll
     for (int cp = 0; cp < CK / 2; ++cp) {
+      // The next step's tiles go to the other LDS buffer in the middle of this step's MFMA
+      // stream: their global loads have had half a step to land, and the LDS writes retire in
+      // the shadow of the remaining MFMAs instead of in front of the barrier.
+      if (cp == CK / 4 && t + 1 < steps) store_lds(buf ^ 1);
 #pragma unroll
       for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
@@ -210,7 +214,6 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
             for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
         }
     }
-    if (t + 1 < steps) store_lds(buf ^ 1);
     __syncthreads();
   }
 

@@ -134,6 +134,9 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
+      // next step's tiles go to the other buffer half-way through this step's MFMA stream, so
+      // the LDS writes retire in the shadow of the remaining MFMAs, not in front of the barrier
+      if (kk == BK / 2 && t + 1 < steps) store_lds(buf ^ 1);
       float a[FM], b[FN];
 #pragma unroll
       for (int i = 0; i < FM; ++i) a[i] = as[(kk + half) * LDA + i * 32];
@@ -144,7 +147,6 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
     }
-    if (t + 1 < steps) store_lds(buf ^ 1);
     __syncthreads();
   }
 

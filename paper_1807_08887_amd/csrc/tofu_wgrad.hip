@@ -174,24 +174,30 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     if (t + 1 < steps) load_global(t + 1);
     const float* dsm = &Ds[buf][half][wave * 32 + l32];
     const float* xsm = &Xs[buf][l32 * kPLX + half];
-    // operands of column pair kp+1 are fetched while the nine MFMAs of pair kp run
-    float a_next = dsm[0], b_next[9];
+    // Two operand register sets alternate: while the nine MFMAs of one column pair run, the
+    // operands of the next pair are fetched into the other set (no register copies).  The next
+    // step's tiles are written to the other LDS buffer half-way through, in the MFMA shadow.
+    auto fetch = [&](int kp, float& a, float (&b)[9]) {
+      a = dsm[2 * kp * LDD];
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) b_next[tap] = xsm[(tap / 3) * kLDW + tap % 3];
-    for (int kp = 0; kp < KP; ++kp) {
-      const float a = a_next;
-      float b[9];
-#pragma unroll
-      for (int tap = 0; tap < 9; ++tap) b[tap] = b_next[tap];
-      if (kp + 1 < KP) {
-        a_next = dsm[2 * (kp + 1) * LDD];
-#pragma unroll
-        for (int tap = 0; tap < 9; ++tap) b_next[tap] = xsm[2 * (kp + 1) + (tap / 3) * kLDW + tap % 3];
-      }
+      for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[2 * kp + (tap / 3) * kLDW + tap % 3];
+    };
+    auto fma9 = [&](float a, const float (&b)[9]) {
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
+    };
+    float a0, a1, b0[9], b1[9];
+    const int half_way = (KP / 2) & ~1;
+    fetch(0, a0, b0);
+    for (int kp = 0; kp < KP; kp += 2) {
+      if (kp == half_way && t + 1 < steps) store_lds(buf ^ 1);
+      if (kp + 1 < KP) fetch(kp + 1, a1, b1);
+      fma9(a0, b0);
+      if (kp + 1 < KP) {
+        if (kp + 2 < KP) fetch(kp + 2, a0, b0);
+        fma9(a1, b1);
+      }
     }
-    if (t + 1 < steps) store_lds(buf ^ 1);
     __syncthreads();
   }
 
