@@ -27,7 +27,8 @@ struct MatmulArgs {
   int m, n, k;      // shard extents
   int k_slice;      // K elements per slice (multiple of BK); slices = gridDim.y
   int tiles_n;      // number of tiles along n
-  int fast;         // 1: unit column strides and 16-byte aligned rows -> vector loads
+  int fast;         // 1: unit column strides, 16-byte aligned rows, 32-bit offsets -> buffer vector loads
+  uint32_t a_bytes, b_bytes;   // bytes spanned by the two input boxes (buffer bounds, fast path)
 };
 
 template <int BM, int BN, int BK, int WM, int WN>
@@ -35,7 +36,9 @@ struct MatmulCfg {
   static constexpr int kThreads = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN;   // wavefront tile
   static constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wavefront
-  static constexpr int LDA = BM + 4;                 // k-major A tile: As[k][m]
+  // k-major A tile As[k][m]; the pitch makes the transposing writes of a half-wavefront
+  // (BK/4 column groups x 128/BK rows) hit 32 different banks
+  static constexpr int LDA = BM + 32 / BK;
   static constexpr int LDB = BN + 4;                 // Bs[k][n]
   static constexpr int kLdsFloats = 2 * BK * (LDA + LDB);
   static constexpr int AV = BM * BK / 4 / kThreads;  // 16-byte vectors of A per thread per step
@@ -61,24 +64,34 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
   const int k_begin = blockIdx.y * p.k_slice;
   const int k_end = min(p.k, k_begin + p.k_slice);
   const int steps = (k_end - k_begin + BK - 1) / BK;
-  const bool interior = p.fast && m0 + BM <= p.m && n0 + BN <= p.n;
+  // Fast path: per-lane byte offsets are fixed; a K step only moves a scalar offset.  Rows past
+  // m read as zero (offset out of range); columns past n may read the next row's values, which
+  // only reach accumulator columns that are never stored.
+  uint32_t a_voff[Cfg::AV], b_voff[Cfg::BV];
+#pragma unroll
+  for (int i = 0; i < Cfg::AV; ++i) {
+    const int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+    a_voff[i] = m0 + row < p.m ? 4u * (uint32_t)((int64_t)(m0 + row) * p.a_rs + 4 * q) : kNoOffset;
+  }
+#pragma unroll
+  for (int i = 0; i < Cfg::BV; ++i) {
+    const int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+    b_voff[i] = n0 + 4 * c < p.n ? 4u * (uint32_t)((int64_t)row * p.b_rs + n0 + 4 * c) : kNoOffset;
+  }
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A, p.a_bytes);
+  const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(p.B, p.b_bytes);
 
   v4f32 ra[Cfg::AV], rb[Cfg::BV];
 
   auto load_global = [&](int step) {
     const int k0 = k_begin + step * BK;
     const bool full_k = k0 + BK <= k_end;
-    if (interior && full_k) {
+    if (p.fast && full_k) {
+      const uint32_t a_soff = 4u * (uint32_t)k0, b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
 #pragma unroll
-      for (int i = 0; i < Cfg::AV; ++i) {
-        int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
-        ra[i] = *reinterpret_cast<const v4f32*>(p.A + (int64_t)(m0 + row) * p.a_rs + k0 + 4 * q);
-      }
+      for (int i = 0; i < Cfg::AV; ++i) ra[i] = buf_load4(a_rsrc, a_voff[i], a_soff);
 #pragma unroll
-      for (int i = 0; i < Cfg::BV; ++i) {
-        int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
-        rb[i] = *reinterpret_cast<const v4f32*>(p.B + (int64_t)(k0 + row) * p.b_rs + n0 + 4 * c);
-      }
+      for (int i = 0; i < Cfg::BV; ++i) rb[i] = buf_load4(b_rsrc, b_voff[i], b_soff);
     } else {
 #pragma unroll
       for (int i = 0; i < Cfg::AV; ++i) {
@@ -185,7 +198,7 @@ __global__ void __launch_bounds__(256) slice_sum_kernel(float* __restrict__ C, i
 }
 
 // ---- launch plan -------------------------------------------------------------------------
-constexpr int kBM = 128, kBN = 64, kBK = 16, kWM = 2, kWN = 2;
+constexpr int kBM = 128, kBN = 64, kBK = 32, kWM = 2, kWN = 2;
 constexpr int kTargetGroups = 512;   // two resident workgroups on each of the 256 compute units
 constexpr int kMaxSplit = 16;        // the reduce kernel sums at most 16 inputs
 
@@ -229,8 +242,12 @@ extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* s
   p.m = (int)m; p.n = (int)n; p.k = (int)k;
   p.tiles_n = (int)((n + kBN - 1) / kBN);
   const int tiles_m = (int)((m + kBM - 1) / kBM);
-  p.fast = as[1] == 1 && bs[1] == 1 && as[0] % 4 == 0 && bs[0] % 4 == 0 &&
-           (reinterpret_cast<uintptr_t>(p.A) & 15) == 0 && (reinterpret_cast<uintptr_t>(p.B) & 15) == 0;
+  const int64_t a_span = 1 + (m - 1) * as[0] + (k - 1) * as[1], b_span = 1 + (k - 1) * bs[0] + (n - 1) * bs[1];
+  p.fast = as[1] == 1 && bs[1] == 1 && as[0] >= 0 && bs[0] >= 0 && as[0] % 4 == 0 && bs[0] % 4 == 0 &&
+           (reinterpret_cast<uintptr_t>(p.A) & 15) == 0 && (reinterpret_cast<uintptr_t>(p.B) & 15) == 0 &&
+           a_span < ((int64_t)1 << 29) && b_span < ((int64_t)1 << 29);
+  p.a_bytes = p.fast ? (uint32_t)(4 * a_span) : 0;
+  p.b_bytes = p.fast ? (uint32_t)(4 * b_span) : 0;
 
   const int split = matmul_split_k(m, n, k);
   if (split > 1) {
