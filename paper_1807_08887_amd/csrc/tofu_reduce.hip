@@ -18,25 +18,20 @@ struct ReducePtrs {
   const float* p[kMaxReduceK];
 };
 
-#ifndef TOFU_REDUCE_NT_LOAD
-#define TOFU_REDUCE_NT_LOAD 1
-#endif
-#ifndef TOFU_REDUCE_MAX_BLOCKS
-#define TOFU_REDUCE_MAX_BLOCKS 16384
-#endif
-#ifndef TOFU_REDUCE_UNROLL8
-#define TOFU_REDUCE_UNROLL8 2
-#endif
-__device__ __forceinline__ v4f ld_stream(const v4f* p) {
-#if TOFU_REDUCE_NT_LOAD
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
+constexpr int kReduceThreads = 512;
+constexpr int kReduceMaxBlocks = 16384;
+// Inputs larger than the last-level cache are read with the streaming (nontemporal) hint;
+// smaller ones -- typically including a partial the previous kernel just wrote -- with ordinary
+// loads so that they may hit in cache.  Both choices were measured on MI355X.
+constexpr int64_t kStreamingBytes = (int64_t)256 << 20;
+
+template <bool NT>
+__device__ __forceinline__ v4f ld_vec(const v4f* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
 }
 
-template <int K, int UNROLL>
-__global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, ReducePtrs src, int64_t n_vec, int64_t count) {
+template <int K, int UNROLL, bool NT>
+__global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restrict__ dst, ReducePtrs src, int64_t n_vec, int64_t count) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   // main part: UNROLL vectors per trip, all loads first
@@ -45,7 +40,7 @@ __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, Re
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-      for (int j = 0; j < K; ++j) v[u][j] = ld_stream(reinterpret_cast<const v4f*>(src.p[j]) + i + u * stride);
+      for (int j = 0; j < K; ++j) v[u][j] = ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[j]) + i + u * stride);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       v4f acc = v[u][0];
@@ -55,9 +50,9 @@ __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, Re
     }
   }
   for (; i < n_vec; i += stride) {
-    v4f acc = ld_stream(reinterpret_cast<const v4f*>(src.p[0]) + i);
+    v4f acc = ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[0]) + i);
 #pragma unroll
-    for (int j = 1; j < K; ++j) acc += ld_stream(reinterpret_cast<const v4f*>(src.p[j]) + i);
+    for (int j = 1; j < K; ++j) acc += ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[j]) + i);
     __builtin_nontemporal_store(acc, reinterpret_cast<v4f*>(dst) + i);
   }
   // scalar tail (count not a multiple of 4, or the whole array when pointers are not 16-byte aligned)
@@ -70,13 +65,10 @@ __global__ void __launch_bounds__(256) reduce_kernel(float* __restrict__ dst, Re
 }
 
 template <int K>
-static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int blocks, hipStream_t s) {
-  if (K <= 4)
-    hipLaunchKernelGGL((reduce_kernel<K, 4>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
-  else if (K <= 8)
-    hipLaunchKernelGGL((reduce_kernel<K, TOFU_REDUCE_UNROLL8>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
-  else
-    hipLaunchKernelGGL((reduce_kernel<K, 1>), dim3(blocks), dim3(256), 0, s, dst, src, n_vec, count);
+static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int blocks, bool nt, hipStream_t s) {
+  constexpr int U = K <= 4 ? 4 : K <= 8 ? 2 : 1;
+  if (nt) hipLaunchKernelGGL((reduce_kernel<K, U, true>), dim3(blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count);
+  else hipLaunchKernelGGL((reduce_kernel<K, U, false>), dim3(blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count);
 }
 
 int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, void* stream) {
@@ -90,11 +82,12 @@ int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, v
   const int64_t n_vec = aligned ? count / 4 : 0;
   // Enough resident lanes to cover HBM latency, few enough that every lane streams several vectors.
   int64_t work = n_vec > 0 ? n_vec : count;
-  int64_t want = (work + 255) / 256;
-  int blocks = (int)(want < TOFU_REDUCE_MAX_BLOCKS ? (want < 1 ? 1 : want) : TOFU_REDUCE_MAX_BLOCKS);
+  int64_t want = (work + kReduceThreads - 1) / kReduceThreads;
+  int blocks = (int)(want < kReduceMaxBlocks ? (want < 1 ? 1 : want) : kReduceMaxBlocks);
+  const bool nt = (int64_t)(k + 1) * count * (int64_t)sizeof(float) > kStreamingBytes;
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (k) {
-#define TOFU_CASE(K) case K: launch_k<K>(dst, src, n_vec, count, blocks, s); break;
+#define TOFU_CASE(K) case K: launch_k<K>(dst, src, n_vec, count, blocks, nt, s); break;
     TOFU_CASE(1) TOFU_CASE(2) TOFU_CASE(3) TOFU_CASE(4) TOFU_CASE(5) TOFU_CASE(6) TOFU_CASE(7) TOFU_CASE(8)
     TOFU_CASE(9) TOFU_CASE(10) TOFU_CASE(11) TOFU_CASE(12) TOFU_CASE(13) TOFU_CASE(14) TOFU_CASE(15) TOFU_CASE(16)
 #undef TOFU_CASE
