@@ -184,35 +184,38 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
 
   const int steps = (p.CI + CK - 1) / CK;
+  constexpr int KS = (CK / 2) * 9;            // MFMA k-steps per step: (channel pair, tap)
   load_global(0);
   store_lds(0);
   __syncthreads();
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
-    if (t + 1 < steps) load_global(t + 1);
+    // The body is branch-free so that the compiler can count outstanding LDS operations exactly:
+    // the last step simply stages its own tiles again into the idle buffer.
+    load_global(min(t + 1, steps - 1));
     const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * 9 * LDM;
     const float* xs = Xs + buf * XB;
+    // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
+    float a[2][FM], b[2][FN];
+    auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
+      const int cp = s / 9, tap = s % 9, kh = tap / 3, kw = tap % 3;
 #pragma unroll
-    for (int cp = 0; cp < CK / 2; ++cp) {
-      // The next step's tiles go to the other LDS buffer in the middle of this step's MFMA
-      // stream: their global loads have had half a step to land, and the LDS writes retire in
-      // the shadow of the remaining MFMAs instead of in front of the barrier.
-      if (cp == CK / 4 && t + 1 < steps) store_lds(buf ^ 1);
+      for (int i = 0; i < FM; ++i) av[i] = wsm[(cp * 18 + tap) * LDM + i * 32];
 #pragma unroll
-      for (int kh = 0; kh < 3; ++kh)
+      for (int j = 0; j < FN; ++j) bv[j] = xs[cp * 2 * PL + pos_l[j] + kh * LDW + kw];
+    };
+    fetch(0, a[0], b[0]);
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) {
-          const int tap = kh * 3 + kw;
-          float a[FM], b[FN];
+    for (int s = 0; s < KS; ++s) {
+      if (s + 1 < KS) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
+      // the next step's tiles go to the other LDS buffer half-way through the MFMA stream: their
+      // global loads have had half a step to land and the writes retire in the MFMA shadow
+      if (s == KS / 2) store_lds(buf ^ 1);
 #pragma unroll
-          for (int i = 0; i < FM; ++i) a[i] = wsm[(cp * 18 + tap) * LDM + i * 32];
+      for (int i = 0; i < FM; ++i)
 #pragma unroll
-          for (int j = 0; j < FN; ++j) b[j] = xs[cp * 2 * PL + pos_l[j] + kh * LDW + kw];
-#pragma unroll
-          for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
-        }
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[s & 1][i], b[s & 1][j], acc[i][j]);
     }
     __syncthreads();
   }

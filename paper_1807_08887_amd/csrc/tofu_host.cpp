@@ -251,9 +251,7 @@ size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits
     return s > 1 ? (size_t)s * (size_t)m * (size_t)n * sizeof(float) : 0;
   }
   if (op->kind == TOFU_OP_CONV2D_WGRAD) {
-    int64_t co = r.hi[0] - r.lo[0], ci = r.hi[1] - r.lo[1], nb = r.hi[2] - r.lo[2];
-    int s = wgrad_split_n(co, ci, nb, conv_out_extent(op->H, op->KH, op->stride, op->pad));
-    return s > 1 ? (size_t)s * (size_t)co * (size_t)ci * (size_t)(op->KH * op->KW) * sizeof(float) : 0;
+    return wgrad_workspace_bytes(r.hi[0] - r.lo[0], r.hi[1] - r.lo[1], r.hi[2] - r.lo[2]);
   }
   return 0;
 }

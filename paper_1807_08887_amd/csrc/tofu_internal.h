@@ -44,8 +44,8 @@ const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const in
 // ---- launch plans (shared by tofu_workspace_bytes and the entry points) ----
 // Number of K slices the matmul kernel cuts its own reduction into for an m x n x k shard.
 int matmul_split_k(int64_t m, int64_t n, int64_t k);
-// Number of batch slices the weight-gradient kernel cuts its reduction into.
-int wgrad_split_n(int64_t co, int64_t ci, int64_t nb, int64_t rows);
+// Workspace the weight-gradient kernel needs for a shard of co x ci output channels and nb images.
+size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb);
 
 // Enqueue dst[i] = sum_j parts[j][i] (fixed order j = 0..k-1); used by the public reduce and
 // by the kernels that split their own reduction.  Pointers are device pointers.

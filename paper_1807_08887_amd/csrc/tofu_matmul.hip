@@ -142,23 +142,31 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
   __syncthreads();
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
-    if (t + 1 < steps) load_global(t + 1);
-    const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32;
-    const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32;
+    // Branch-free body (the compiler can then count outstanding LDS operations exactly): the
+    // last step stages its own tiles again into the idle buffer.
+    load_global(min(t + 1, steps - 1));
+    const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32 + half * LDA;
+    const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32 + half * LDB;
+    // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
+    float a[2][FM], b[2][FN];
+    auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
+      for (int i = 0; i < FM; ++i) av[i] = as[2 * s * LDA + i * 32];
+#pragma unroll
+      for (int j = 0; j < FN; ++j) bv[j] = bs[2 * s * LDB + j * 32];
+    };
+    fetch(0, a[0], b[0]);
+#pragma unroll
+    for (int s = 0; s < BK / 2; ++s) {
+      if (s + 1 < BK / 2) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
       // next step's tiles go to the other buffer half-way through this step's MFMA stream, so
       // the LDS writes retire in the shadow of the remaining MFMAs, not in front of the barrier
-      if (kk == BK / 2 && t + 1 < steps) store_lds(buf ^ 1);
-      float a[FM], b[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) a[i] = as[(kk + half) * LDA + i * 32];
-#pragma unroll
-      for (int j = 0; j < FN; ++j) b[j] = bs[(kk + half) * LDB + j * 32];
+      if (s == BK / 4) store_lds(buf ^ 1);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[s & 1][i], b[s & 1][j], acc[i][j]);
     }
     __syncthreads();
   }

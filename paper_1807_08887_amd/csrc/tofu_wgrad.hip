@@ -11,9 +11,13 @@
 //     (Ds[w][co]) and x[n, ci tile, h-pad .. h-pad+2, :] is staged with its zero border, so the
 //     nine taps are nine shifted reads of the same three staged rows.  One MFMA contracts two
 //     adjacent output columns (lanes 0-31: w, lanes 32-63: w+1).
-//   * The batch range of the shard is cut into slices (grid.y) so that enough workgroups exist
-//     to balance 256 compute units; slices are written tap-major to the caller's workspace and
-//     summed in fixed order by a second kernel that also restores the [co][ci][kh][kw] layout.
+//   * Load balance: the work is T tiles x NB images ("units", tile-major).  400 tiles cannot fill
+//     512 workgroup slots evenly, so workgroup g takes the units [g*N/G, (g+1)*N/G) -- the same
+//     even split as a shard range.  A run of units inside one tile is a segment; a segment that
+//     is a whole tile is written straight to dw, any other goes tap-major to a workspace slot
+//     and a second kernel sums each tile's segments in workgroup order (fixed, no atomics) and
+//     restores the [co][ci][kh][kw] layout.  Each workgroup writes at most a few slots, so the
+//     workspace is about 2.5x the output instead of one full copy per image.
 #include <hip/hip_runtime.h>
 
 #include "tofu_internal.h"
@@ -24,32 +28,36 @@ namespace tofu {
 struct WgradArgs {
   const float* x;    // element at the low corner of the (clipped) input box
   const float* dy;   // element (n_lo, co_lo, 0, 0)
-  float* out;        // dw element (co_lo, ci_lo, 0, 0), or the workspace when slices > 1
+  float* out;        // dw element (co_lo, ci_lo, 0, 0)
+  float* slots;      // workspace: [groups * max_segments] partial tiles of kSlotFloats floats
   int64_t xs[4], ds[4], os[4];   // element strides: x (n,c,h,w), dy (n,co,h,w), out (co,ci,kh,kw)
-  int64_t slice_stride;          // floats between slices in the workspace
   uint32_t x_bytes, dy_bytes;    // bytes spanned by the two input boxes (buffer bounds, fast path)
   int NB, CO, CI;    // images, output channels, input channels of the shard
   int HO, WO;        // output rows / columns
   int IH, IW;        // rows / columns of the clipped input box
   int plh, plw;      // zero rows / columns in front of the input box
-  int n_per_slice;   // images per slice
   int tiles_m, tiles_n;
+  int groups;        // workgroups that share the tiles x images units
+  int max_segments;  // most tile segments one workgroup can produce
   int CW;            // output columns per K step (<= 32, multiple of 4 unless WO itself is not)
   int chunks;        // column chunks per output row
-  int to_workspace;  // 1: write [tap][co][ci] slices to the workspace
   int vec;           // 1: rows of dy are contiguous and 16-byte aligned -> vector loads (generic path)
 };
 
 // LDS geometry is fixed so that every staging index splits with compile-time divisors.
 constexpr int kKR = 32;              // dy positions per K step (a chunk of one output row)
 constexpr int kLDW = kKR + 2;        // staged x columns per row: chunk widened by the filter window
-constexpr int kPLX = 3 * kLDW + 3;   // staged floats per input channel; odd -> 32 channels hit 32 banks
+constexpr int kPLX = 3 * kLDW + 3;
+constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace: [tap][128 co][32 ci]   // staged floats per input channel; odd -> 32 channels hit 32 banks
 
 // FAST: one chunk per output row, dy rows are whole aligned vectors, every operand offset fits
 // 32 bits.  Then each lane's staging addresses are fixed byte offsets, a step only changes a
 // scalar offset, and all padding comes from out-of-range buffer reads -- no branches, no
 // per-step index arithmetic.  Otherwise a generic guarded path is used.
-template <int BM, int BCI, bool FAST>
+// BALANCED: the workgroup walks a range of units and writes every segment to a workspace slot
+// (even a whole tile: one simple epilogue keeps the register count down); otherwise a workgroup
+// is one whole tile and writes dw directly.
+template <int BM, int BCI, bool FAST, bool BALANCED>
 __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(const WgradArgs p) {
   constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 2;
   constexpr int D_ITEMS = BM * (kKR / 4), X_ITEMS = BCI * 3 * kLDW;
@@ -63,23 +71,32 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int total = p.tiles_m * p.tiles_n;
-  const int per_xcd = (total + 7) / 8;
-  const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;   // keep neighbouring tiles on one XCD
-  if (lid >= total) return;
-  const int tile_n = lid / p.tiles_m, tile_m = lid % p.tiles_m;
-  const int m0 = tile_m * BM, c0 = tile_n * BCI;
-  const int n_begin = blockIdx.y * p.n_per_slice;
-  const int n_end = min(p.NB, n_begin + p.n_per_slice);
-  const int steps = (n_end - n_begin) * p.HO * p.chunks;
+  // consecutive workgroup numbers (which share tiles) stay on one XCD
+  const int per_xcd = (p.groups + 7) / 8;
+  const int g = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (g >= p.groups) return;
+  const int64_t n_units = (int64_t)p.tiles_m * p.tiles_n * p.NB;
+  const int u_begin = (int)(g * n_units / p.groups), u_end = (int)((g + 1) * n_units / p.groups);
   const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
+  const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x - (int64_t)p.plh * p.xs[2], p.x_bytes + 4u * (uint32_t)(p.plh * p.xs[2]));
+  const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
+  const int x_ci = tid / TPC, x_sub = tid % TPC;
+
+  int segment = 0;
+  for (int u = u_begin; u < u_end; ++segment) {
+  // ---- one segment: images [n_begin, n_end) of one tile ----
+  const int tile = u / p.NB;
+  const int n_begin = u - tile * p.NB;
+  const int n_end = min(p.NB, n_begin + (u_end - u));
+  u += n_end - n_begin;
+  const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
+  const int m0 = tile_m * BM, c0 = tile_n * BCI;
+  const int steps = (n_end - n_begin) * p.HO * p.chunks;
 
   // ---- fast-path staging maps ----
   // dy: thread -> (row = tid/8 + 32*j, columns 4*(tid%8) .. +3); x: thread -> (channel tid/TPC, elements tid%TPC + TPC*j)
-  const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
-  const int x_ci = tid / TPC, x_sub = tid % TPC;
   uint32_t d_voff[DJ], x_voff[XF];
-  int x_r[XF];
   if (FAST) {
 #pragma unroll
     for (int j = 0; j < DJ; ++j) {
@@ -90,13 +107,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     for (int j = 0; j < XF; ++j) {
       const int e = x_sub + TPC * j, r = e / kLDW, c = e - r * kLDW, iw = c - p.plw;
       const bool ok = e < 3 * kLDW && c0 + x_ci < p.CI && iw >= 0 && iw < p.IW;
-      x_r[j] = r;
       // row offset r*xs2 is relative to input row (oh - plh); the buffer base is moved back by plh rows
       x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)iw * p.xs[3]) : kNoOffset;
     }
   }
-  const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
-  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x - (int64_t)p.plh * p.xs[2], p.x_bytes + 4u * (uint32_t)(p.plh * p.xs[2]));
 
   v4f32 rd[DJ];
   float rx[FAST ? XF : XJ];
@@ -110,7 +124,8 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
       for (int j = 0; j < DJ; ++j) rd[j] = buf_load4(d_rsrc, d_voff[j], d_soff);
 #pragma unroll
       for (int j = 0; j < XF; ++j) {
-        const bool row_ok = (unsigned)(oh + x_r[j] - p.plh) < (unsigned)p.IH;
+        const int e = x_sub + TPC * j, r = (e >= kLDW) + (e >= 2 * kLDW);   // staged row of this element
+        const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
         rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
       }
       return;
@@ -169,14 +184,19 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     store_lds(0);
   }
   __syncthreads();
+  // Column pairs per step, rounded up to even (the staged columns past CW are zeros) so that the
+  // two operand register sets below alternate without a remainder case.
+  const int KPE = (KP + 1) & ~1;
+  const int half_way = (KPE / 2) & ~1;
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
-    if (t + 1 < steps) load_global(t + 1);
+    // Branch-free body (the compiler can then count outstanding LDS operations exactly): the
+    // last step stages its own tiles again into the idle buffer.
+    load_global(min(t + 1, steps - 1));
     const float* dsm = &Ds[buf][half][wave * 32 + l32];
     const float* xsm = &Xs[buf][l32 * kPLX + half];
     // Two operand register sets alternate: while the nine MFMAs of one column pair run, the
-    // operands of the next pair are fetched into the other set (no register copies).  The next
-    // step's tiles are written to the other LDS buffer half-way through, in the MFMA shadow.
+    // operands of the next pair are fetched into the other set (no register copies).
     auto fetch = [&](int kp, float& a, float (&b)[9]) {
       a = dsm[2 * kp * LDD];
 #pragma unroll
@@ -187,32 +207,29 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
       for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
     };
     float a0, a1, b0[9], b1[9];
-    const int half_way = (KP / 2) & ~1;
     fetch(0, a0, b0);
-    for (int kp = 0; kp < KP; kp += 2) {
-      if (kp == half_way && t + 1 < steps) store_lds(buf ^ 1);
-      if (kp + 1 < KP) fetch(kp + 1, a1, b1);
+    for (int kp = 0; kp < KPE; kp += 2) {
+      // the next step's tiles go to the other LDS buffer half-way through, in the MFMA shadow
+      if (kp == half_way) store_lds(buf ^ 1);
+      fetch(kp + 1, a1, b1);
+      __builtin_amdgcn_sched_barrier(0);           // keep each fetch ahead of the MFMAs it overlaps with
       fma9(a0, b0);
-      if (kp + 1 < KP) {
-        if (kp + 2 < KP) fetch(kp + 2, a0, b0);
-        fma9(a1, b1);
-      }
+      fetch(min(kp + 2, KPE - 1), a0, b0);         // past the end: a harmless re-read
+      __builtin_amdgcn_sched_barrier(0);
+      fma9(a1, b1);
     }
     __syncthreads();
   }
 
-  const int ci = c0 + l32;
-  if (p.to_workspace) {
-    // [slice][tap][co][ci]: a lane row of 32 input channels is one contiguous 128-byte store
-    float* o = p.out + (int64_t)blockIdx.y * p.slice_stride;
+  if (BALANCED) {
+    // slot [tap][co_local][ci_local]: a lane row of 32 input channels is one 128-byte store
+    float* o = p.slots + ((int64_t)g * p.max_segments + segment) * kSlotFloats + (wave * 32 + 4 * half) * BCI + l32;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int co = m0 + wave * 32 + acc_row(v, half);
-        if (co < p.CO && ci < p.CI) o[((int64_t)tap * p.CO + co) * p.CI + ci] = acc[tap][v];
-      }
+      for (int v = 0; v < 16; ++v) o[(tap * BM + 8 * (v >> 2) + (v & 3)) * BCI] = acc[tap][v];
   } else {
+    const int ci = c0 + l32;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
@@ -222,39 +239,65 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
           p.out[(int64_t)co * p.os[0] + (int64_t)ci * p.os[1] + (tap / 3) * p.os[2] + (tap % 3) * p.os[3]] = acc[tap][v];
       }
   }
+  __syncthreads();   // the next segment's prologue overwrites LDS buffer 0
+  }  // segments
 }
 
-// dw[co][ci][tap] = sum_j ws[j][tap][co][ci], j in fixed order.  One thread per (co, ci): its nine
-// reads per slice are coalesced across lanes (ci fastest); its nine writes cover 36 contiguous bytes.
-__global__ void __launch_bounds__(256) wgrad_slice_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
-                                                               const float* __restrict__ ws, int slices, int64_t slice_stride, int CO, int CI) {
-  const int64_t items = (int64_t)CO * CI;
+// Sums every tile's segments (one to a few workspace slots) in workgroup order and writes
+// dw[co][ci][kh][kw].  One thread per (co, ci): its nine reads per slot are coalesced
+// across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
+__global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
+                                                                 const float* __restrict__ slots, int groups, int max_segments, int NB,
+                                                                 int tiles_m, int tiles_n, int CO, int CI) {
+  constexpr int BM = 128, BCI = 32;
+  const int64_t n_units = (int64_t)tiles_m * tiles_n * NB;
+  const int64_t items = (int64_t)tiles_m * tiles_n * BM * BCI;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t co = i / CI, ci = i - co * CI;
+    const int tile = (int)(i / (BM * BCI)), local = (int)(i % (BM * BCI)), co_l = local / BCI, ci_l = local % BCI;
+    const int tile_n = tile / tiles_m, tile_m = tile % tiles_m;
+    const int co = tile_m * BM + co_l, ci = tile_n * BCI + ci_l;
+    // workgroups whose unit ranges meet this tile: g(u) = floor(((u + 1) * G - 1) / N)
+    const int64_t u0 = (int64_t)tile * NB, u1 = u0 + NB - 1;
+    const int g_first = (int)(((u0 + 1) * groups - 1) / n_units), g_last = (int)(((u1 + 1) * groups - 1) / n_units);
+    if (co >= CO || ci >= CI) continue;
     float acc[9];
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) acc[tap] = ws[(int64_t)tap * items + i];
-    for (int j = 1; j < slices; ++j)
+    for (int tap = 0; tap < 9; ++tap) acc[tap] = 0.f;
+    for (int g = g_first; g <= g_last; ++g) {
+      const int first_tile = (int)((g * n_units / groups) / NB);   // tile of the workgroup's first unit = its segment 0
+      const float* sl = slots + ((int64_t)g * max_segments + (tile - first_tile)) * kSlotFloats + co_l * BCI + ci_l;
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) acc[tap] += ws[j * slice_stride + (int64_t)tap * items + i];
+      for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
+    }
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) dw[co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw] = acc[tap];
   }
 }
 
 constexpr int gBM = 128, gBCI = 32;
-constexpr int kTargetGroupsW = 6144;   // ~12 rounds of two workgroups per compute unit
-constexpr int kMaxSlices = 16;
+constexpr int kWgradSlots = 512;       // two resident workgroups on each of the 256 compute units
 
-int wgrad_split_n(int64_t co, int64_t ci, int64_t nb, int64_t rows) {
-  (void)rows;
-  int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
-  if (tiles >= 1024 || nb < 2) return 1;
-  int64_t want = (kTargetGroupsW + tiles - 1) / tiles;
-  if (want > kMaxSlices) want = kMaxSlices;
-  if (want > nb) want = nb;
-  int64_t per = (nb + want - 1) / want;
-  return (int)((nb + per - 1) / per);
+// Number of workgroups and the most segments one of them can produce for a shard of
+// co x ci output channels and nb images; groups == tiles means whole tiles and no workspace.
+void wgrad_plan(int64_t co, int64_t ci, int64_t nb, int* groups, int* max_segments) {
+  const int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
+  const int64_t units = tiles * nb;
+  if (tiles >= 2 * kWgradSlots || nb < 2 || tiles % kWgradSlots == 0) {
+    *groups = (int)tiles;
+    *max_segments = 1;
+    return;
+  }
+  const int64_t g = units < kWgradSlots ? units : kWgradSlots;
+  const int64_t per = (units + g - 1) / g;                 // most units per workgroup
+  *groups = (int)g;
+  *max_segments = (int)((per + nb - 2) / nb + 1);
+}
+
+size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb) {
+  int groups, max_segments;
+  wgrad_plan(co, ci, nb, &groups, &max_segments);
+  const int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
+  return groups == tiles ? 0 : (size_t)groups * max_segments * kSlotFloats * sizeof(float);
 }
 
 }  // namespace tofu
@@ -313,31 +356,28 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   const bool fast = nonneg && p.vec && p.chunks == 1 && WO % 4 == 0 && x_span + p.plh * xs[2] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
   p.x_bytes = fast ? (uint32_t)(4 * x_span) : 0;
   p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
-  const int slices = wgrad_split_n(CO, CI, NB, HO);
-  p.n_per_slice = (int)((NB + slices - 1) / slices);
-  p.to_workspace = slices > 1;
-  p.slice_stride = CO * CI * 9;
-  if (slices > 1) {
-    const size_t need = (size_t)slices * (size_t)p.slice_stride * sizeof(float);
-    if (!workspace || workspace_bytes < need)
-      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
-    p.out = static_cast<float*>(workspace);
-  } else {
-    p.out = dw_out;
-  }
-  auto kern = fast ? wgrad_kernel<gBM, gBCI, true> : wgrad_kernel<gBM, gBCI, false>;
+  int groups, max_segments;
+  wgrad_plan(CO, CI, NB, &groups, &max_segments);
+  p.groups = groups;
+  p.max_segments = max_segments;
+  p.out = dw_out;
+  p.slots = static_cast<float*>(workspace);
+  const size_t need = wgrad_workspace_bytes(CO, CI, NB);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+  auto kern = need > 0 ? (fast ? wgrad_kernel<gBM, gBCI, true, true> : wgrad_kernel<gBM, gBCI, false, true>)
+                       : (fast ? wgrad_kernel<gBM, gBCI, true, false> : wgrad_kernel<gBM, gBCI, false, false>);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int total = p.tiles_m * p.tiles_n;
-  hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8, slices), dim3(NT), 0, s, p);
+  hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
-  if (slices > 1) {
-    const int64_t items = CO * CI;
+  if (need > 0) {
+    const int64_t items = (int64_t)p.tiles_m * p.tiles_n * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
-    hipLaunchKernelGGL(wgrad_slice_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
-                       static_cast<const float*>(workspace), slices, p.slice_stride, (int)CO, (int)CI);
+    hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
+                       static_cast<const float*>(workspace), groups, max_segments, (int)NB, p.tiles_m, p.tiles_n, (int)CO, (int)CI);
     e = hipGetLastError();
-    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient slice sum launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient segment sum launch failed: %s", hipGetErrorString(e));
   }
   return TOFU_OK;
 }
