@@ -20,11 +20,8 @@ struct ReducePtrs {
 
 constexpr int kReduceThreads = 512;
 constexpr int kReduceMaxBlocks = 16384;
-// Inputs larger than the last-level cache are read with the streaming (nontemporal) hint;
-// smaller ones -- typically including a partial the previous kernel just wrote -- with ordinary
-// loads so that they may hit in cache.  Both choices were measured on MI355X.
-constexpr int64_t kStreamingBytes = (int64_t)256 << 20;
-
+// Inputs are read with the streaming (nontemporal) hint: measured cold (inside the whole-step
+// benchmark) it is the faster choice for both the 151 MB and the 531 MB reduction.
 template <bool NT>
 __device__ __forceinline__ v4f ld_vec(const v4f* p) {
   return NT ? __builtin_nontemporal_load(p) : *p;
@@ -84,7 +81,7 @@ int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, v
   int64_t work = n_vec > 0 ? n_vec : count;
   int64_t want = (work + kReduceThreads - 1) / kReduceThreads;
   int blocks = (int)(want < kReduceMaxBlocks ? (want < 1 ? 1 : want) : kReduceMaxBlocks);
-  const bool nt = (int64_t)(k + 1) * count * (int64_t)sizeof(float) > kStreamingBytes;
+  const bool nt = true;
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (k) {
 #define TOFU_CASE(K) case K: launch_k<K>(dst, src, n_vec, count, blocks, nt, s); break;
