@@ -185,14 +185,16 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
 
   const int steps = (p.CI + CK - 1) / CK;
   constexpr int KS = (CK / 2) * 9;            // MFMA k-steps per step: (channel pair, tap)
+  // Pipeline: the tiles of step t+1 are written to LDS in the middle of step t, and right after
+  // that the global loads of step t+2 are issued into the same registers, so every load has a
+  // whole step to land.  The body is branch-free (the compiler can then count outstanding LDS
+  // operations exactly): the last steps simply stage the final tiles again into the idle buffer.
   load_global(0);
   store_lds(0);
+  load_global(min(1, steps - 1));
   __syncthreads();
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
-    // The body is branch-free so that the compiler can count outstanding LDS operations exactly:
-    // the last step simply stages its own tiles again into the idle buffer.
-    load_global(min(t + 1, steps - 1));
     const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * 9 * LDM;
     const float* xs = Xs + buf * XB;
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
@@ -209,9 +211,11 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     for (int s = 0; s < KS; ++s) {
       if (s + 1 < KS) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
       __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
-      // the next step's tiles go to the other LDS buffer half-way through the MFMA stream: their
-      // global loads have had half a step to land and the writes retire in the MFMA shadow
-      if (s == KS / 2) store_lds(buf ^ 1);
+      // half-way through the MFMA stream, so that the LDS writes retire in the MFMA shadow
+      if (s == KS / 2) {
+        store_lds(buf ^ 1);
+        load_global(min(t + 2, steps - 1));
+      }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll

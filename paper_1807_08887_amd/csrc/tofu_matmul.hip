@@ -135,16 +135,18 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
 
+  // Pipeline: the tiles of step t+1 are written to LDS in the middle of step t, and right after
+  // that the global loads of step t+2 are issued into the same registers, so every load has a
+  // whole step to land.  The body is branch-free (the compiler can then count outstanding LDS
+  // operations exactly): the last steps simply stage the final tiles again into the idle buffer.
   if (steps > 0) {
     load_global(0);
     store_lds(0);
+    load_global(min(1, steps - 1));
   }
   __syncthreads();
   for (int t = 0; t < steps; ++t) {
     const int buf = t & 1;
-    // Branch-free body (the compiler can then count outstanding LDS operations exactly): the
-    // last step stages its own tiles again into the idle buffer.
-    load_global(min(t + 1, steps - 1));
     const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32 + half * LDA;
     const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32 + half * LDB;
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
@@ -162,7 +164,10 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
       __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
       // next step's tiles go to the other buffer half-way through this step's MFMA stream, so
       // the LDS writes retire in the shadow of the remaining MFMAs, not in front of the barrier
-      if (s == BK / 4) store_lds(buf ^ 1);
+      if (s == BK / 4) {
+        store_lds(buf ^ 1);
+        load_global(min(t + 2, steps - 1));
+      }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll

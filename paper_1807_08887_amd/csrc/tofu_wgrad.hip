@@ -179,10 +179,8 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 #pragma unroll
   for (int t = 0; t < 9; ++t) acc[t] = acc_zero();
 
-  if (steps > 0) {
-    load_global(0);
-    store_lds(0);
-  }
+  load_global(0);
+  store_lds(0);
   __syncthreads();
   // Column pairs per step, rounded up to even (the staged columns past CW are zeros) so that the
   // two operand register sets below alternate without a remainder case.
