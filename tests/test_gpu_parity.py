@@ -272,6 +272,21 @@ def test_conv2d_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
     assert_close(got, val, absum, f"conv2d {opd}")
 
 
+def test_conv2d_wide_rows_and_limits():
+    """56-wide rows need the narrower channel step; rows too wide for the staging buffers are
+    reported as unsupported instead of being computed some slower way."""
+    opd = dict(kind="conv2d", batch=1, c_in=6, c_out=64, H=20, W=56, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(44, 0, (1, 6, 20, 56), 1.0)
+    w = synth.normal(44, 1, (64, 6, 3, 3), 0.3)
+    got = run_conv(opd, [], dev(x), dev(w)).cpu().numpy()
+    val, absum = oracle.conv2d_box(x, w, pad=1)
+    assert_close(got, val, absum, "conv2d 20x56")
+    wide = dict(opd, W=400)
+    with pytest.raises(tofu.TofuError) as e:
+        run_conv(wide, [], torch.zeros(1, 6, 20, 400, device=DEV), dev(w))
+    assert e.value.status == -6
+
+
 @pytest.mark.parametrize("k", [2, 3, 4])
 def test_conv2d_pnr_invariant_bit_exact(k):
     opd = dict(kind="conv2d", batch=4, c_in=12, c_out=72, H=12, W=10, KH=3, KW=3, stride=1, pad=1)
@@ -344,6 +359,21 @@ def test_wgrad_pnr_invariant_bit_exact(k):
     for dim in ["CO", "CI", "N"]:
         got = assemble(opd, dim, k, lambda sp: run_wgrad(opd, sp, dx, ddy))
         assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_wgrad_many_tiles_few_images():
+    """960 output tiles x 2 images over 512 workgroups: a workgroup's unit range then spans up
+    to three tiles (partial, whole, partial), every tile is summed from workspace slots."""
+    co, ci, nb = 640, 6144, 2
+    opd = dict(kind="conv2d_wgrad", batch=nb, c_in=ci, c_out=co, H=4, W=4, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(53, 0, (nb, ci, 4, 4), 1.0)
+    dy = synth.normal(53, 1, (nb, co, 4, 4), 1.0)
+    got = run_wgrad(opd, [], dev(x), dev(dy)).cpu().numpy()
+    pts = np.concatenate([synth.coords(53, 2, 20000, got.shape),
+                          np.array([[0, 0, 0, 0], [co - 1, ci - 1, 2, 2], [127, 31, 1, 1], [128, 32, 0, 2]])])
+    val, absum = oracle.wgrad_pts(x, dy, 3, 3, pts, pad=1)
+    assert not np.isnan(got).any()
+    assert_close(got[tuple(pts.T)], val, absum, "wgrad 960 tiles x 2 images")
 
 
 def test_runs_are_bit_identical():
