@@ -11,7 +11,8 @@
 // lanes write neighbouring bytes and every destination line is written whole, whichever source
 // it comes from), looks up the source that holds that position ONCE, and then walks down the
 // rows with constant pointer increments: the loop body is UNROLL loads, UNROLL stores and two
-// 64-bit adds.  When a source cuts the outermost dimension there is a single "row" and the
+// 64-bit adds.  A workgroup owns a run of consecutive rows, so its trips stay in neighbouring
+// DRAM pages.  When a source cuts the outermost dimension there is a single "row" and the
 // kernel degenerates to one lookup + one copy per lane.  Pure HBM stream: 1 read + 1 write per
 // element; loads are ordinary, stores carry the streaming (nontemporal) hint, which measured
 // fastest of the four combinations on MI355X.
@@ -66,6 +67,7 @@ struct FetchPlan {
   FastDiv row_vecs_div;              // same, for thread -> (row of the workgroup, vector of the row)
   uint32_t rows;                     // number of rows
   uint32_t rows_per_block;           // rows a workgroup covers per trip (row_vecs <= 256), else 1
+  uint32_t rows_per_group;           // consecutive rows owned by one workgroup (multiple of rows_per_block)
   FetchSource src[kMaxFetchSources];
 };
 
@@ -81,21 +83,23 @@ template <> struct VecT<1> { typedef float type; };
 template <int VEC, int UNROLL, int FLAT>
 __global__ void __launch_bounds__(256) fetch_kernel(const FetchPlan t) {
   typedef typename VecT<VEC>::type V;
-  // which vector of the row, which row to start with, how many rows to skip per trip
-  uint32_t col, row, row_step;
+  // Which vector of the row; which rows.  A workgroup owns a run of consecutive rows (its trips
+  // then touch neighbouring DRAM pages, which measured ~7 % faster than striding the whole
+  // region) and covers rows_per_block of them per trip.
+  uint32_t col, row;
+  const uint32_t row_step = t.rows_per_block;
+  const uint32_t row_end = min(t.rows, (blockIdx.y + 1) * t.rows_per_group);
   if (t.rows_per_block > 1) {
     const uint32_t sub = fdiv(threadIdx.x, t.row_vecs_div);   // small rows: several rows per workgroup
     col = threadIdx.x - sub * t.row_vecs;
     if (sub >= t.rows_per_block) return;
-    row = blockIdx.y * t.rows_per_block + sub;
-    row_step = gridDim.y * t.rows_per_block;
+    row = blockIdx.y * t.rows_per_group + sub;
   } else {
     col = blockIdx.x * blockDim.x + threadIdx.x;
     if (col >= t.row_vecs) return;
-    row = blockIdx.y;
-    row_step = gridDim.y;
+    row = blockIdx.y * t.rows_per_group;
   }
-  if (row >= t.rows) return;
+  if (row >= row_end) return;
 
   // inner coordinates of this lane's vector (innermost coordinate in floats), once
   int32_t coord[TOFU_MAX_DIMS];
@@ -140,7 +144,7 @@ __global__ void __launch_bounds__(256) fetch_kernel(const FetchPlan t) {
   float* d = t.dst + d_off + (int64_t)(int32_t)row * t.dst_row_stride;
   const int64_t d_step = (int64_t)(int32_t)row_step * t.dst_row_stride;
 
-  for (; row + (UNROLL - 1) * row_step < t.rows; row += UNROLL * row_step) {
+  for (; row + (UNROLL - 1) * row_step < row_end; row += UNROLL * row_step) {
     V v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) v[u] = *reinterpret_cast<const V*>(s + u * s_step);
@@ -149,7 +153,7 @@ __global__ void __launch_bounds__(256) fetch_kernel(const FetchPlan t) {
     s += UNROLL * s_step;
     d += UNROLL * d_step;
   }
-  for (; row < t.rows; row += row_step) {
+  for (; row < row_end; row += row_step) {
     __builtin_nontemporal_store(*reinterpret_cast<const V*>(s), reinterpret_cast<V*>(d));
     s += s_step;
     d += d_step;
@@ -328,28 +332,25 @@ extern "C" int tofu_region_fetch(const tofu_tensor_t* dst, const tofu_tensor_t* 
   }
 
   // ---- launch shape: lanes along a row, workgroups (and trips) down the rows ----
-#ifndef TOFU_FETCH_UNROLL
-#define TOFU_FETCH_UNROLL 2
-#endif
-#ifndef TOFU_FETCH_MAX_BLOCKS
-#define TOFU_FETCH_MAX_BLOCKS 16384
-#endif
-  constexpr int kUnroll = TOFU_FETCH_UNROLL;
-  constexpr int64_t kMaxBlocks = TOFU_FETCH_MAX_BLOCKS;
+  constexpr int kUnroll = 4;
+  constexpr int64_t kMaxBlocks = 16384;
   dim3 grid;
+  int64_t groups;   // workgroups down the rows
   if (row_vecs <= 256) {
     plan.rows_per_block = (uint32_t)(256 / row_vecs);
-    const int64_t need = (plan.rows + plan.rows_per_block - 1) / plan.rows_per_block;
-    grid = dim3(1, (unsigned)(need < kMaxBlocks ? need : kMaxBlocks));
+    groups = kMaxBlocks;
+    grid.x = 1;
   } else {
     plan.rows_per_block = 1;
-    const int64_t col_blocks = (row_vecs + 255) / 256;
-    int64_t row_blocks = kMaxBlocks / col_blocks;
-    if (row_blocks < 1) row_blocks = 1;
-    if (row_blocks > plan.rows) row_blocks = plan.rows;
-    if (row_blocks > 65535) row_blocks = 65535;
-    grid = dim3((unsigned)col_blocks, (unsigned)row_blocks);
+    grid.x = (unsigned)((row_vecs + 255) / 256);
+    groups = kMaxBlocks / grid.x < 1 ? 1 : kMaxBlocks / grid.x;
+    if (groups > 65535) groups = 65535;
   }
+  // consecutive rows per workgroup: a whole number of trips, at least one
+  int64_t per = (plan.rows + groups - 1) / groups;
+  per = (per + plan.rows_per_block - 1) / plan.rows_per_block * plan.rows_per_block;
+  plan.rows_per_group = (uint32_t)per;
+  grid.y = (unsigned)((plan.rows + per - 1) / per);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int flat = n_inner != 1 ? 0 : n_live <= 2 ? 2 : n_live <= 4 ? 4 : 0;
   // whole rows per workgroup: no more lanes than rows_per_block rows need (rounded to wavefronts)
