@@ -19,6 +19,8 @@
 //     32-63: ci+1); the B operand of a lane is one LDS read at (its position's row/col) + tap.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tofu_internal.h"
 #include "tofu_mfma.h"
 
@@ -185,18 +187,33 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
 
   const int steps = (p.CI + CK - 1) / CK;
   constexpr int KS = (CK / 2) * 9;            // MFMA k-steps per step: (channel pair, tap)
-  // Pipeline: the tiles of step t+1 are written to LDS in the middle of step t, and right after
-  // that the global loads of step t+2 are issued into the same registers, so every load has a
-  // whole step to land.  The body is branch-free (the compiler can then count outstanding LDS
-  // operations exactly): the last steps simply stage the final tiles again into the idle buffer.
+  // Staging work of one step = XJ input items + WV weight items.  In a HOT step each item (write
+  // last step's registers to LDS, then reload them for the step after next) is issued between
+  // two k-steps of the MFMA stream, one item every STRIDE k-steps, so that no MFMA waits behind
+  // a block of staging instructions.  Steps whose reload would touch the ragged last channel
+  // step (or weights that are not dense) use the guarded loads in one block instead.
+  constexpr int NI = XJ + WV, STRIDE = (KS - 2) / NI > 0 ? (KS - 2) / NI : 1;
+  static_assert(1 + (NI - 1) * STRIDE < KS, "staging items must fit into one step");
+  const int n_hot = !p.w_fast ? 0 : p.CI % CK == 0 ? steps : max(0, steps - 3);
+
+  // Pipeline: the tiles of step t+1 are written to LDS during step t, and right after each write
+  // the global load of step t+2 is issued into the same register, so every load has a whole step
+  // to land.  The body is branch-free (the compiler can then count outstanding LDS operations
+  // exactly): the last steps simply stage the final tiles again into the idle buffer.
   load_global(0);
   store_lds(0);
   load_global(min(1, steps - 1));
   __syncthreads();
-  for (int t = 0; t < steps; ++t) {
+
+  auto run_step = [&](int t, auto hot_tag) {
+    constexpr bool HOT = decltype(hot_tag)::value;
     const int buf = t & 1;
     const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * 9 * LDM;
     const float* xs = Xs + buf * XB;
+    float* xs_next = Xs + (buf ^ 1) * XB;
+    float* ws_next = Ws + (buf ^ 1) * WB;
+    const int nxt = min(t + 2, steps - 1);
+    const uint32_t x_soff = 4u * (uint32_t)((int64_t)nxt * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt * CK);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
@@ -210,19 +227,33 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s + 1 < KS) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
-      // half-way through the MFMA stream, so that the LDS writes retire in the MFMA shadow
-      if (s == KS / 2) {
+      if (HOT) {
+        if (s >= 1 && (s - 1) % STRIDE == 0 && (s - 1) / STRIDE < NI) {
+          const int item = (s - 1) / STRIDE;
+          if (item < XJ) {
+            xs_next[x_loff[item]] = rx[item];
+            rx[item] = buf_load(x_rsrc, x_voff[item], x_soff);
+          } else {
+            const int i = item - XJ;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) ws_next[w_loff[i] + jj * LDM] = rw[i][jj];
+            rw[i] = buf_load4(w_rsrc, w_voff[i], w_soff);
+          }
+        }
+      } else if (s == KS / 2) {
         store_lds(buf ^ 1);
-        load_global(min(t + 2, steps - 1));
+        load_global(nxt);
       }
+      __builtin_amdgcn_sched_barrier(0);       // keep fetch and staging ahead of the MFMAs they overlap with
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[s & 1][i], b[s & 1][j], acc[i][j]);
     }
     __syncthreads();
-  }
+  };
+  for (int t = 0; t < n_hot; ++t) run_step(t, std::true_type());
+  for (int t = n_hot; t < steps; ++t) run_step(t, std::false_type());
 
 #pragma unroll
   for (int i = 0; i < FM; ++i)

@@ -13,6 +13,8 @@
 // the caller's workspace and sums them in fixed order with the reduce kernel.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tofu_internal.h"
 #include "tofu_mfma.h"
 
@@ -135,8 +137,8 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
 
-  // Pipeline: the tiles of step t+1 are written to LDS in the middle of step t, and right after
-  // that the global loads of step t+2 are issued into the same registers, so every load has a
+  // Pipeline: the tiles of step t+1 are written to LDS during step t, and right after
+  // each write the global loads of step t+2 are issued into the same registers, so every load has a
   // whole step to land.  The body is branch-free (the compiler can then count outstanding LDS
   // operations exactly): the last steps simply stage the final tiles again into the idle buffer.
   if (steps > 0) {
@@ -145,10 +147,24 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     load_global(min(1, steps - 1));
   }
   __syncthreads();
-  for (int t = 0; t < steps; ++t) {
+  // Staging work of one step = AV tiles of A + BV tiles of B per lane.  In a HOT step each item
+  // (write last step's registers to LDS, then reload them for the step after next) is issued
+  // between two k-steps of the MFMA stream, so that no MFMA waits behind a block of staging
+  // instructions.  Steps whose reload would touch a ragged K tail, and operands that need the
+  // guarded element loads, stage in one block instead.
+  constexpr int KS = BK / 2, NI = Cfg::AV + Cfg::BV, STRIDE = (KS - 2) / NI > 0 ? (KS - 2) / NI : 1;
+  static_assert(1 + (NI - 1) * STRIDE < KS, "staging items must fit into one step");
+  const int n_hot = !p.fast ? 0 : (k_end - k_begin) % BK == 0 ? steps : max(0, steps - 3);
+
+  auto run_step = [&](int t, auto hot_tag) {
+    constexpr bool HOT = decltype(hot_tag)::value;
     const int buf = t & 1;
     const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32 + half * LDA;
     const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32 + half * LDB;
+    float* as_next = As + (buf ^ 1) * BK * LDA;
+    float* bs_next = Bs + (buf ^ 1) * BK * LDB;
+    const int nxt = min(t + 2, steps - 1), k0 = k_begin + nxt * BK;
+    const uint32_t a_soff = 4u * (uint32_t)k0, b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
@@ -159,22 +175,36 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     };
     fetch(0, a[0], b[0]);
 #pragma unroll
-    for (int s = 0; s < BK / 2; ++s) {
-      if (s + 1 < BK / 2) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);       // keep the fetch ahead of the MFMAs it overlaps with
-      // next step's tiles go to the other buffer half-way through this step's MFMA stream, so
-      // the LDS writes retire in the shadow of the remaining MFMAs, not in front of the barrier
-      if (s == BK / 4) {
+    for (int s = 0; s < KS; ++s) {
+      if (s + 1 < KS) fetch(s + 1, a[(s + 1) & 1], b[(s + 1) & 1]);
+      if (HOT) {
+        if (s >= 1 && (s - 1) % STRIDE == 0 && (s - 1) / STRIDE < NI) {
+          const int item = (s - 1) / STRIDE;
+          if (item < Cfg::AV) {
+            const int idx = tid + item * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) as_next[(4 * q + j) * LDA + row] = ra[item][j];
+            ra[item] = buf_load4(a_rsrc, a_voff[item], a_soff);
+          } else {
+            const int i = item - Cfg::AV, idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+            *reinterpret_cast<v4f32*>(bs_next + row * LDB + 4 * c) = rb[i];
+            rb[i] = buf_load4(b_rsrc, b_voff[i], b_soff);
+          }
+        }
+      } else if (s == KS / 2) {
         store_lds(buf ^ 1);
-        load_global(min(t + 2, steps - 1));
+        load_global(nxt);
       }
+      __builtin_amdgcn_sched_barrier(0);       // keep fetch and staging ahead of the MFMAs they overlap with
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[s & 1][i], b[s & 1][j], acc[i][j]);
     }
     __syncthreads();
-  }
+  };
+  for (int t = 0; t < n_hot; ++t) run_step(t, std::true_type());
+  for (int t = n_hot; t < steps; ++t) run_step(t, std::false_type());
 
   float* C = p.C + (int64_t)blockIdx.y * p.c_slice;
 #pragma unroll
