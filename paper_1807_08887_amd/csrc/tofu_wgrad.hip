@@ -57,8 +57,9 @@ constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace
 // BALANCED: the workgroup walks a range of units and writes every segment to a workspace slot
 // (even a whole tile: one simple epilogue keeps the register count down); otherwise a workgroup
 // is one whole tile and writes dw directly.
-template <int BM, int BCI, bool FAST, bool BALANCED>
+template <int BM, int BCI, bool FAST, bool BALANCED, int KPT = 0>
 __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(const WgradArgs p) {
+  static_assert(KPT == 0 || (FAST && KPT % 2 == 0 && KPT >= 4), "a compile-time column-pair count needs the fast staging maps");
   constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 2;
   constexpr int D_ITEMS = BM * (kKR / 4), X_ITEMS = BCI * 3 * kLDW;
   constexpr int DJ = (D_ITEMS + NT - 1) / NT, XJ = (X_ITEMS + NT - 1) / NT;
@@ -179,44 +180,107 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 #pragma unroll
   for (int t = 0; t < 9; ++t) acc[t] = acc_zero();
 
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  // Column pairs per step, rounded up to even (the staged columns past CW are zeros) so that the
-  // two operand register sets below alternate without a remainder case.
-  const int KPE = (KP + 1) & ~1;
-  const int half_way = (KPE / 2) & ~1;
-  for (int t = 0; t < steps; ++t) {
-    const int buf = t & 1;
-    // Branch-free body (the compiler can then count outstanding LDS operations exactly): the
-    // last step stages its own tiles again into the idle buffer.
-    load_global(min(t + 1, steps - 1));
-    const float* dsm = &Ds[buf][half][wave * 32 + l32];
-    const float* xsm = &Xs[buf][l32 * kPLX + half];
-    // Two operand register sets alternate: while the nine MFMAs of one column pair run, the
-    // operands of the next pair are fetched into the other set (no register copies).
-    auto fetch = [&](int kp, float& a, float (&b)[9]) {
-      a = dsm[2 * kp * LDD];
-#pragma unroll
-      for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[2 * kp + (tap / 3) * kLDW + tap % 3];
-    };
-    auto fma9 = [&](float a, const float (&b)[9]) {
-#pragma unroll
-      for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
-    };
-    float a0, a1, b0[9], b1[9];
-    fetch(0, a0, b0);
-    for (int kp = 0; kp < KPE; kp += 2) {
-      // the next step's tiles go to the other LDS buffer half-way through, in the MFMA shadow
-      if (kp == half_way) store_lds(buf ^ 1);
-      fetch(kp + 1, a1, b1);
-      __builtin_amdgcn_sched_barrier(0);           // keep each fetch ahead of the MFMAs it overlaps with
-      fma9(a0, b0);
-      fetch(min(kp + 2, KPE - 1), a0, b0);         // past the end: a harmless re-read
-      __builtin_amdgcn_sched_barrier(0);
-      fma9(a1, b1);
-    }
+  if constexpr (KPT > 0) {
+    // Column-pair count known at compile time (KPT == (CW + 1) / 2 rounded up to even): the step
+    // is fully unrolled and the staging work of a lane (DJ dy items, XF x items) is dealt out
+    // over the fetch slots of the step, IPS items per slot, the last two slots left empty.  An
+    // item writes the registers loaded for step t+1 to the idle LDS buffer and reloads them for
+    // step t+2 at once, so no MFMA waits behind a block of staging instructions and every load
+    // has a whole step to land.
+    constexpr int NI = DJ + XF, IPS = (NI + KPT - 3) / (KPT - 2);
+    load_global(0);
+    store_lds(0);
+    load_global(min(1, steps - 1));
     __syncthreads();
+    for (int t = 0; t < steps; ++t) {
+      const int buf = t & 1;
+      const int nxt = min(t + 2, steps - 1);
+      const int n = n_begin + nxt / p.HO, oh = nxt - (nxt / p.HO) * p.HO;
+      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
+      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
+      const float* dsm = &Ds[buf][half][wave * 32 + l32];
+      const float* xsm = &Xs[buf][l32 * kPLX + half];
+      auto fetch = [&](int kp, float& a, float (&b)[9]) {
+        a = dsm[2 * kp * LDD];
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[2 * kp + (tap / 3) * kLDW + tap % 3];
+      };
+      auto fma9 = [&](float a, const float (&b)[9]) {
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
+      };
+      auto stage = [&](int slot) {
+#pragma unroll
+        for (int item = slot * IPS; item < (slot + 1) * IPS && item < NI; ++item) {
+          if (item < DJ) {
+            const int row = d_row + item * (NT / (kKR / 4));
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) Ds[buf ^ 1][4 * d_q + jj][row] = rd[item][jj];
+            rd[item] = buf_load4(d_rsrc, d_voff[item], d_soff);
+          } else {
+            const int j = item - DJ;
+            Xs[buf ^ 1][x_ci * kPLX + x_sub + TPC * j] = rx[j];
+            const int e = x_sub + TPC * j, r = (e >= kLDW) + (e >= 2 * kLDW);
+            const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
+            rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
+          }
+        }
+      };
+      float a0, a1, b0[9], b1[9];
+      fetch(0, a0, b0);
+#pragma unroll
+      for (int kp = 0; kp < KPT; kp += 2) {
+        fetch(kp + 1, a1, b1);
+        stage(kp);
+        __builtin_amdgcn_sched_barrier(0);         // keep fetch and staging ahead of the MFMAs they overlap with
+        fma9(a0, b0);
+        fetch(kp + 2 < KPT ? kp + 2 : KPT - 1, a0, b0);   // past the end: a harmless re-read
+        stage(kp + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        fma9(a1, b1);
+      }
+      __syncthreads();
+    }
+  } else {
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    // Column pairs per step, rounded up to even (the staged columns past CW are zeros) so that the
+    // two operand register sets below alternate without a remainder case.
+    const int KPE = (KP + 1) & ~1;
+    const int half_way = (KPE / 2) & ~1;
+    for (int t = 0; t < steps; ++t) {
+      const int buf = t & 1;
+      // Branch-free body (the compiler can then count outstanding LDS operations exactly): the
+      // last step stages its own tiles again into the idle buffer.
+      load_global(min(t + 1, steps - 1));
+      const float* dsm = &Ds[buf][half][wave * 32 + l32];
+      const float* xsm = &Xs[buf][l32 * kPLX + half];
+      // Two operand register sets alternate: while the nine MFMAs of one column pair run, the
+      // operands of the next pair are fetched into the other set (no register copies).
+      auto fetch = [&](int kp, float& a, float (&b)[9]) {
+        a = dsm[2 * kp * LDD];
+  #pragma unroll
+        for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[2 * kp + (tap / 3) * kLDW + tap % 3];
+      };
+      auto fma9 = [&](float a, const float (&b)[9]) {
+  #pragma unroll
+        for (int tap = 0; tap < 9; ++tap) acc[tap] = mfma_32x32x2(a, b[tap], acc[tap]);
+      };
+      float a0, a1, b0[9], b1[9];
+      fetch(0, a0, b0);
+      for (int kp = 0; kp < KPE; kp += 2) {
+        // the next step's tiles go to the other LDS buffer half-way through, in the MFMA shadow
+        if (kp == half_way) store_lds(buf ^ 1);
+        fetch(kp + 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);           // keep each fetch ahead of the MFMAs it overlaps with
+        fma9(a0, b0);
+        fetch(min(kp + 2, KPE - 1), a0, b0);         // past the end: a harmless re-read
+        __builtin_amdgcn_sched_barrier(0);
+        fma9(a1, b1);
+      }
+      __syncthreads();
+    }
   }
 
   if (BALANCED) {
@@ -363,8 +427,22 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   const size_t need = wgrad_workspace_bytes(CO, CI, NB);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
-  auto kern = need > 0 ? (fast ? wgrad_kernel<gBM, gBCI, true, true> : wgrad_kernel<gBM, gBCI, false, true>)
-                       : (fast ? wgrad_kernel<gBM, gBCI, true, false> : wgrad_kernel<gBM, gBCI, false, false>);
+  // fast shards of the common widths run the fully unrolled step (column pairs rounded up to even)
+  const int kpe = ((p.CW + 1) / 2 + 1) & ~1;
+  void (*kern)(const WgradArgs);
+  if (need > 0) {
+    kern = !fast       ? wgrad_kernel<gBM, gBCI, false, true>
+           : kpe == 8  ? wgrad_kernel<gBM, gBCI, true, true, 8>
+           : kpe == 14 ? wgrad_kernel<gBM, gBCI, true, true, 14>
+           : kpe == 16 ? wgrad_kernel<gBM, gBCI, true, true, 16>
+                       : wgrad_kernel<gBM, gBCI, true, true>;
+  } else {
+    kern = !fast       ? wgrad_kernel<gBM, gBCI, false, false>
+           : kpe == 8  ? wgrad_kernel<gBM, gBCI, true, false, 8>
+           : kpe == 14 ? wgrad_kernel<gBM, gBCI, true, false, 14>
+           : kpe == 16 ? wgrad_kernel<gBM, gBCI, true, false, 16>
+                       : wgrad_kernel<gBM, gBCI, true, false>;
+  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);
   hipError_t e = hipGetLastError();

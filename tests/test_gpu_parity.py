@@ -338,7 +338,11 @@ def run_wgrad(opd, splits, dx, ddy):
 
 
 @pytest.mark.parametrize("batch,c_in,c_out,H,W,pad", [(3, 40, 130, 28, 28, 1), (2, 5, 33, 9, 11, 1), (4, 32, 64, 8, 8, 0),
-                                                      (1, 3, 5, 1, 1, 1), (2, 9, 20, 6, 70, 1)])
+                                                      (1, 3, 5, 1, 1, 1), (2, 9, 20, 6, 70, 1),
+                                                      # widths 16 / 32 / 28 take the unrolled steps, 24 the looped fast one;
+                                                      # H = 1 gives workgroups a single step
+                                                      (2, 32, 128, 16, 16, 1), (3, 33, 40, 6, 32, 1), (2, 20, 30, 5, 24, 1),
+                                                      (1, 8, 8, 1, 16, 1), (5, 64, 256, 2, 28, 1)])
 def test_wgrad_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
     opd = dict(kind="conv2d_wgrad", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=pad)
     ho, wo = H + 2 * pad - 2, W + 2 * pad - 2
