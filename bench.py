@@ -18,6 +18,12 @@ import sys
 import time
 
 PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 matrix peak, HBM3E peak
+# HBM-side bytes per launch of the single-kernel contraction legs, from the two hardware-counter
+# runs summarised in profiles/all_legs_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE in KiB per
+# dispatch, each scaled by the factor that makes the same counter match the 256 MiB
+# calibration copy of that run (2.0 for reads, 1.0 for writes).
+TRAFFIC_KIB = {"conv_cout": (427707.0, 31755.6), "conv_cout_h": (251119.0, 16041.4), "gemm_ksplit": (149614.0, 16384.0)}
+TRAFFIC_SCALE = (2.0, 1.0)
 METRIC = "shard GEMM/conv TFLOP/s (% fp32 MFMA peak); partition-n-reduce GB/s (% HBM)"
 
 
@@ -34,7 +40,7 @@ def cpu_baseline(legs):
             continue
         if h["kind"] == "matmul":
             box = h["box"]
-            n = 1 << 17 if "b_col0" in h else 1 << 19
+            n = 3 << 17 if "b_col0" in h else 3 << 19
             pts = synth.coords(900, 1, n, [b[1] - b[0] for b in box])
             k0, k1 = h["krange"]
             t = time.perf_counter()
@@ -46,7 +52,7 @@ def cpu_baseline(legs):
             flop += 2.0 * n * (k1 - k0)
             parts.append(f"{leg.name}: {n} outputs")
         elif h["kind"] == "conv2d" and leg.name == "conv_cout":
-            n = 1 << 18
+            n = 3 << 18
             shape = [b[1] - b[0] for b in h["box"]]
             pts = synth.coords(900, 2, n, shape)
             t = time.perf_counter()
@@ -55,7 +61,7 @@ def cpu_baseline(legs):
             flop += leg.work * n / float(np.prod(shape))
             parts.append(f"{leg.name}: {n} outputs")
         elif h["kind"] == "wgrad":
-            n = 1 << 17
+            n = 3 << 17
             c = h["x"].shape[1]
             pts = synth.coords(900, 3, n, (c, c, 3, 3))
             t = time.perf_counter()
@@ -74,6 +80,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--legs", type=str, default="", help="comma-separated subset of legs (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain elementwise copy of 256 MiB before the timed steps, so that a "
+                         "hardware-counter run holds a kernel of known traffic to scale its counters by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one worker's shard on ONE GPU; --gpus > 1 is not supported "
@@ -101,6 +110,12 @@ def main():
         if events is not None:
             events[len(legs)].record()
 
+    if args.calibration_copy:      # reads 2^26 floats, writes 2^26 floats (torch's vectorised elementwise kernel)
+        cal_src = torch.empty(1 << 26, dtype=torch.float32, device=dev)    # contents do not matter
+        cal_dst = torch.empty_like(cal_src)
+        torch.mul(cal_src, 1.0, out=cal_dst)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,6 +142,9 @@ def main():
     flop = sum(l.work for l in legs if l.bound == "mfma")
     single_kernel = [e for e in leg_out if e["leg"] in ("conv_cout", "conv_cout_h", "gemm_ksplit")] or leg_out
     dom = max(single_kernel, key=lambda e: e["ms"])
+    traffic = None
+    if dom["leg"] in TRAFFIC_KIB:
+        traffic = round(1024.0 * sum(k * f for k, f in zip(TRAFFIC_KIB[dom["leg"]], TRAFFIC_SCALE)))
     out = {
         "metric": METRIC, "value": round(flop / (ms_per_step * 1e-3) * 1e-12, 3), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -135,7 +153,7 @@ def main():
                    "shapes": "LSTM gate GEMM 128x32768x16384 (8-way N and K shards); 3x3 conv 2560ch 14x14 batch 128 "
                              "(C_out/8 and C_out/8 x H/2 shards, halo fetch); 3x3 wgrad 1280ch 28x28 (batch/8 shard); 8-way reduces"},
         "roofline": {"kernel": dom["leg"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": PEAK[dom["bound"]][0],
-                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic},
         "legs": leg_out,
     }
     if not args.no_cpu_baseline:
