@@ -70,7 +70,43 @@ def cpu_baseline(legs):
             flop += leg.work * n / float(c * c * 9)
             parts.append(f"{leg.name}: {n} outputs")
     return {"value": flop / secs * 1e-12 if secs > 0 else None, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "cpu": cpu_model(),
             "seconds": round(secs, 3), "sample": "seeded output coordinates, every term of each sum: " + "; ".join(parts)}
+
+
+def attainable(torch, tofu, dev):
+    """The two probes of include/tofu_probe.h: what a register-only MFMA loop and a plain copy
+    larger than the last-level cache reach on this GPU (median of 5 launches each)."""
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
+    dst = torch.empty_like(src)
+    wgs, iters = 2048, 4096
+
+    def timed(fn):
+        fn()
+        ms = []
+        for _ in range(5):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            ms.append(a.elapsed_time(b))
+        return sorted(ms)[2]
+    t_mfma = timed(lambda: tofu.probe_mfma(sink, iters, wgs))
+    t_copy = timed(lambda: tofu.probe_copy(dst, src))
+    return {"mfma_loop_tflops": round(wgs * 4 * iters * 8 * 4096 / t_mfma * 1e-9, 1),
+            "copy_1gib_gbs": round(2 * src.numel() * 4 / t_copy * 1e-6, 1)}
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main():
@@ -98,6 +134,7 @@ def main():
     tofu.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    peaks = attainable(torch, tofu, dev)
     which = [s for s in args.legs.split(",") if s] or None
     legs = tofu_workloads.build(dev, which, keep_host=not args.no_cpu_baseline)
     torch.cuda.synchronize()
@@ -154,6 +191,7 @@ def main():
                              "(C_out/8 and C_out/8 x H/2 shards, halo fetch); 3x3 wgrad 1280ch 28x28 (batch/8 shard); 8-way reduces"},
         "roofline": {"kernel": dom["leg"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": PEAK[dom["bound"]][0],
                      "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic},
+        "attainable": peaks,
         "legs": leg_out,
     }
     if not args.no_cpu_baseline:

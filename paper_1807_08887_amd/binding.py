@@ -85,8 +85,10 @@ def load():
     for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad"):
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
+    lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
+    lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -206,3 +208,15 @@ def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, strea
         count = dst.numel()
     ptrs = (ctypes.c_void_p * max(1, len(partials)))(*[addr(p) for p in partials])
     _check(load().tofu_partition_reduce(ctypes.c_void_p(addr(dst)), ptrs, len(partials), count, _stream(stream)))
+
+
+def probe_mfma(sink, iters: int, workgroups: int, stream=None) -> None:
+    """include/tofu_probe.h: register-only fp32 MFMA loop; FLOP = workgroups * 4 * iters * 8 * 4096."""
+    _check(load().tofu_probe_mfma(ctypes.c_void_p(sink.data_ptr()), iters, workgroups, _stream(stream)))
+
+
+def probe_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
+    """include/tofu_probe.h: plain 16-byte-vector copy between two device tensors."""
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    _check(load().tofu_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes, _stream(stream)))

@@ -387,3 +387,17 @@ def test_runs_are_bit_identical():
     c1 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
     c2 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
     assert np.array_equal(c1, c2)
+
+
+# ----------------------------------------------------------------------------- probes
+def test_probes_copy_exactly_and_leave_the_sink_alone():
+    """The measurement aids of tofu_probe.h: the copy is bit-exact on a ragged vector count,
+    the MFMA loop writes nothing."""
+    src = dev(synth.normal(77, 0, (4 * 100003,), 1.0))
+    dst = torch.zeros_like(src)
+    tofu.probe_copy(dst, src)
+    assert torch.equal(dst, src)
+    sink = torch.full((64,), 3.0, dtype=torch.float32, device=DEV)
+    tofu.probe_mfma(sink, 16, 8)
+    torch.cuda.synchronize()
+    assert (sink == 3.0).all()

@@ -17,14 +17,18 @@ FAKE = 0x7F0000000000        # a non-null "device pointer"; nothing below ever d
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "tofu.h")).read()
-    names = set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", header))
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_probe.h"]
+    names = set()
+    for h in headers:
+        names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
-            "tofu_last_error"} <= names
+            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
-        assert hasattr(lib, n), f"{n} is declared in tofu.h but not exported"
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
 
 
 def test_shard_range_matches_oracle_exhaustively():
@@ -184,3 +188,16 @@ def test_reduce_error_paths_are_checked_on_the_host():
     assert lib.tofu_partition_reduce(None, ptrs, 2, 16, None) == -1
     assert lib.tofu_partition_reduce(None, ptrs, 2, 0, None) == 0                              # empty is a no-op
     assert "k = 17" in tofu.last_error() or tofu.last_error()
+
+
+def test_probe_error_paths_are_checked_on_the_host():
+    lib = tofu.load()
+    vp = ctypes.c_void_p
+    assert lib.tofu_probe_mfma(vp(0), 1, 1, None) == -1
+    assert lib.tofu_probe_mfma(vp(FAKE), 0, 1, None) == -1
+    assert lib.tofu_probe_mfma(vp(FAKE), 1, 0, None) == -1
+    assert lib.tofu_probe_copy(vp(0), vp(FAKE), 16, None) == -1
+    assert lib.tofu_probe_copy(vp(FAKE), vp(FAKE + 4096), 24, None) == -1      # not a multiple of 16
+    assert lib.tofu_probe_copy(vp(FAKE + 4), vp(FAKE + 4096), 16, None) == -1  # misaligned
+    assert lib.tofu_probe_copy(vp(FAKE), vp(FAKE + 4096), 0, None) == 0        # nothing to do, nothing launched
+    assert "copy probe" in tofu.last_error() or tofu.last_error() is not None
