@@ -136,7 +136,10 @@ def main():
     torch.cuda.set_device(0)
     peaks = attainable(torch, tofu, dev)
     which = [s for s in args.legs.split(",") if s] or None
-    legs = tofu_workloads.build(dev, which, keep_host=not args.no_cpu_baseline)
+    names = which if which else list(tofu_workloads.STEP_LEGS) + list(tofu_workloads.EXTRA_LEGS)
+    built = tofu_workloads.build(dev, names, keep_host=not args.no_cpu_baseline)
+    legs = [l for l in built if l.name not in tofu_workloads.EXTRA_LEGS or which]
+    extra_legs = [l for l in built if l not in legs]
     torch.cuda.synchronize()
 
     def step(events=None):
@@ -194,6 +197,24 @@ def main():
         "attainable": peaks,
         "legs": leg_out,
     }
+    if extra_legs:
+        # outside the step: the <C_out/8, H/2> shard with the fetch fused into the convolution,
+        # timed right after the steps (same buffers, warm clocks)
+        extras = []
+        for leg in extra_legs:
+            for _ in range(3):
+                leg.run()
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+            for i in range(10):
+                e[i].record()
+                leg.run()
+            e[10].record()
+            torch.cuda.synchronize()
+            ms = sorted(e[i].elapsed_time(e[i + 1]) for i in range(10))[5]
+            extras.append({"leg": leg.name, "bound": "mfma", "ms": round(ms, 4), "achieved": round(leg.work / ms * 1e-9, 2),
+                           "unit": "TFLOP/s", "frac": round(leg.work / ms * 1e-9 / PEAK["mfma"][0], 4),
+                           "note": "replaces fetch_halo + conv_cout_h; median of 10 launches back to back"})
+        out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(legs)
     print(json.dumps(out))

@@ -138,7 +138,7 @@ const char* tofu_last_error(void);
  * dst->extent exactly: a hole -> UNCOVERED, a doubly-claimed coordinate ->
  * OVERLAP (both detected on the host from the boxes alone).  All tensors
  * must have the same ndim (1..TOFU_MAX_DIMS).  An empty dst->extent is a
- * no-op.  nsrc is limited to 64.  dst must not alias any source. */
+ * no-op.  nsrc is limited to 16.  dst must not alias any source. */
 int tofu_region_fetch(const tofu_tensor_t* dst, const tofu_tensor_t* srcs, int32_t nsrc,
                       void* hip_stream);
 
@@ -160,6 +160,21 @@ int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int3
 int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                       const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The same convolution shard with the fetch fused into it (Sec. 6: the
+ * consumer reads its input region straight from the blocks that hold it, so
+ * no assembled copy of the region exists).  `x_srcs` is a HOST array of
+ * 1 <= nsrc <= 16 descriptors of DEVICE blocks of the global input tensor.
+ * Clipped to the input box tofu_op_regions derives, the blocks must tile that
+ * box exactly (a hole -> UNCOVERED, a coordinate held twice -> OVERLAP), and
+ * every block that holds part of the box must span all of the box's channels
+ * (blocks cut along N, H or W -- the halo case); otherwise UNSUPPORTED and the
+ * caller assembles the region with tofu_region_fetch.  Results are bit-identical
+ * to tofu_shard_conv2d on the assembled region.  Other rules as above. */
+int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                            const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w,
+                            const tofu_tensor_t* y, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
 
 /* Shard of the convolution's weight gradient.  The batch index is a
  * reduction index of this operator, so a batch split is Case-2 (Sec. 4.2)

@@ -84,11 +84,12 @@ def load():
     lib.tofu_region_fetch.argtypes = [P(Tensor), P(Tensor), i32, vp]
     for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad"):
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
+    lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -190,6 +191,15 @@ def shard_matmul(op, splits, A: Tensor, B: Tensor, C: Tensor, workspace=None, st
 
 def shard_conv2d(op, splits, x: Tensor, w: Tensor, y: Tensor, workspace=None, stream=None) -> None:
     _shard(load().tofu_shard_conv2d, op, splits, x, w, y, workspace, stream)
+
+
+def shard_conv2d_fused(op, splits, x_srcs: Sequence[Tensor], w: Tensor, y: Tensor, workspace=None, stream=None) -> None:
+    """tofu_shard_conv2d_fused: the input region is read from the blocks `x_srcs` that hold it."""
+    sp, n = _splits(splits)
+    arr = (Tensor * max(1, len(x_srcs)))(*x_srcs)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size())
+    _check(load().tofu_shard_conv2d_fused(ctypes.byref(op), sp, n, arr, len(x_srcs), ctypes.byref(w), ctypes.byref(y), ws_ptr, ws_bytes,
+                                          _stream(stream)))
 
 
 def shard_conv2d_wgrad(op, splits, x: Tensor, dy: Tensor, dw: Tensor, workspace=None, stream=None) -> None:

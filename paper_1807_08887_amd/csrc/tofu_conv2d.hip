@@ -44,6 +44,21 @@ struct ConvArgs {
   int w_fast;       // 1: weights dense over (ci,kh,kw) and 16-byte aligned -> vector loads
 };
 
+// Input region held by several blocks (the fetch fused into the consumer, Sec. 6): every block
+// spans the region's channels and holds a box of its (image, row, column) coordinates.
+constexpr int kMaxConvSources = 16;
+struct ConvSrc {
+  const float* base;   // address the region's low corner WOULD have inside this block
+  int64_t s[4];        // element strides (n, c, h, w) of the block
+  int lo[3], hi[3];    // (image, row, column) box held, relative to the region's low corner
+};
+struct ConvSources {
+  int n;
+  ConvSrc src[kMaxConvSources];
+};
+// Lanes with nothing to read (zero border, idle staging slots) load from here in the multi-block kernels.
+__device__ float kZeroWords[64];
+
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
 struct ConvCfg {
   static constexpr int kThreads = 64 * WM * WN;
@@ -58,8 +73,8 @@ struct ConvCfg {
   static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ>
-__global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI>
+__device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources* srcs) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
   constexpr uint32_t kNone = kNoOffset;
@@ -94,7 +109,9 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
   const int E = (T_b - T_a + 1) * LDW;        // staged floats per channel for this tile
 
   // ---- per-thread staging lists, fixed for the whole K loop ----
-  uint32_t x_voff[XJ];   // byte offset of the element inside channel step 0, kNone = reads as zero
+  uint32_t x_voff[MULTI ? 1 : XJ];   // byte offset of the element inside channel step 0, kNone = reads as zero
+  const float* x_ptr[MULTI ? XJ : 1];  // multi-block form: address of the element inside channel step 0 ...
+  int x_inc[MULTI ? XJ : 1];           // ... and its element increment per channel step (0 for lanes that read zeros)
   int x_loff[XJ];        // LDS float index inside one x buffer (or its scratch tail)
 #pragma unroll
   for (int j = 0; j < XJ; ++j) {
@@ -107,7 +124,19 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     const bool live = ci_l < CK && rem < E;
     const bool valid = live && img < p.NB && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
     x_loff[j] = live ? ci_l * PL + rem : CK * PL + lane;
-    x_voff[j] = valid ? 4u * (uint32_t)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : kNone;
+    if constexpr (MULTI) {
+      x_ptr[j] = kZeroWords;
+      x_inc[j] = 0;
+      for (int b = 0; b < srcs->n; ++b) {     // the blocks tile the region: at most one of them holds the coordinate
+        const ConvSrc& S = srcs->src[b];
+        if (valid && img >= S.lo[0] && img < S.hi[0] && ih >= S.lo[1] && ih < S.hi[1] && iw >= S.lo[2] && iw < S.hi[2]) {
+          x_ptr[j] = S.base + ((int64_t)img * S.s[0] + (int64_t)ci_l * S.s[1] + (int64_t)ih * S.s[2] + (int64_t)iw * S.s[3]);
+          x_inc[j] = CK * (int)S.s[1];
+        }
+      }
+    } else {
+      x_voff[j] = valid ? 4u * (uint32_t)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : kNone;
+    }
   }
   uint32_t w_voff[WV];
   int w_loff[WV];
@@ -126,15 +155,24 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
   auto load_global = [&](int step) {
     const int ci0 = step * CK;
     const bool whole = ci0 + CK <= p.CI;        // only the last step can run past the shard's channels
-    const uint32_t x_soff = 4u * (uint32_t)((int64_t)ci0 * p.xs[1]);
-    if (whole) {
-#pragma unroll
-      for (int j = 0; j < XJ; ++j) rx[j] = buf_load(x_rsrc, x_voff[j], x_soff);
-    } else {
+    if constexpr (MULTI) {
 #pragma unroll
       for (int j = 0; j < XJ; ++j) {
-        const bool ok = ci0 + (tid + j * NT) / p.E < p.CI;
-        rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNone, x_soff);
+        const bool ok = whole || ci0 + (tid + j * NT) / p.E < p.CI;
+        const float* src = x_ptr[j] + (int64_t)step * x_inc[j];
+        rx[j] = *(ok ? src : kZeroWords);
+      }
+    } else {
+      const uint32_t x_soff = 4u * (uint32_t)((int64_t)ci0 * p.xs[1]);
+      if (whole) {
+#pragma unroll
+        for (int j = 0; j < XJ; ++j) rx[j] = buf_load(x_rsrc, x_voff[j], x_soff);
+      } else {
+#pragma unroll
+        for (int j = 0; j < XJ; ++j) {
+          const bool ok = ci0 + (tid + j * NT) / p.E < p.CI;
+          rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNone, x_soff);
+        }
       }
     }
     if (p.w_fast && whole) {
@@ -213,7 +251,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     float* xs_next = Xs + (buf ^ 1) * XB;
     float* ws_next = Ws + (buf ^ 1) * WB;
     const int nxt = min(t + 2, steps - 1);
-    const uint32_t x_soff = 4u * (uint32_t)((int64_t)nxt * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt * CK);
+    const uint32_t x_soff = MULTI ? 0u : 4u * (uint32_t)((int64_t)nxt * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt * CK);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
@@ -232,7 +270,8 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
           const int item = (s - 1) / STRIDE;
           if (item < XJ) {
             xs_next[x_loff[item]] = rx[item];
-            rx[item] = buf_load(x_rsrc, x_voff[item], x_soff);
+            if constexpr (MULTI) rx[item] = x_ptr[item][(int64_t)nxt * x_inc[item]];
+            else rx[item] = buf_load(x_rsrc, x_voff[item], x_soff);
           } else {
             const int i = item - XJ;
 #pragma unroll
@@ -268,6 +307,18 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs 
     }
 }
 
+// input region in one buffer
+template <int BM, int BN, int CK, int WM, int WN, int XJ>
+__global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
+  conv2d_body<BM, BN, CK, WM, WN, XJ, false>(p, nullptr);
+}
+
+// input region read from the blocks that hold it
+template <int BM, int BN, int CK, int WM, int WN, int XJ>
+__global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_multi_kernel(const ConvArgs p, const ConvSources srcs) {
+  conv2d_body<BM, BN, CK, WM, WN, XJ, true>(p, &srcs);
+}
+
 constexpr size_t kLdsLimit = 160 * 1024;
 
 // Most floats per channel any tile of BN consecutive positions stages (rows touched + halo rows).
@@ -283,7 +334,7 @@ static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN) {
 }
 
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
-static int launch_conv(ConvArgs p, int64_t E, hipStream_t stream) {
+static int launch_conv(ConvArgs p, const ConvSources* srcs, int64_t E, hipStream_t stream) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   p.tiles_m = (p.CO + BM - 1) / BM;
   p.tiles_n = (p.P + BN - 1) / BN;
@@ -292,26 +343,27 @@ static int launch_conv(ConvArgs p, int64_t E, hipStream_t stream) {
   const size_t lds_bytes = sizeof(float) * Cfg::lds_floats(p.PL);
   if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
   auto kern = conv2d_kernel<BM, BN, CK, WM, WN, XJ>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+  auto kern_multi = conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ>;
+  static bool attr_set[2] = {false, false};
+  const int which = srcs ? 1 : 0;
+  if (!attr_set[which]) {
+    const void* fn = srcs ? reinterpret_cast<const void*>(kern_multi) : reinterpret_cast<const void*>(kern);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
-    attr_set = true;
+    attr_set[which] = true;
   }
   const int total = p.tiles_m * p.tiles_n;
-  hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p);
+  if (srcs) hipLaunchKernelGGL(kern_multi, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p, *srcs);
+  else hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d launch failed: %s", hipGetErrorString(e));
   return TOFU_OK;
 }
 
-}  // namespace tofu
-
-extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
-                                 const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
-  using namespace tofu;
-  (void)workspace; (void)workspace_bytes;
+// Shared by the two entry points: `x` is the single buffer that holds the input region, or NULL
+// when the region is read from the `nsrc` blocks `x_srcs`.
+static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
+                        const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y, void* hip_stream) {
   if (!op || op->kind != TOFU_OP_CONV2D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d");
   tofu_region_t out_box, in_boxes[2];
   int64_t pad_lo[2], pad_hi[2];
@@ -320,27 +372,58 @@ extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* s
   if (rc) return rc;
   if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1)
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d kernels implement KH = KW = 3, stride 1, pad 0 or 1");
-  if ((rc = check_tensor("x", x, 4, &in_boxes[0]))) return rc;
+  const bool multi = x == nullptr;
+  tofu_region_t inter[kMaxConvSources];
+  if (multi) {
+    if (nsrc < 1 || nsrc > kMaxConvSources) return fail(TOFU_ERR_INVALID_ARG, "nsrc = %d outside [1,%d]", (int)nsrc, kMaxConvSources);
+    if (!x_srcs) return fail(TOFU_ERR_INVALID_ARG, "x_srcs is NULL");
+    if ((rc = check_tiling("x_srcs", &in_boxes[0], x_srcs, nsrc, inter))) return rc;
+  } else if ((rc = check_tensor("x", x, 4, &in_boxes[0]))) {
+    return rc;
+  }
   if ((rc = check_tensor("w", w, 4, &in_boxes[1]))) return rc;
   if ((rc = check_tensor("y", y, 4, &out_box))) return rc;
   if (volume(&out_box) == 0) return TOFU_OK;
 
-  int64_t xs[4], ws[4], ys[4];
-  effective_strides(x, xs);
+  int64_t xs[4] = {0, 0, 0, 0}, ws[4], ys[4];
   effective_strides(w, ws);
   effective_strides(y, ys);
   ConvArgs p;
-  p.x = element_ptr(x, xs, in_boxes[0].lo);
   p.w = element_ptr(w, ws, in_boxes[1].lo);
   p.y = const_cast<float*>(element_ptr(y, ys, out_box.lo));
-  for (int d = 0; d < 4; ++d) { p.xs[d] = xs[d]; p.ws[d] = ws[d]; p.ys[d] = ys[d]; }
   const int64_t NB = out_box.hi[0] - out_box.lo[0], CO = out_box.hi[1] - out_box.lo[1];
   const int64_t BH = out_box.hi[2] - out_box.lo[2], BW = out_box.hi[3] - out_box.lo[3];
   const int64_t CI = in_boxes[0].hi[1] - in_boxes[0].lo[1];
   const int64_t P = NB * BH * BW;
   if (P >= (1 << 30) || CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
-  // lanes address the input and the filters with 32-bit byte offsets from the boxes' low corners
+  // lanes address the filters (and a single input buffer) with 32-bit byte offsets from the boxes' low corners
   int64_t x_span = 1, w_span = 1;
+  ConvSources srcs;
+  srcs.n = 0;
+  if (multi) {
+    p.x = nullptr;
+    for (int j = 0; j < nsrc; ++j) {
+      if (volume(&inter[j]) == 0) continue;
+      if (inter[j].lo[1] != in_boxes[0].lo[1] || inter[j].hi[1] != in_boxes[0].hi[1])
+        return fail(TOFU_ERR_UNSUPPORTED, "conv2d: x_srcs[%d] holds only part of the region's channels; assemble the region with tofu_region_fetch", j);
+      ConvSrc& S = srcs.src[srcs.n++];
+      int64_t st[4];
+      effective_strides(&x_srcs[j], st);
+      S.base = element_ptr(&x_srcs[j], st, in_boxes[0].lo);
+      for (int d = 0; d < 4; ++d) S.s[d] = st[d];
+      if (st[1] >= ((int64_t)1 << 27) || st[1] <= -((int64_t)1 << 27))
+        return fail(TOFU_ERR_UNSUPPORTED, "conv2d: channel stride of x_srcs[%d] does not fit the kernel's 32-bit step", j);
+      const int dims[3] = {0, 2, 3};
+      for (int i = 0; i < 3; ++i) {
+        S.lo[i] = (int)(inter[j].lo[dims[i]] - in_boxes[0].lo[dims[i]]);
+        S.hi[i] = (int)(inter[j].hi[dims[i]] - in_boxes[0].lo[dims[i]]);
+      }
+    }
+  } else {
+    effective_strides(x, xs);
+    p.x = element_ptr(x, xs, in_boxes[0].lo);
+  }
+  for (int d = 0; d < 4; ++d) { p.xs[d] = xs[d]; p.ws[d] = ws[d]; p.ys[d] = ys[d]; }
   for (int d = 0; d < 4; ++d) {
     if (xs[d] < 0 || ws[d] < 0) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: negative strides are not supported");
     x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
@@ -348,7 +431,7 @@ extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* s
   }
   if (x_span >= ((int64_t)1 << 29) || w_span >= ((int64_t)1 << 29))
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d: an operand region spans 2 GiB or more");
-  p.x_bytes = (uint32_t)(4 * x_span);
+  p.x_bytes = multi ? 0u : (uint32_t)(4 * x_span);
   p.w_bytes = (uint32_t)(4 * w_span);
   p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
   p.IH = (int)(in_boxes[0].hi[2] - in_boxes[0].lo[2]);
@@ -357,14 +440,32 @@ extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* s
   p.LDW = (int)BW + 2;
   p.w_fast = ws[3] == 1 && ws[2] == 3 && ws[1] == 9 && ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const ConvSources* sp = multi ? &srcs : nullptr;
 
   // Tile choice: 256 positions per workgroup (64x64 per wavefront) when that still leaves about two
   // workgroups for each of the 256 compute units, else 128 positions; fewer channels per step
   // when the staged rows are wide.
   const int64_t tiles_m = (CO + 63) / 64;
   const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
-  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, E256, stream);
-  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, E128, stream);
-  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, E128, stream);
+  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, sp, E256, stream);
+  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, sp, E128, stream);
+  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, sp, E128, stream);
   return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)E128);
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!x) return tofu::fail(TOFU_ERR_INVALID_ARG, "x is NULL");
+  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, hip_stream);
+}
+
+extern "C" int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, hip_stream);
 }

@@ -194,30 +194,7 @@ extern "C" int tofu_region_fetch(const tofu_tensor_t* dst, const tofu_tensor_t* 
 
   // ---- intersections and the exact-tiling proof ----
   tofu_region_t inter[kMaxFetchSources];
-  int64_t covered = 0;
-  for (int j = 0; j < nsrc; ++j) {
-    char name[24];
-    snprintf(name, sizeof(name), "srcs[%d]", j);
-    rc = check_tensor(name, &srcs[j], nd, nullptr);
-    if (rc) return rc;
-    inter[j].ndim = nd;
-    for (int d = 0; d < nd; ++d) {
-      inter[j].lo[d] = srcs[j].extent.lo[d] > dst->extent.lo[d] ? srcs[j].extent.lo[d] : dst->extent.lo[d];
-      inter[j].hi[d] = srcs[j].extent.hi[d] < dst->extent.hi[d] ? srcs[j].extent.hi[d] : dst->extent.hi[d];
-    }
-    int64_t v = volume(&inter[j]);
-    if (v == 0) continue;
-    if (!srcs[j].data) return fail(TOFU_ERR_INVALID_ARG, "srcs[%d] has a NULL data pointer", j);
-    for (int i = 0; i < j; ++i) {
-      if (volume(&inter[i]) == 0) continue;
-      bool disjoint = false;
-      for (int d = 0; d < nd; ++d) disjoint = disjoint || inter[i].hi[d] <= inter[j].lo[d] || inter[j].hi[d] <= inter[i].lo[d];
-      if (!disjoint) return fail(TOFU_ERR_OVERLAP, "srcs[%d] and srcs[%d] both hold part of the destination region", i, j);
-    }
-    covered += v;
-  }
-  if (covered != want)
-    return fail(TOFU_ERR_UNCOVERED, "sources hold %lld of the %lld elements of the destination region", (long long)covered, (long long)want);
+  if ((rc = check_tiling("srcs", &dst->extent, srcs, nsrc, inter))) return rc;
 
   // ---- gather the live sources: strides, and their boxes relative to the destination box ----
   struct Live {

@@ -173,6 +173,36 @@ int check_tensor(const char* name, const tofu_tensor_t* t, int32_t ndim, const t
   return TOFU_OK;
 }
 
+int check_tiling(const char* name, const tofu_region_t* want, const tofu_tensor_t* srcs, int32_t nsrc, tofu_region_t* inter) {
+  const int nd = want->ndim;
+  const int64_t need = volume(want);
+  int64_t covered = 0;
+  for (int j = 0; j < nsrc; ++j) {
+    char item[40];
+    snprintf(item, sizeof(item), "%s[%d]", name, j);
+    int rc = check_tensor(item, &srcs[j], nd, nullptr);
+    if (rc) return rc;
+    inter[j].ndim = nd;
+    for (int d = 0; d < nd; ++d) {
+      inter[j].lo[d] = srcs[j].extent.lo[d] > want->lo[d] ? srcs[j].extent.lo[d] : want->lo[d];
+      inter[j].hi[d] = srcs[j].extent.hi[d] < want->hi[d] ? srcs[j].extent.hi[d] : want->hi[d];
+    }
+    const int64_t v = volume(&inter[j]);
+    if (v == 0) continue;
+    if (!srcs[j].data) return fail(TOFU_ERR_INVALID_ARG, "%s has a NULL data pointer", item);
+    for (int i = 0; i < j; ++i) {
+      if (volume(&inter[i]) == 0) continue;
+      bool disjoint = false;
+      for (int d = 0; d < nd; ++d) disjoint = disjoint || inter[i].hi[d] <= inter[j].lo[d] || inter[j].hi[d] <= inter[i].lo[d];
+      if (!disjoint) return fail(TOFU_ERR_OVERLAP, "%s[%d] and %s[%d] both hold part of the wanted region", name, i, name, j);
+    }
+    covered += v;
+  }
+  if (covered != need)
+    return fail(TOFU_ERR_UNCOVERED, "%s hold %lld of the %lld elements of the wanted region", name, (long long)covered, (long long)need);
+  return TOFU_OK;
+}
+
 const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const int64_t* coord) {
   const float* p = static_cast<const float*>(t->data);
   for (int d = 0; d < t->extent.ndim; ++d) p += (coord[d] - t->extent.lo[d]) * stride[d];

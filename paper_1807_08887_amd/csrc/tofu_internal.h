@@ -38,6 +38,12 @@ int64_t volume(const tofu_region_t* r);
 // Validate a tensor argument: non-null, ndim as expected, lo <= hi, and extent contains `need`.
 int check_tensor(const char* name, const tofu_tensor_t* t, int32_t ndim, const tofu_region_t* need);
 
+// Proof that the boxes of `srcs` tile the box `want` exactly once they are clipped to it:
+// pairwise disjoint (else TOFU_ERR_OVERLAP) and of the same total volume (else TOFU_ERR_UNCOVERED).
+// inter[j] receives the clipped box of srcs[j] (possibly empty); sources that hold part of the
+// box must have a data pointer.  `name` labels the array in error messages.
+int check_tiling(const char* name, const tofu_region_t* want, const tofu_tensor_t* srcs, int32_t nsrc, tofu_region_t* inter);
+
 // Pointer to the element at global coordinate `coord` (which must lie inside the extent).
 const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const int64_t* coord);
 

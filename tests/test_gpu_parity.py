@@ -328,6 +328,79 @@ def test_conv2d_on_fetched_halo_region():
     assert e.value.status == -2
 
 
+def blocks_of(x, cuts):
+    """Cut the global array x into blocks along (N, H, W) at the given cut points; returns
+    [(device block, low corner)] in row-major block order (every block spans all channels)."""
+    out = []
+    n_cuts, h_cuts, w_cuts = cuts
+    for (n0, n1), (h0, h1), (w0, w1) in itertools.product(zip(n_cuts, n_cuts[1:]), zip(h_cuts, h_cuts[1:]), zip(w_cuts, w_cuts[1:])):
+        out.append((dev(x[n0:n1, :, h0:h1, w0:w1].copy()), [n0, 0, h0, w0]))
+    return out
+
+
+@pytest.mark.parametrize("shape,cuts", [
+    ((5, 16, 64, 14, 14), ([0, 5], [0, 7, 14], [0, 14])),             # the halo case: two row blocks
+    ((4, 9, 70, 12, 10), ([0, 1, 4], [0, 5, 6, 12], [0, 3, 10])),     # blocks cut along N, H and W, one row high
+    ((3, 7, 33, 9, 30), ([0, 3], [0, 9], [0, 11, 30])),               # ragged channel tail, 128-position tiles
+])
+def test_conv2d_fused_fetch_matches_oracle_and_the_assembled_region(shape, cuts):
+    """The convolution that reads its region straight from the blocks holding it: against the
+    oracle on the global tensor, and bit for bit against fetch-then-convolve, for every shard
+    of a <CO/2, H/2> plan and for the unpartitioned operator."""
+    batch, c_in, c_out, H, W = shape
+    opd = dict(kind="conv2d", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(47, 0, (batch, c_in, H, W), 1.0)
+    w = synth.normal(47, 1, (c_out, c_in, 3, 3), 0.3)
+    val, absum = oracle.conv2d_box(x, w, pad=1)
+    blocks = blocks_of(x, cuts)
+    srcs = [tofu.tensor(t, lo) for t, lo in blocks]
+    dw = dev(w)
+    op = tofu.conv2d_desc(batch, c_in, c_out, H, W)
+    plans = [[]] + [[("CO", 2, a), ("H", 2, b)] for a, b in itertools.product(range(2), repeat=2)]
+    for plan in plans:
+        sp = [(CONV_DIMS[d], k, s) for d, k, s in plan]
+        reg = R.op_regions(opd, plan)
+        y = torch.full((batch, c_out, H, W), float("nan"), dtype=torch.float32, device=DEV)
+        tofu.shard_conv2d_fused(op, sp, srcs, tofu.tensor(dw), tofu.tensor(y))
+        sl = R.box_slices(reg["out_box"])
+        got = y.cpu().numpy()
+        assert_close(got[sl], val[sl], absum[sl], f"fused conv {plan}")
+        mask = np.ones(got.shape, bool)
+        mask[sl] = False
+        assert np.isnan(got[mask]).all(), "wrote outside the shard's output box"
+        box = reg["in_boxes"][0]
+        region = torch.empty([hi - lo for lo, hi in box], dtype=torch.float32, device=DEV)
+        tofu.region_fetch(tofu.tensor(region, [lo for lo, _ in box]), srcs)
+        y2 = run_conv(opd, plan, region, dw, x_lo=[lo for lo, _ in box])
+        assert torch.equal(y[sl], y2[sl]), f"fused and fetched results differ for {plan}"
+
+
+def test_conv2d_fused_fetch_error_paths():
+    opd = dict(kind="conv2d", batch=2, c_in=8, c_out=64, H=8, W=8, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(48, 0, (2, 8, 8, 8), 1.0)
+    dw = dev(synth.normal(48, 1, (64, 8, 3, 3), 0.3))
+    op = tofu.conv2d_desc(2, 8, 64, 8, 8)
+    y = torch.zeros(2, 64, 8, 8, dtype=torch.float32, device=DEV)
+    top, bottom = dev(x[:, :, 0:4].copy()), dev(x[:, :, 4:8].copy())
+    call = lambda srcs, sp=(): tofu.shard_conv2d_fused(op, list(sp), srcs, tofu.tensor(dw), tofu.tensor(y))
+    with pytest.raises(tofu.TofuError) as e:           # a missing row block is a hole, never zeros
+        call([tofu.tensor(top, [0, 0, 0, 0])])
+    assert e.value.status == -3
+    with pytest.raises(tofu.TofuError) as e:           # the same rows held twice
+        call([tofu.tensor(top, [0, 0, 0, 0]), tofu.tensor(bottom, [0, 0, 4, 0]), tofu.tensor(top, [0, 0, 0, 0])])
+    assert e.value.status == -4
+    lo_c, hi_c = dev(x[:, 0:4].copy()), dev(x[:, 4:8].copy())
+    with pytest.raises(tofu.TofuError) as e:           # blocks cut along the channels need the fetch
+        call([tofu.tensor(lo_c, [0, 0, 0, 0]), tofu.tensor(hi_c, [0, 4, 0, 0])])
+    assert e.value.status == -6
+    with pytest.raises(tofu.TofuError) as e:
+        call([])
+    assert e.value.status == -1
+    # a shard that needs only the top rows is served by the top block alone
+    call([tofu.tensor(top, [0, 0, 0, 0])], sp=[(CONV_DIMS["H"], 4, 0)])
+    torch.cuda.synchronize()
+
+
 # ----------------------------------------------------------------------------- wgrad
 def run_wgrad(opd, splits, dx, ddy):
     op = tofu.wgrad_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["H"], opd["W"], pad=opd["pad"])

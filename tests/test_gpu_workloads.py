@@ -44,7 +44,7 @@ def _check_reduce(leg):
 
 
 @pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_ksplit", "reduce_gates"),
-                                   ("conv_cout", "fetch_halo", "conv_cout_h"), ("wgrad_batch", "reduce_dw")])
+                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw")])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)
     legs = tofu_workloads.build("cuda:0", group)
@@ -73,6 +73,9 @@ def test_full_size_legs(group):
             opts[:, 2] += h0      # output row in global coordinates; channels stay local to the shard's filters
             val, absum = oracle.conv2d_pts(h["x"], h["w"], opts, stride=1, pad=1)
             _close(y[tuple(pts.T)], val, absum, leg.name)
+            if leg.name == "conv_cout_h_fused":   # reading the blocks directly changes no bit of the result
+                fetched = next(l for l in legs if l.name == "conv_cout_h")
+                assert torch.equal(leg.out, fetched.out)
         elif h["kind"] == "wgrad":
             dw = leg.out.cpu().numpy()
             pts = _points(73, 2048, dw.shape)

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
         names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
-            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy"} <= names
+            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
@@ -175,6 +175,25 @@ def test_shard_call_error_paths_are_checked_on_the_host():
         tofu.shard_conv2d_wgrad(wg, [], _t([(0, 16), (0, 64), (0, 8), (0, 8)]), _t([(0, 16), (0, 64), (0, 8), (0, 8)], FAKE + (1 << 20)),
                                 _t([(0, 64), (0, 64), (0, 3), (0, 3)], FAKE + (2 << 20)), stream=0)
     assert e.value.status == -5
+
+
+def test_fused_conv_error_paths_are_checked_on_the_host():
+    cv = tofu.conv2d_desc(2, 4, 64, 8, 8)
+    w, y = _t([(0, 64), (0, 4), (0, 3), (0, 3)], FAKE + (1 << 20)), _t([(0, 2), (0, 64), (0, 8), (0, 8)], FAKE + (2 << 20))
+    top = _t([(0, 2), (0, 4), (0, 4), (0, 8)], FAKE + (3 << 20))
+    bottom = _t([(0, 2), (0, 4), (4, 8), (0, 8)], FAKE + (4 << 20))
+    cases = [([top], -3),                                                       # rows 4..7 held by nobody
+             ([top, bottom, top], -4),                                          # rows 0..3 held twice
+             ([_t([(0, 2), (0, 2), (0, 8), (0, 8)], FAKE + (5 << 20)), _t([(0, 2), (2, 4), (0, 8), (0, 8)], FAKE + (6 << 20))], -6),  # cut along channels
+             ([], -1),
+             ([top] * 17, -1)]
+    for srcs, status in cases:
+        with pytest.raises(tofu.TofuError) as e:
+            tofu.shard_conv2d_fused(cv, [], srcs, w, y, stream=0)
+        assert e.value.status == status, (len(srcs), tofu.last_error())
+    with pytest.raises(tofu.TofuError) as e:      # the H/2 shard needs halo row 4, which the top block lacks
+        tofu.shard_conv2d_fused(cv, [(tofu.CONV_DIM_H, 2, 0)], [top], w, y, stream=0)
+    assert e.value.status == -3
 
 
 def test_reduce_error_paths_are_checked_on_the_host():

@@ -9,6 +9,7 @@ Builds, from the seeded generator, the device buffers of the four large workload
   conv_cout     3x3 conv 2560->2560 @14x14, batch 128: shard 3 of an 8-way C_out split
   fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
   conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
+  conv_cout_h_fused  (extra, built only when named) the same shard reading the two blocks directly
   wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
   reduce_dw     that partial + 7 remote partials -> dW                           (partition-n-reduce)
 
@@ -54,6 +55,10 @@ def _call(fn, *args):
 def _ws(op, splits, dev):
     n = tofu.workspace_bytes(op, splits)
     return torch.empty(n // 4, dtype=torch.float32, device=dev) if n else None
+
+
+STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
+EXTRA_LEGS = ("conv_cout_h_fused",)     # variants outside the step, built only when named
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -105,7 +110,8 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                             dict(kind="reduce", remote=remote, own_index=s, own=part, keep=order) if keep_host else dict(keep=order)))
 
     # ------------------------------------------------------------------ Wide-ResNet conv forward
-    if want("conv_cout", "fetch_halo", "conv_cout_h"):
+    extra = lambda name: which is not None and name in which
+    if want("conv_cout", "fetch_halo", "conv_cout_h") or extra("conv_cout_h_fused"):
         cfg = synth.CONFIGS["wresnet_conv_fwd"]
         NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
         op = tofu.conv2d_desc(NB, C, C, H, W)
@@ -124,7 +130,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         legs.append(Leg("conv_cout", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
                         _call(tofu.shard_conv2d, op, sp_co, tx, tw, ty), y,
                         dict(host_common, box=reg["out_box"], keep=(dx, dw)), conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * H * W))
-    if want("fetch_halo", "conv_cout_h"):
+    if want("fetch_halo", "conv_cout_h") or extra("conv_cout_h_fused"):
         sp = sp_co + [(tofu.CONV_DIM_H, cfg["k_h"], cfg["shard_h"])]
         reg2 = tofu.op_regions(op, sp)
         box = reg2["in_boxes"][0]                                       # rows [0,8) of the input
@@ -148,6 +154,14 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
             legs.append(Leg("conv_cout_h", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
                             _call(tofu.shard_conv2d, op, sp, t_region, tw, ty2), y2,
                             dict(host_common, box=reg2["out_box"], keep=(region, dw, own, halo)),
+                            conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
+        if extra("conv_cout_h_fused"):
+            (h0, h1) = reg2["out_box"][2]
+            y3 = torch.zeros(NB, co1 - co0, h1 - h0, W, dtype=torch.float32, device=dev)
+            taps = _conv_valid_taps(h0, h1, 0, W, H, W)
+            legs.append(Leg("conv_cout_h_fused", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
+                            _call(tofu.shard_conv2d_fused, op, sp, srcs, tw, tofu.tensor(y3, [0, co0, h0, 0])), y3,
+                            dict(host_common, box=reg2["out_box"], keep=(dw, own, halo)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
 
     # ------------------------------------------------------------------ Wide-ResNet conv weight gradient
