@@ -24,6 +24,9 @@ PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 ma
 # calibration copy of that run (2.0 for reads, 1.0 for writes).
 TRAFFIC_KIB = {"conv_cout": (427707.0, 31755.6), "conv_cout_h": (251119.0, 16041.4), "gemm_ksplit": (149614.0, 16384.0)}
 TRAFFIC_SCALE = (2.0, 1.0)
+EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
+               "gemm_dx_nsplit": "backward of gemm_nsplit: partial dX = dY_s . W_s^T (128x16384x4096), W_s read transposed in place",
+               "gemm_dw_nsplit": "backward of gemm_nsplit: dW_s = X^T . dY_s (16384x4096x128), X read transposed in place"}
 METRIC = "shard GEMM/conv TFLOP/s (% fp32 MFMA peak); partition-n-reduce GB/s (% HBM)"
 
 
@@ -198,8 +201,8 @@ def main():
         "legs": leg_out,
     }
     if extra_legs:
-        # outside the step: the <C_out/8, H/2> shard with the fetch fused into the convolution,
-        # timed right after the steps (same buffers, warm clocks)
+        # outside the step: the fused-fetch convolution and the backward GEMMs, timed right after
+        # the steps (warm clocks)
         extras = []
         for leg in extra_legs:
             for _ in range(3):
@@ -213,7 +216,7 @@ def main():
             ms = sorted(e[i].elapsed_time(e[i + 1]) for i in range(10))[5]
             extras.append({"leg": leg.name, "bound": "mfma", "ms": round(ms, 4), "achieved": round(leg.work / ms * 1e-9, 2),
                            "unit": "TFLOP/s", "frac": round(leg.work / ms * 1e-9 / PEAK["mfma"][0], 4),
-                           "note": "replaces fetch_halo + conv_cout_h; median of 10 launches back to back"})
+                           "note": EXTRA_NOTES.get(leg.name, "") + "; median of 10 launches back to back"})
         out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(legs)

@@ -3,8 +3,13 @@
 // worker's index ranges touch).  C[m,n] = sum_{k in shard} A[m,k] * B[k,n] for (m,n) in the
 // shard's output box.
 //
+// The operands are addressed through their element strides, so the backward GEMMs of the same
+// layer (dX = dY * W^T, dW = X^T * dY; forward and backward form one group, Sec. 5.1) are the
+// same call with a transposed view: TA / TB select the staging for an operand whose rows (A) or
+// columns (B) are contiguous along the other index.
+//
 // Kernel: a BM x BN output tile per workgroup, K walked in steps of BK.  Each step stages
-// A[BM x BK] (transposed to k-major) and B[BK x BN] in LDS through registers, double-buffered so
+// A[BM x BK] (as k-major As[k][m]) and B[BK x BN] (as Bs[k][n]) in LDS through registers, double-buffered so
 // that the global loads of step t+1 are in flight while the matrix cores work on step t; one
 // barrier per step.  WM x WN wavefronts each own a (BM/WM) x (BN/WN) block of 32x32 MFMA tiles
 // and read their operands from LDS with conflict-free 32-lane rows.  Tall-skinny shards (the
@@ -29,19 +34,23 @@ struct MatmulArgs {
   int m, n, k;      // shard extents
   int k_slice;      // K elements per slice (multiple of BK); slices = gridDim.y
   int tiles_n;      // number of tiles along n
-  int fast;         // 1: unit column strides, 16-byte aligned rows, 32-bit offsets -> buffer vector loads
+  int fast;         // 1: each operand contiguous along one index, 16-byte aligned, 32-bit offsets -> buffer vector loads
   uint32_t a_bytes, b_bytes;   // bytes spanned by the two input boxes (buffer bounds, fast path)
 };
 
-template <int BM, int BN, int BK, int WM, int WN>
+// TA: A is contiguous along m (a transposed view) instead of along k.
+// TB: B is contiguous along k (a transposed view) instead of along n.
+template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB>
 struct MatmulCfg {
   static constexpr int kThreads = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN;   // wavefront tile
   static constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wavefront
-  // k-major A tile As[k][m]; the pitch makes the transposing writes of a half-wavefront
-  // (BK/4 column groups x 128/BK rows) hit 32 different banks
-  static constexpr int LDA = BM + 32 / BK;
-  static constexpr int LDB = BN + 4;                 // Bs[k][n]
+  // k-major A tile As[k][m].  Vectors along k are transposed on the LDS write: the pitch makes
+  // the writes of a half-wavefront (BK/4 column groups x 128/BK rows) hit 32 different banks.
+  // Vectors along m are written whole and need a pitch of whole vectors.
+  static constexpr int LDA = TA ? BM + 4 : BM + 32 / BK;
+  // Bs[k][n]: whole vectors along n, or (TB) transposing writes with an odd pitch
+  static constexpr int LDB = TB ? BN + 1 : BN + 4;
   static constexpr int kLdsFloats = 2 * BK * (LDA + LDB);
   static constexpr int AV = BM * BK / 4 / kThreads;  // 16-byte vectors of A per thread per step
   static constexpr int BV = BK * BN / 4 / kThreads;
@@ -50,9 +59,9 @@ struct MatmulCfg {
   static_assert(BK % 4 == 0, "BK must hold whole vectors");
 };
 
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB>
 __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p) {
-  using Cfg = MatmulCfg<BM, BN, BK, WM, WN>;
+  using Cfg = MatmulCfg<BM, BN, BK, WM, WN, TA, TB>;
   constexpr int NT = Cfg::kThreads, LDA = Cfg::LDA, LDB = Cfg::LDB, FM = Cfg::FM, FN = Cfg::FN;
   __shared__ float lds[Cfg::kLdsFloats];
   float* As = lds;                      // [2][BK][LDA]
@@ -66,19 +75,31 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
   const int k_begin = blockIdx.y * p.k_slice;
   const int k_end = min(p.k, k_begin + p.k_slice);
   const int steps = (k_end - k_begin + BK - 1) / BK;
-  // Fast path: per-lane byte offsets are fixed; a K step only moves a scalar offset.  Rows past
-  // m read as zero (offset out of range); columns past n may read the next row's values, which
-  // only reach accumulator columns that are never stored.
+  // Fast path: per-lane byte offsets are fixed; a K step only moves a scalar offset.  Vectors
+  // that start past m or n read as zero (offset out of range); a vector that straddles the edge
+  // may read a neighbouring row's values, which only reach accumulators that are never stored.
   uint32_t a_voff[Cfg::AV], b_voff[Cfg::BV];
 #pragma unroll
   for (int i = 0; i < Cfg::AV; ++i) {
-    const int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
-    a_voff[i] = m0 + row < p.m ? 4u * (uint32_t)((int64_t)(m0 + row) * p.a_rs + 4 * q) : kNoOffset;
+    const int idx = tid + i * NT;
+    if (TA) {   // vector = rows m..m+3 of one k
+      const int kk = idx / (BM / 4), mq = idx % (BM / 4);
+      a_voff[i] = m0 + 4 * mq < p.m ? 4u * (uint32_t)((int64_t)kk * p.a_cs + m0 + 4 * mq) : kNoOffset;
+    } else {    // vector = columns k..k+3 of one row
+      const int row = idx / (BK / 4), q = idx % (BK / 4);
+      a_voff[i] = m0 + row < p.m ? 4u * (uint32_t)((int64_t)(m0 + row) * p.a_rs + 4 * q) : kNoOffset;
+    }
   }
 #pragma unroll
   for (int i = 0; i < Cfg::BV; ++i) {
-    const int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
-    b_voff[i] = n0 + 4 * c < p.n ? 4u * (uint32_t)((int64_t)row * p.b_rs + n0 + 4 * c) : kNoOffset;
+    const int idx = tid + i * NT;
+    if (TB) {   // vector = rows k..k+3 of one column
+      const int col = idx / (BK / 4), q = idx % (BK / 4);
+      b_voff[i] = n0 + col < p.n ? 4u * (uint32_t)((int64_t)(n0 + col) * p.b_cs + 4 * q) : kNoOffset;
+    } else {    // vector = columns n..n+3 of one row
+      const int row = idx / (BN / 4), c = idx % (BN / 4);
+      b_voff[i] = n0 + 4 * c < p.n ? 4u * (uint32_t)((int64_t)row * p.b_rs + n0 + 4 * c) : kNoOffset;
+    }
   }
   const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A, p.a_bytes);
   const __amdgpu_buffer_rsrc_t b_rsrc = make_rsrc(p.B, p.b_bytes);
@@ -89,46 +110,59 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     const int k0 = k_begin + step * BK;
     const bool full_k = k0 + BK <= k_end;
     if (p.fast && full_k) {
-      const uint32_t a_soff = 4u * (uint32_t)k0, b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
+      const uint32_t a_soff = 4u * (uint32_t)((int64_t)k0 * p.a_cs), b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
 #pragma unroll
       for (int i = 0; i < Cfg::AV; ++i) ra[i] = buf_load4(a_rsrc, a_voff[i], a_soff);
 #pragma unroll
       for (int i = 0; i < Cfg::BV; ++i) rb[i] = buf_load4(b_rsrc, b_voff[i], b_soff);
-    } else {
+    } else {    // guarded element loads into the same register layout
 #pragma unroll
       for (int i = 0; i < Cfg::AV; ++i) {
-        int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+        const int idx = tid + i * NT;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          int mm = m0 + row, kk = k0 + 4 * q + j;
+          const int mm = m0 + (TA ? 4 * (idx % (BM / 4)) + j : idx / (BK / 4));
+          const int kk = k0 + (TA ? idx / (BM / 4) : 4 * (idx % (BK / 4)) + j);
           ra[i][j] = (mm < p.m && kk < k_end) ? p.A[(int64_t)mm * p.a_rs + (int64_t)kk * p.a_cs] : 0.f;
         }
       }
 #pragma unroll
       for (int i = 0; i < Cfg::BV; ++i) {
-        int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
+        const int idx = tid + i * NT;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          int kk = k0 + row, nn = n0 + 4 * c + j;
+          const int kk = k0 + (TB ? 4 * (idx % (BK / 4)) + j : idx / (BN / 4));
+          const int nn = n0 + (TB ? idx / (BK / 4) : 4 * (idx % (BN / 4)) + j);
           rb[i][j] = (kk < k_end && nn < p.n) ? p.B[(int64_t)kk * p.b_rs + (int64_t)nn * p.b_cs] : 0.f;
         }
       }
     }
   };
-  auto store_lds = [&](int buf) {
-    float* as = As + buf * BK * LDA;
-    float* bs = Bs + buf * BK * LDB;
-#pragma unroll
-    for (int i = 0; i < Cfg::AV; ++i) {
-      int idx = tid + i * NT, row = idx / (BK / 4), q = idx % (BK / 4);
+  auto store_a = [&](float* as, int i) {
+    const int idx = tid + i * NT;
+    if (TA) {
+      *reinterpret_cast<v4f32*>(as + (idx / (BM / 4)) * LDA + 4 * (idx % (BM / 4))) = ra[i];
+    } else {
+      const int row = idx / (BK / 4), q = idx % (BK / 4);
 #pragma unroll
       for (int j = 0; j < 4; ++j) as[(4 * q + j) * LDA + row] = ra[i][j];
     }
+  };
+  auto store_b = [&](float* bs, int i) {
+    const int idx = tid + i * NT;
+    if (TB) {
+      const int col = idx / (BK / 4), q = idx % (BK / 4);
 #pragma unroll
-    for (int i = 0; i < Cfg::BV; ++i) {
-      int idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
-      *reinterpret_cast<v4f32*>(bs + row * LDB + 4 * c) = rb[i];
+      for (int j = 0; j < 4; ++j) bs[(4 * q + j) * LDB + col] = rb[i][j];
+    } else {
+      *reinterpret_cast<v4f32*>(bs + (idx / (BN / 4)) * LDB + 4 * (idx % (BN / 4))) = rb[i];
     }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < Cfg::AV; ++i) store_a(As + buf * BK * LDA, i);
+#pragma unroll
+    for (int i = 0; i < Cfg::BV; ++i) store_b(Bs + buf * BK * LDB, i);
   };
 
   acc16 acc[FM][FN];
@@ -164,7 +198,7 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     float* as_next = As + (buf ^ 1) * BK * LDA;
     float* bs_next = Bs + (buf ^ 1) * BK * LDB;
     const int nxt = min(t + 2, steps - 1), k0 = k_begin + nxt * BK;
-    const uint32_t a_soff = 4u * (uint32_t)k0, b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
+    const uint32_t a_soff = 4u * (uint32_t)((int64_t)k0 * p.a_cs), b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
@@ -181,13 +215,11 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
         if (s >= 1 && (s - 1) % STRIDE == 0 && (s - 1) / STRIDE < NI) {
           const int item = (s - 1) / STRIDE;
           if (item < Cfg::AV) {
-            const int idx = tid + item * NT, row = idx / (BK / 4), q = idx % (BK / 4);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) as_next[(4 * q + j) * LDA + row] = ra[item][j];
+            store_a(as_next, item);
             ra[item] = buf_load4(a_rsrc, a_voff[item], a_soff);
           } else {
-            const int i = item - Cfg::AV, idx = tid + i * NT, row = idx / (BN / 4), c = idx % (BN / 4);
-            *reinterpret_cast<v4f32*>(bs_next + row * LDB + 4 * c) = rb[i];
+            const int i = item - Cfg::AV;
+            store_b(bs_next, i);
             rb[i] = buf_load4(b_rsrc, b_voff[i], b_soff);
           }
         }
@@ -286,7 +318,11 @@ extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* s
   p.tiles_n = (int)((n + kBN - 1) / kBN);
   const int tiles_m = (int)((m + kBM - 1) / kBM);
   const int64_t a_span = 1 + (m - 1) * as[0] + (k - 1) * as[1], b_span = 1 + (k - 1) * bs[0] + (n - 1) * bs[1];
-  p.fast = as[1] == 1 && bs[1] == 1 && as[0] >= 0 && bs[0] >= 0 && as[0] % 4 == 0 && bs[0] % 4 == 0 &&
+  // Vector staging needs each operand contiguous along one index with the other stride a whole
+  // number of vectors: A along k (plain) or along m (ta), B along n (plain) or along k (tb).
+  const bool ta = as[1] != 1 && as[0] == 1, tb = bs[1] != 1 && bs[0] == 1;
+  const int64_t a_ld = ta ? as[1] : as[0], b_ld = tb ? bs[1] : bs[0];
+  p.fast = (ta || as[1] == 1) && (tb || bs[1] == 1) && a_ld >= 0 && b_ld >= 0 && a_ld % 4 == 0 && b_ld % 4 == 0 &&
            (reinterpret_cast<uintptr_t>(p.A) & 15) == 0 && (reinterpret_cast<uintptr_t>(p.B) & 15) == 0 &&
            a_span < ((int64_t)1 << 29) && b_span < ((int64_t)1 << 29);
   p.a_bytes = p.fast ? (uint32_t)(4 * a_span) : 0;
@@ -308,7 +344,11 @@ extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* s
   }
   const int slices = (int)((k + p.k_slice - 1) / p.k_slice);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL((matmul_kernel<kBM, kBN, kBK, kWM, kWN>), dim3(tiles_m * p.tiles_n, slices > 0 ? slices : 1), dim3(64 * kWM * kWN), 0, s, p);
+  void (*kern)(const MatmulArgs) = matmul_kernel<kBM, kBN, kBK, kWM, kWN, false, false>;   // also the guarded path for any strides
+  if (p.fast && ta && tb) kern = matmul_kernel<kBM, kBN, kBK, kWM, kWN, true, true>;
+  else if (p.fast && ta) kern = matmul_kernel<kBM, kBN, kBK, kWM, kWN, true, false>;
+  else if (p.fast && tb) kern = matmul_kernel<kBM, kBN, kBK, kWM, kWN, false, true>;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * p.tiles_n, slices > 0 ? slices : 1), dim3(64 * kWM * kWN), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "matmul launch failed: %s", hipGetErrorString(e));
   if (split > 1) {

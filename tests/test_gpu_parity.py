@@ -251,6 +251,57 @@ def test_matmul_strided_views():
     assert (wide[:, :100] == 0).all() and (wide[:, 300:] == 0).all()
 
 
+@pytest.mark.parametrize("Bt,K,N", [(40, 136, 200), (128, 96, 260), (33, 70, 50)])
+def test_matmul_backward_gemms_through_transposed_views(Bt, K, N):
+    """The backward GEMMs of Y = X W are the same entry point on transposed views:
+    dX = dY W^T (B operand contiguous along k) and dW = X^T dY (A operand contiguous along m),
+    each under every split dimension; small integers, so sums are exact and equality is bit-exact.
+    Strides that are whole vectors take the vector staging, (33, 70, 50) the guarded one."""
+    X = synth.small_int(35, 0, (Bt, K), -3, 3)
+    W = synth.small_int(35, 1, (K, N), -3, 3)
+    dY = synth.small_int(35, 2, (Bt, N), -3, 3)
+    dX_, dW_, ddY = dev(X), dev(W), dev(dY)
+    # dX[Bt,K] = dY[Bt,N] . W^T[N,K]
+    want = oracle.matmul_box(dY, np.ascontiguousarray(W.T))[0]
+    op_d = dict(kind="matmul", M=Bt, N=K, K=N)
+    op = tofu.matmul_desc(Bt, K, N)
+
+    def run_dx(sp):
+        C = torch.full((Bt, K), float("nan"), dtype=torch.float32, device=DEV)
+        spl = [(MM_DIMS[d], k, s) for d, k, s in sp]
+        tofu.shard_matmul(op, spl, tofu.tensor(ddY), tofu.tensor(dW_.t()), tofu.tensor(C), workspace(op, spl))
+        return C
+    for dim, k in itertools.product(["M", "N", "K"], [2, 3]):
+        got = assemble(op_d, dim, k, run_dx)
+        assert np.array_equal(got.astype(np.float64), want), ("dX", dim, k)
+    # dW[K,N] = X^T[K,Bt] . dY[Bt,N]
+    want = oracle.matmul_box(np.ascontiguousarray(X.T), dY)[0]
+    op_d = dict(kind="matmul", M=K, N=N, K=Bt)
+    op2 = tofu.matmul_desc(K, N, Bt)
+
+    def run_dw(sp):
+        C = torch.full((K, N), float("nan"), dtype=torch.float32, device=DEV)
+        spl = [(MM_DIMS[d], k, s) for d, k, s in sp]
+        tofu.shard_matmul(op2, spl, tofu.tensor(dX_.t()), tofu.tensor(ddY), tofu.tensor(C), workspace(op2, spl))
+        return C
+    for dim, k in itertools.product(["M", "N", "K"], [2, 3]):
+        got = assemble(op_d, dim, k, run_dw)
+        assert np.array_equal(got.astype(np.float64), want), ("dW", dim, k)
+
+
+def test_matmul_transposed_views_long_k():
+    """Both operands transposed, K long enough for the kernel's own K slices, fp32 data."""
+    A = synth.uniform(36, 0, (128, 2080), -1, 1)
+    B = synth.uniform(36, 1, (2080, 192), -1, 1)
+    val, absum = oracle.matmul_box(A, B)
+    dAt, dBt = dev(A.T.copy()), dev(B.T.copy())
+    op = tofu.matmul_desc(128, 192, 2080)
+    for a_view, b_view, what in [(dAt.t(), dBt.t(), "TT"), (dAt.t(), dev(B), "TN"), (dev(A), dBt.t(), "NT")]:
+        C = torch.empty(128, 192, dtype=torch.float32, device=DEV)
+        tofu.shard_matmul(op, [], tofu.tensor(a_view), tofu.tensor(b_view), tofu.tensor(C), workspace(op, []))
+        assert_close(C.cpu().numpy(), val, absum, what)
+
+
 # ----------------------------------------------------------------------------- conv2d
 def run_conv(opd, splits, dx, dw, x_lo=None):
     op = tofu.conv2d_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["H"], opd["W"], pad=opd["pad"])

@@ -43,7 +43,7 @@ def _check_reduce(leg):
     assert np.array_equal(out[idx], ref)
 
 
-@pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_ksplit", "reduce_gates"),
+@pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_dx_nsplit", "gemm_dw_nsplit"), ("gemm_ksplit", "reduce_gates"),
                                    ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw")])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)

@@ -10,6 +10,8 @@ Builds, from the seeded generator, the device buffers of the four large workload
   fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
   conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
   conv_cout_h_fused  (extra, built only when named) the same shard reading the two blocks directly
+  gemm_dx_nsplit     (extra) backward of the N-split gate GEMM: partial dX = dY_s . W_s^T, W_s read transposed in place
+  gemm_dw_nsplit     (extra) backward of the N-split gate GEMM: dW_s = X^T . dY_s, X read transposed in place
   wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
   reduce_dw     that partial + 7 remote partials -> dW                           (partition-n-reduce)
 
@@ -58,7 +60,8 @@ def _ws(op, splits, dev):
 
 
 STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
-EXTRA_LEGS = ("conv_cout_h_fused",)     # variants outside the step, built only when named
+# variants and backward operators outside the step, built only when named
+EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit")
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -85,6 +88,35 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         legs.append(Leg("gemm_nsplit", "mfma", 2.0 * M * (n1 - n0) * K,
                         _call(tofu.shard_matmul, op, splits, tA, tB, tC, ws), C,
                         dict(kind="matmul", A=X, B=Ws, box=reg["out_box"], krange=(0, K), b_col0=n0, keep=(dX, dW, ws)) if keep_host else dict(keep=(dX, dW, ws))))
+    if which is not None and ("gemm_dx_nsplit" in which or "gemm_dw_nsplit" in which):
+        # Backward GEMMs of the N-split worker (forward and backward operators form one group and
+        # keep the weights' partition): the worker holds X, its block W_s and its block dY_s.
+        M, N, K, k = 128, 32768, 16384, 8
+        cfg = synth.CONFIGS["lstm_gates_nsplit"]
+        s = cfg["shard"]
+        n0, n1 = tofu.shard_range(N, k, s)
+        X = synth.draw(cfg["a"], cfg["seed"], 0, (M, K))
+        Ws = synth.draw(cfg["b"], cfg["seed"], 1, (K, n1 - n0))
+        dYs = synth.normal(cfg["seed"], 2, (M, n1 - n0), 1.0)
+        dX, dW, ddY = up(X), up(Ws), up(dYs)
+        if "gemm_dx_nsplit" in which:      # dX[M,K] = dY[M,N] . W^T[N,K]; the N split is a reduction split here
+            opx = tofu.matmul_desc(M, K, N)
+            spx = [(tofu.MM_DIM_K, k, s)]
+            part = torch.zeros(M, K, dtype=torch.float32, device=dev)
+            wsx = _ws(opx, spx, dev)
+            legs.append(Leg("gemm_dx_nsplit", "mfma", 2.0 * M * K * (n1 - n0),
+                            _call(tofu.shard_matmul, opx, spx, tofu.tensor(ddY, [0, n0]), tofu.tensor(dW.t(), [n0, 0]), tofu.tensor(part), wsx), part,
+                            dict(kind="matmul", A=dYs, B=np.ascontiguousarray(Ws.T), box=[(0, M), (0, K)], krange=(0, n1 - n0), b_col0=0,
+                                 keep=(ddY, dW, wsx)) if keep_host else dict(keep=(ddY, dW, wsx))))
+        if "gemm_dw_nsplit" in which:      # dW[K,N] = X^T[K,M] . dY[M,N]; the N split stays an output split
+            opw = tofu.matmul_desc(K, N, M)
+            spw = [(tofu.MM_DIM_N, k, s)]
+            gW = torch.zeros(K, n1 - n0, dtype=torch.float32, device=dev)
+            wsw_ = _ws(opw, spw, dev)
+            legs.append(Leg("gemm_dw_nsplit", "mfma", 2.0 * K * (n1 - n0) * M,
+                            _call(tofu.shard_matmul, opw, spw, tofu.tensor(dX.t()), tofu.tensor(ddY, [0, n0]), tofu.tensor(gW, [0, n0]), wsw_), gW,
+                            dict(kind="matmul", A=np.ascontiguousarray(X.T), B=dYs, box=[(0, K), (0, n1 - n0)], krange=(0, M), b_col0=0,
+                                 keep=(dX, ddY, wsw_)) if keep_host else dict(keep=(dX, ddY, wsw_))))
     if want("gemm_ksplit", "reduce_gates"):
         cfg = synth.CONFIGS["lstm_gates_ksplit"]
         s = cfg["shard"]
