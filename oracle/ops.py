@@ -147,6 +147,38 @@ def wgrad_pts(x, dy, KH, KW, pts, stride=1, pad=0, nrange=None):
     return v, s
 
 
+def _dgrad_dims(dy, w, H, W, stride, pad):
+    c_out, c_in, KH, KW = w.shape
+    batch = dy.shape[0]
+    ho = (H + 2 * pad - KH) // stride + 1
+    wo = (W + 2 * pad - KW) // stride + 1
+    assert dy.shape == (batch, c_out, ho, wo), "dy must have the forward output's shape"
+    return [_i64(v) for v in (batch, c_in, c_out, H, W, KH, KW, stride, pad)], (batch, c_in, c_out)
+
+
+def dgrad_box(dy, w, H, W, stride=1, pad=0, box=None, corange=None):
+    """dx over box [(n),(ci),(h),(w)] of the H x W input (default all), summing co over corange (default all)."""
+    dy, pd = _f32(dy); w, pw = _f32(w)
+    args, (batch, c_in, c_out) = _dgrad_dims(dy, w, H, W, stride, pad)
+    box = box or ((0, batch), (0, c_in), (0, H), (0, W))
+    shape = [b[1] - b[0] for b in box]
+    c0, c1 = corange or (0, c_out)
+    lo, hi = _box(box)
+    v, s, pv, ps = _out(int(np.prod(shape)))
+    _load().oracle_dgrad_box(pd, pw, *args, lo, hi, _i64(c0), _i64(c1), pv, ps)
+    return v.reshape(shape), s.reshape(shape)
+
+
+def dgrad_pts(dy, w, H, W, pts, stride=1, pad=0, corange=None):
+    dy, pd = _f32(dy); w, pw = _f32(w)
+    args, (_, _, c_out) = _dgrad_dims(dy, w, H, W, stride, pad)
+    c0, c1 = corange or (0, c_out)
+    p, pp = _pts(pts, 4)
+    v, s, pv, ps = _out(len(p))
+    _load().oracle_dgrad_pts(pd, pw, *args, _i64(len(p)), pp, _i64(c0), _i64(c1), pv, ps)
+    return v, s
+
+
 def reduce(partials):
     """Element-wise sum of a list of equally shaped float32 arrays -> (value, abs_sum)."""
     arrs = [np.ascontiguousarray(p, dtype=np.float32) for p in partials]

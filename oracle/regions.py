@@ -30,6 +30,7 @@ ITER_DIMS = {
     "matmul": (("M", "N"), ("K",)),
     "conv2d": (("N", "CO", "H", "W"), ("CI",)),
     "conv2d_wgrad": (("CO", "CI"), ("N",)),
+    "conv2d_dgrad": (("N", "CI", "H", "W"), ("CO",)),     # H, W: rows / columns of the forward INPUT
 }
 
 
@@ -54,6 +55,8 @@ def iteration_extents(op: dict) -> dict:
         return {"N": op["batch"], "CO": op["c_out"], "H": ho, "W": wo, "CI": op["c_in"]}
     if kind == "conv2d_wgrad":
         return {"CO": op["c_out"], "CI": op["c_in"], "N": op["batch"]}
+    if kind == "conv2d_dgrad":
+        return {"N": op["batch"], "CI": op["c_in"], "H": op["H"], "W": op["W"], "CO": op["c_out"]}
     raise ValueError(kind)
 
 
@@ -77,6 +80,16 @@ def _window(out_lo, out_hi, ksize, stride, pad, size):
     need_lo = out_lo * stride - pad
     need_hi = (out_hi - 1) * stride + (ksize - 1) - pad + 1
     lo, hi = max(need_lo, 0), min(need_hi, size)
+    return (lo, hi), lo - need_lo, need_hi - hi
+
+
+def _window_back(in_lo, in_hi, ksize, stride, pad, out_size):
+    """Output coordinates o whose window o*stride + d - pad, d in [0,ksize), reaches an input
+    coordinate in [in_lo,in_hi): the range of dy a data-gradient shard reads.  Same return
+    convention as _window; the cut-off counts are the window positions that fall outside dy."""
+    need_lo = -((-(in_lo + pad - (ksize - 1))) // stride)          # ceil
+    need_hi = (in_hi - 1 + pad) // stride + 1
+    lo, hi = max(need_lo, 0), min(need_hi, out_size)
     return (lo, hi), lo - need_lo, need_hi - hi
 
 
@@ -104,6 +117,14 @@ def op_regions(op: dict, splits):
         out_box = [r["CO"], r["CI"], (0, op["KH"]), (0, op["KW"])]
         in_boxes = [[r["N"], r["CI"], hbox, wbox],
                     [r["N"], r["CO"], (0, ho), (0, wo)]]
+    elif kind == "conv2d_dgrad":
+        ho = conv_out_size(op["H"], op["KH"], op["stride"], op["pad"])
+        wo = conv_out_size(op["W"], op["KW"], op["stride"], op["pad"])
+        hbox, pad_lo[0], pad_hi[0] = _window_back(*r["H"], op["KH"], op["stride"], op["pad"], ho)
+        wbox, pad_lo[1], pad_hi[1] = _window_back(*r["W"], op["KW"], op["stride"], op["pad"], wo)
+        out_box = [r["N"], r["CI"], r["H"], r["W"]]
+        in_boxes = [[r["N"], r["CO"], hbox, wbox],
+                    [r["CO"], r["CI"], (0, op["KH"]), (0, op["KW"])]]
     else:
         raise ValueError(kind)
     return dict(out_box=out_box, in_boxes=in_boxes, pad_lo=pad_lo, pad_hi=pad_hi,

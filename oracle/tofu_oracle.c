@@ -164,6 +164,58 @@ void oracle_wgrad_pts(const float* x, const float* dy, i64 batch, i64 c_in, i64 
     wgrad_elem(x, dy, &c, pts[4 * i], pts[4 * i + 1], pts[4 * i + 2], pts[4 * i + 3], n0, n1, &val[i], &absum[i]);
 }
 
+/* ---- data gradient of that convolution ---------------------------------------
+ * dx[n,ci,ih,iw] = sum_{co} sum_{(h,kh): h*s+kh-p = ih} sum_{(w,kw): w*s+kw-p = iw} dy[n,co,h,w] * wt[co,ci,kh,kw],
+ * the derivative of sum(dy*y) with respect to x[n,ci,ih,iw]: every output position whose
+ * window covers (ih,iw) contributes through the tap that points at it.  Forward and backward
+ * operators of a layer are partitioned as one group (Sec. 5.1); the output channel co is the
+ * reduction index here, so a co split is Case-2 (Sec. 4.2) and [co0,co1) restricts the sum. */
+static void dgrad_elem(const float* dy, const float* wt, const conv_t* c, i64 n, i64 ci, i64 ih, i64 iw, i64 co0,
+                       i64 co1, double* val, double* absum) {
+  double acc = 0.0, as = 0.0;
+  for (i64 co = co0; co < co1; ++co)
+    for (i64 kh = 0; kh < c->KH; ++kh)
+      for (i64 kw = 0; kw < c->KW; ++kw) {
+        i64 hs = ih + c->pad - kh, ws = iw + c->pad - kw;   /* h*s and w*s of the output position, if any */
+        if (hs < 0 || ws < 0 || hs % c->stride || ws % c->stride) continue;
+        i64 h = hs / c->stride, w = ws / c->stride;
+        if (h >= c->HO || w >= c->WO) continue;
+        double p = (double)dy[((n * c->c_out + co) * c->HO + h) * c->WO + w] *
+                   (double)wt[((co * c->c_in + ci) * c->KH + kh) * c->KW + kw];
+        acc += p;
+        as += fabs(p);
+      }
+  *val = acc;
+  *absum = as;
+}
+
+/* Dense box lo[4]..hi[4] over (n,ci,ih,iw) of dx. */
+void oracle_dgrad_box(const float* dy, const float* wt, i64 batch, i64 c_in, i64 c_out, i64 H, i64 W, i64 KH,
+                      i64 KW, i64 stride, i64 pad, const i64* lo, const i64* hi, i64 co0, i64 co1, double* val,
+                      double* absum) {
+  conv_t c = conv_make(batch, c_in, c_out, H, W, KH, KW, stride, pad);
+  i64 d0 = hi[0] - lo[0], d1 = hi[1] - lo[1], d2 = hi[2] - lo[2], d3 = hi[3] - lo[3];
+#pragma omp parallel for schedule(static)
+  for (i64 e = 0; e < d0 * d1 * d2 * d3; ++e) {
+    i64 r = e;
+    i64 iw = lo[3] + r % d3; r /= d3;
+    i64 ih = lo[2] + r % d2; r /= d2;
+    i64 ci = lo[1] + r % d1; r /= d1;
+    i64 n = lo[0] + r;
+    dgrad_elem(dy, wt, &c, n, ci, ih, iw, co0, co1, &val[e], &absum[e]);
+  }
+}
+
+/* Listed output coordinates: pts[i] = (n, ci, ih, iw). */
+void oracle_dgrad_pts(const float* dy, const float* wt, i64 batch, i64 c_in, i64 c_out, i64 H, i64 W, i64 KH,
+                      i64 KW, i64 stride, i64 pad, i64 npts, const i64* pts, i64 co0, i64 co1, double* val,
+                      double* absum) {
+  conv_t c = conv_make(batch, c_in, c_out, H, W, KH, KW, stride, pad);
+#pragma omp parallel for schedule(static)
+  for (i64 i = 0; i < npts; ++i)
+    dgrad_elem(dy, wt, &c, pts[4 * i], pts[4 * i + 1], pts[4 * i + 2], pts[4 * i + 3], co0, co1, &val[i], &absum[i]);
+}
+
 /* ---- output reduction of partition-n-reduce (Sec. 3.1 way 2) ----------------
  * val[i] = sum_j partials[j][i] in fp64, absum[i] = sum_j |partials[j][i]|. */
 void oracle_reduce(const float* const* partials, i64 k, i64 count, double* val, double* absum) {

@@ -292,6 +292,99 @@ def test_wgrad_adjoint_identity_and_closed_form():
     assert np.array_equal(dw, 2.0 * np.array([[12, 15, 12], [16, 20, 16], [12, 15, 12]]))
 
 
+# ------------------------------------------------------------------ dgrad
+@pytest.mark.parametrize("stride,pad,kh,kw", [(1, 1, 3, 3), (1, 0, 3, 3), (2, 1, 3, 3), (1, 1, 2, 3), (2, 0, 3, 3)])
+def test_dgrad_against_torch_autograd_fp64(stride, pad, kh, kw):
+    x = torch.zeros(3, 2, 7, 6, dtype=torch.float64, requires_grad=True)
+    w = synth.normal(12, 0, (4, 2, kh, kw), 1.0)
+    y = F.conv2d(x, torch.from_numpy(w).double(), stride=stride, padding=pad)
+    dy = synth.normal(12, 1, tuple(y.shape), 1.0)
+    (y * torch.from_numpy(dy).double()).sum().backward()
+    v, s = oracle.dgrad_box(dy, w, 7, 6, stride=stride, pad=pad)
+    assert np.allclose(v, x.grad.numpy(), rtol=0, atol=1e-12)
+    assert (s >= np.abs(v) - 1e-12).all()
+    pts = synth.coords(12, 2, 10, v.shape)
+    assert np.array_equal(oracle.dgrad_pts(dy, w, 7, 6, pts, stride=stride, pad=pad)[0], v[tuple(pts.T)])
+    # a restricted output-channel range is that channel block's contribution
+    a = oracle.dgrad_box(dy, w, 7, 6, stride=stride, pad=pad, corange=(0, 1))[0]
+    b = oracle.dgrad_box(dy, w, 7, 6, stride=stride, pad=pad, corange=(1, 4))[0]
+    assert np.allclose(a + b, v, rtol=0, atol=1e-12)
+
+
+def test_dgrad_adjoint_identity_and_closed_forms():
+    """<dgrad(dy,w), x> == <dy, conv(x,w)> ties the gradient to the forward definition."""
+    x = synth.normal(13, 0, (2, 3, 6, 5), 1.0)
+    w = synth.normal(13, 1, (4, 3, 3, 3), 1.0)
+    dy = synth.normal(13, 2, (2, 4, 6, 5), 1.0)
+    lhs = (oracle.dgrad_box(dy, w, 6, 5, pad=1)[0] * x.astype(np.float64)).sum()
+    rhs = (dy.astype(np.float64) * oracle.conv2d_box(x, w, pad=1)[0]).sum()
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+    # all ones, 4x5 image, 3 output channels: every pixel gets one term per tap whose output position exists
+    v = oracle.dgrad_box(np.ones((1, 3, 4, 5), np.float32), np.ones((3, 2, 3, 3), np.float32), 4, 5, pad=1)[0]
+    want = 3.0 * np.array([[4, 6, 6, 6, 4], [6, 9, 9, 9, 6], [6, 9, 9, 9, 6], [4, 6, 6, 6, 4]])
+    assert np.array_equal(v[0, 0], want) and np.array_equal(v[0, 1], want)
+    # centre-tap delta filters: dx[ci] = sum_co dy[co] * w[co,ci,1,1]
+    wd = np.zeros((2, 2, 3, 3), np.float32)
+    wd[0, 1, 1, 1], wd[1, 0, 1, 1] = 2.0, -3.0
+    d = synth.small_int(13, 3, (1, 2, 4, 4), -3, 3)
+    v = oracle.dgrad_box(d, wd, 4, 4, pad=1)[0]
+    assert np.array_equal(v[0, 1], 2.0 * d[0, 0]) and np.array_equal(v[0, 0], -3.0 * d[0, 1])
+    # orientation: the forward tap (kh,kw) = (0,2) reads x[h-1, w+1], so dy[h,w] lands on dx[h-1, w+1]
+    wo = np.zeros((1, 1, 3, 3), np.float32)
+    wo[0, 0, 0, 2] = 1.0
+    d = np.zeros((1, 1, 4, 4), np.float32)
+    d[0, 0, 2, 1] = 5.0
+    v = oracle.dgrad_box(d, wo, 4, 4, pad=1)[0]
+    want = np.zeros((4, 4))
+    want[1, 2] = 5.0
+    assert np.array_equal(v[0, 0], want)
+    # 1x1 image, pad 1: only the centre tap survives and the operator is dy . W[:, :, 1, 1]
+    d1 = synth.normal(13, 4, (6, 7, 1, 1), 1.0)
+    w1 = synth.normal(13, 5, (7, 5, 3, 3), 1.0)
+    mm = oracle.matmul_box(d1[:, :, 0, 0], np.ascontiguousarray(w1[:, :, 1, 1]))[0]
+    assert np.array_equal(oracle.dgrad_box(d1, w1, 1, 1, pad=1)[0][:, :, 0, 0], mm)
+
+
+def _touch_dgrad(op, ranges):
+    """Mark every dy / w element the defining loop nest reads for the dx box of `ranges`."""
+    s, p = op["stride"], op["pad"]
+    ho, wo_ = R.conv_out_size(op["H"], op["KH"], s, p), R.conv_out_size(op["W"], op["KW"], s, p)
+    dy = np.zeros((op["batch"], op["c_out"], ho, wo_), dtype=bool)
+    w = np.zeros((op["c_out"], op["c_in"], op["KH"], op["KW"]), dtype=bool)
+    for n in range(*ranges["N"]):
+        for ci in range(*ranges["CI"]):
+            for ih in range(*ranges["H"]):
+                for iw in range(*ranges["W"]):
+                    for co in range(*ranges["CO"]):
+                        for h in range(ho):              # every forward output position whose window covers (ih, iw)
+                            for ww in range(wo_):
+                                kh, kw = ih - h * s + p, iw - ww * s + p
+                                if 0 <= kh < op["KH"] and 0 <= kw < op["KW"]:
+                                    dy[n, co, h, ww] = True
+                                    w[co, ci, kh, kw] = True
+    return dy, w
+
+
+@pytest.mark.parametrize("stride,pad,ksz", [(1, 1, 3), (1, 0, 3), (1, 2, 5)])
+def test_dgrad_regions_match_touched_coordinates(stride, pad, ksz):
+    op = dict(kind="conv2d_dgrad", batch=2, c_in=3, c_out=4, H=9, W=7, KH=ksz, KW=ksz, stride=stride, pad=pad)
+    for dim in ["N", "CI", "H", "W", "CO"]:
+        ext = R.iteration_extents(op)[dim]
+        for k in range(1, min(ext, 3) + 1):
+            for s in range(k):
+                reg = R.op_regions(op, [(dim, k, s)])
+                dm, wm = _touch_dgrad(op, reg["ranges"])
+                assert _bbox(dm) == [tuple(b) for b in reg["in_boxes"][0]], (dim, k, s)
+                assert reg["is_partial"] == (dim == "CO" and k > 1)
+                if dim not in ("H", "W"):   # spatial shards may not use every tap against a clipped border
+                    assert _bbox(wm) == [tuple(b) for b in reg["in_boxes"][1]]
+                # residual padding: window positions of the needed dy rows that fall outside dy
+                (hlo, hhi) = reg["ranges"]["H"]
+                ho = R.conv_out_size(op["H"], ksz, stride, pad)
+                assert reg["pad_lo"][0] == max(0, (ksz - 1 - pad) - hlo)
+                assert reg["pad_hi"][0] == max(0, hhi - 1 + pad - (ho - 1))
+
+
 # ------------------------------------------------------------------ reduce
 def test_reduce_pins():
     parts = [synth.normal(9, j, (5, 33), 3.0) for j in range(8)]
@@ -339,6 +432,12 @@ def test_pnr_invariant_on_the_oracle(k):
     for dim in ["CO", "CI", "N"]:
         got = _assemble(op, dim, k, lambda reg: oracle.wgrad_box(x, dy, 3, 3, pad=1, box=reg["out_box"],
                                                                  nrange=reg["ranges"]["N"])[0])
+        assert np.array_equal(got, full), dim
+    op["kind"] = "conv2d_dgrad"
+    full = oracle.dgrad_box(dy, w, 9, 8, pad=1)[0]
+    for dim in ["N", "CI", "H", "W", "CO"]:
+        got = _assemble(op, dim, k, lambda reg: oracle.dgrad_box(dy, w, 9, 8, pad=1, box=reg["out_box"],
+                                                                 corange=reg["ranges"]["CO"])[0])
         assert np.array_equal(got, full), dim
 
 
