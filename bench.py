@@ -25,6 +25,7 @@ PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 ma
 TRAFFIC_KIB = {"conv_cout": (427707.0, 31755.6), "conv_cout_h": (251119.0, 16041.4), "gemm_ksplit": (149614.0, 16384.0)}
 TRAFFIC_SCALE = (2.0, 1.0)
 EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
+               "dgrad_cout": "backward of conv_cout: partial dx[128,2560,14,14] from the C_out/8 blocks of dy and the filters (filter reversal included)",
                "gemm_dx_nsplit": "backward of gemm_nsplit: partial dX = dY_s . W_s^T (128x16384x4096), W_s read transposed in place",
                "gemm_dw_nsplit": "backward of gemm_nsplit: dW_s = X^T . dY_s (16384x4096x128), X read transposed in place"}
 METRIC = "shard GEMM/conv TFLOP/s (% fp32 MFMA peak); partition-n-reduce GB/s (% HBM)"

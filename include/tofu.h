@@ -79,7 +79,9 @@ typedef struct {
 typedef enum {
   TOFU_OP_MATMUL = 0,               /* C[m,n]      = sum_k A[m,k] B[k,n]                                     */
   TOFU_OP_CONV2D = 1,               /* y[n,co,h,w] = sum_{ci,kh,kw} x[n,ci,h*s+kh-p,w*s+kw-p] w[co,ci,kh,kw] */
-  TOFU_OP_CONV2D_WGRAD = 2          /* dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] x[n,ci,h*s+kh-p,w*s+kw-p]  */
+  TOFU_OP_CONV2D_WGRAD = 2,         /* dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] x[n,ci,h*s+kh-p,w*s+kw-p]  */
+  TOFU_OP_CONV2D_DGRAD = 3          /* dx[n,ci,ih,iw]  = sum_{co,kh,kw} dy[n,co,h,w] w[co,ci,kh,kw] over the
+                                       (h,w) with h*s+kh-p = ih, w*s+kw-p = iw                               */
 } tofu_op_kind_t;
 
 /* Iteration dimensions a split may name.  Output dimensions give Case-1
@@ -89,6 +91,9 @@ enum { TOFU_MM_DIM_M = 0, TOFU_MM_DIM_N = 1, TOFU_MM_DIM_K = 2 /* reduction */ }
 enum { TOFU_CONV_DIM_N = 0, TOFU_CONV_DIM_CO = 1, TOFU_CONV_DIM_H = 2, TOFU_CONV_DIM_W = 3,
        TOFU_CONV_DIM_CI = 4 /* reduction */ };
 enum { TOFU_WGRAD_DIM_CO = 0, TOFU_WGRAD_DIM_CI = 1, TOFU_WGRAD_DIM_N = 2 /* reduction */ };
+/* data gradient: H and W are the rows / columns of dx, i.e. of the forward INPUT */
+enum { TOFU_DGRAD_DIM_N = 0, TOFU_DGRAD_DIM_CI = 1, TOFU_DGRAD_DIM_H = 2, TOFU_DGRAD_DIM_W = 3,
+       TOFU_DGRAD_DIM_CO = 4 /* reduction */ };
 
 /* Operator description with the shapes of the UNPARTITIONED operator. */
 typedef struct {
@@ -110,14 +115,17 @@ int tofu_shard_range(int64_t extent, int32_t k, int32_t shard, int64_t* lo, int6
  * operator's iteration space and returns
  *   out_box      the box of the output tensor this shard writes (the whole
  *                output when only reduction dimensions were split),
- *   in_boxes[0]  the box of the first input it reads  (A | x | x),
- *   in_boxes[1]  the box of the second input it reads (B | w | dy),
+ *   in_boxes[0]  the box of the first input it reads  (A | x | x  | dy),
+ *   in_boxes[1]  the box of the second input it reads (B | w | dy | w),
  *   pad_lo/hi[2] conv only: rows/columns (index 0 = H, 1 = W) of the needed
  *                window that fall outside the global input on the low/high
  *                side and are therefore zeros; in_boxes[0] is already clipped,
  *   is_partial   1 when a reduction dimension was split (Case-2), else 0.
  * For conv spatial splits the input box is the output range widened by the
- * filter window ("halo", Sec. 4.2).  Any of the out pointers may be NULL. */
+ * filter window ("halo", Sec. 4.2); for the data gradient it is the range of
+ * dy positions whose windows reach the shard's dx rows / columns, and pad_lo/hi
+ * count the window positions of that range that lie outside dy.
+ * Any of the out pointers may be NULL. */
 int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                     tofu_region_t* out_box, tofu_region_t* in_boxes,
                     int64_t* pad_lo, int64_t* pad_hi, int32_t* is_partial);
@@ -181,6 +189,19 @@ int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_split_t* splits
  * and dw receives a full-size partial.  Same parameter limits as above. */
 int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                             const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Shard of the convolution's data gradient (the backward operator that shares
+ * the forward operator's partition group, Sec. 5.1).  The output channel is a
+ * reduction index of this operator, so a CO split is Case-2 (Sec. 4.2) and dx
+ * receives a full-size partial; N / CI / H / W splits are Case-1, H and W
+ * splits reading a halo-widened box of dy.  Implemented for KH = KW = 3,
+ * stride 1, pad 1 -> otherwise UNSUPPORTED.  The workspace (see
+ * tofu_workspace_bytes; 16-byte aligned) receives the shard's filters with
+ * taps reversed and channels exchanged.  dy rows inside the global tensor but
+ * outside dy->extent are REGION_MISMATCH, never zeros. */
+int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                            const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Partition-n-reduce output step (Sec. 3.1 way 2; Sec. 6): dst[i] =

@@ -11,10 +11,11 @@ import os
 from typing import Optional, Sequence
 
 TOFU_MAX_DIMS = 6
-OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD = 0, 1, 2
+OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD = 0, 1, 2, 3
 MM_DIM_M, MM_DIM_N, MM_DIM_K = 0, 1, 2
 CONV_DIM_N, CONV_DIM_CO, CONV_DIM_H, CONV_DIM_W, CONV_DIM_CI = 0, 1, 2, 3, 4
 WGRAD_DIM_CO, WGRAD_DIM_CI, WGRAD_DIM_N = 0, 1, 2
+DGRAD_DIM_N, DGRAD_DIM_CI, DGRAD_DIM_H, DGRAD_DIM_W, DGRAD_DIM_CO = 0, 1, 2, 3, 4
 
 _i64x = ctypes.c_int64 * TOFU_MAX_DIMS
 
@@ -82,14 +83,14 @@ def load():
     lib.tofu_workspace_bytes.restype = sz
     lib.tofu_workspace_bytes.argtypes = [P(OpDesc), P(Split), i32]
     lib.tofu_region_fetch.argtypes = [P(Tensor), P(Tensor), i32, vp]
-    for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad"):
+    for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad", "tofu_shard_conv2d_dgrad"):
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -126,6 +127,11 @@ def conv2d_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1, kind=OP_C
 
 def wgrad_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1) -> OpDesc:
     return conv2d_desc(batch, c_in, c_out, H, W, KH, KW, stride, pad, kind=OP_CONV2D_WGRAD)
+
+
+def dgrad_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1) -> OpDesc:
+    """Data gradient of the convolution whose INPUT is [batch, c_in, H, W]."""
+    return conv2d_desc(batch, c_in, c_out, H, W, KH, KW, stride, pad, kind=OP_CONV2D_DGRAD)
 
 
 def tensor(t, lo: Optional[Sequence[int]] = None) -> Tensor:
@@ -204,6 +210,10 @@ def shard_conv2d_fused(op, splits, x_srcs: Sequence[Tensor], w: Tensor, y: Tenso
 
 def shard_conv2d_wgrad(op, splits, x: Tensor, dy: Tensor, dw: Tensor, workspace=None, stream=None) -> None:
     _shard(load().tofu_shard_conv2d_wgrad, op, splits, x, dy, dw, workspace, stream)
+
+
+def shard_conv2d_dgrad(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d_dgrad, op, splits, dy, w, dx, workspace, stream)
 
 
 def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, stream=None) -> None:

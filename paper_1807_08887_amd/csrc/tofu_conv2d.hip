@@ -360,16 +360,72 @@ static int launch_conv(ConvArgs p, const ConvSources* srcs, int64_t E, hipStream
   return TOFU_OK;
 }
 
-// Shared by the two entry points: `x` is the single buffer that holds the input region, or NULL
-// when the region is read from the `nsrc` blocks `x_srcs`.
+// One convolution-shaped problem after all region arithmetic: write box `out_box` (n, m, h, w)
+// of y from box `in_box` (n, k, rows, columns) of x, where output row h reads input rows
+// h - out_box.lo[2] + kh - pad_lo[0] of the box (zeros outside it), likewise for columns.
+struct ConvProblem {
+  tofu_region_t out_box, in_box;
+  int64_t pad_lo[2];
+  const float* x;            // element at in_box's low corner in the single input buffer, or NULL ...
+  int64_t xs[4];
+  const ConvSources* srcs;   // ... when the box is read from several blocks
+  const float* w;            // element (m_lo, k_lo, 0, 0); strides (m, k, kh, kw)
+  int64_t ws[4];
+  float* y;                  // element at out_box's low corner
+  int64_t ys[4];
+};
+
+static int conv_core(const ConvProblem& q, hipStream_t stream) {
+  ConvArgs p;
+  p.x = q.x; p.w = q.w; p.y = q.y;
+  const int64_t NB = q.out_box.hi[0] - q.out_box.lo[0], CO = q.out_box.hi[1] - q.out_box.lo[1];
+  const int64_t BH = q.out_box.hi[2] - q.out_box.lo[2], BW = q.out_box.hi[3] - q.out_box.lo[3];
+  const int64_t CI = q.in_box.hi[1] - q.in_box.lo[1];
+  const int64_t P = NB * BH * BW;
+  if (P >= (1 << 30) || CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
+  for (int d = 0; d < 4; ++d) { p.xs[d] = q.xs[d]; p.ws[d] = q.ws[d]; p.ys[d] = q.ys[d]; }
+  // lanes address the filters (and a single input buffer) with 32-bit byte offsets from the boxes' low corners
+  int64_t x_span = 1, w_span = 1;
+  const int64_t w_ext[4] = {CO, CI, 3, 3};
+  for (int d = 0; d < 4; ++d) {
+    if (q.xs[d] < 0 || q.ws[d] < 0) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: negative strides are not supported");
+    x_span += (q.in_box.hi[d] - q.in_box.lo[d] - 1) * q.xs[d];
+    w_span += (w_ext[d] - 1) * q.ws[d];
+  }
+  if (x_span >= ((int64_t)1 << 29) || w_span >= ((int64_t)1 << 29))
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: an operand region spans 2 GiB or more");
+  p.x_bytes = q.srcs ? 0u : (uint32_t)(4 * x_span);
+  p.w_bytes = (uint32_t)(4 * w_span);
+  p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
+  p.IH = (int)(q.in_box.hi[2] - q.in_box.lo[2]);
+  p.IW = (int)(q.in_box.hi[3] - q.in_box.lo[3]);
+  p.plh = (int)q.pad_lo[0]; p.plw = (int)q.pad_lo[1];
+  p.LDW = (int)BW + 2;
+  p.w_fast = q.ws[3] == 1 && q.ws[2] == 3 && q.ws[1] == 9 && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
+
+  // Tile choice: 256 positions per workgroup (64x64 per wavefront) when that still leaves about two
+  // workgroups for each of the 256 compute units, else 128 positions; fewer channels per step
+  // when the staged rows are wide.
+  const int64_t tiles_m = (CO + 63) / 64;
+  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
+  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, q.srcs, E256, stream);
+  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, q.srcs, E128, stream);
+  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, q.srcs, E128, stream);
+  return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)E128);
+}
+
+// Shared by the two forward entry points: `x` is the single buffer that holds the input region,
+// or NULL when the region is read from the `nsrc` blocks `x_srcs`.
 static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
                         const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y, void* hip_stream) {
   if (!op || op->kind != TOFU_OP_CONV2D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d");
-  tofu_region_t out_box, in_boxes[2];
-  int64_t pad_lo[2], pad_hi[2];
+  ConvProblem q;
+  tofu_region_t in_boxes[2];
+  int64_t pad_hi[2];
   int32_t partial = 0;
-  int rc = tofu_op_regions(op, splits, nsplits, &out_box, in_boxes, pad_lo, pad_hi, &partial);
+  int rc = tofu_op_regions(op, splits, nsplits, &q.out_box, in_boxes, q.pad_lo, pad_hi, &partial);
   if (rc) return rc;
+  q.in_box = in_boxes[0];
   if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1)
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d kernels implement KH = KW = 3, stride 1, pad 0 or 1");
   const bool multi = x == nullptr;
@@ -382,26 +438,19 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
     return rc;
   }
   if ((rc = check_tensor("w", w, 4, &in_boxes[1]))) return rc;
-  if ((rc = check_tensor("y", y, 4, &out_box))) return rc;
-  if (volume(&out_box) == 0) return TOFU_OK;
+  if ((rc = check_tensor("y", y, 4, &q.out_box))) return rc;
+  if (volume(&q.out_box) == 0) return TOFU_OK;
 
-  int64_t xs[4] = {0, 0, 0, 0}, ws[4], ys[4];
-  effective_strides(w, ws);
-  effective_strides(y, ys);
-  ConvArgs p;
-  p.w = element_ptr(w, ws, in_boxes[1].lo);
-  p.y = const_cast<float*>(element_ptr(y, ys, out_box.lo));
-  const int64_t NB = out_box.hi[0] - out_box.lo[0], CO = out_box.hi[1] - out_box.lo[1];
-  const int64_t BH = out_box.hi[2] - out_box.lo[2], BW = out_box.hi[3] - out_box.lo[3];
-  const int64_t CI = in_boxes[0].hi[1] - in_boxes[0].lo[1];
-  const int64_t P = NB * BH * BW;
-  if (P >= (1 << 30) || CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
-  // lanes address the filters (and a single input buffer) with 32-bit byte offsets from the boxes' low corners
-  int64_t x_span = 1, w_span = 1;
+  effective_strides(w, q.ws);
+  effective_strides(y, q.ys);
+  q.w = element_ptr(w, q.ws, in_boxes[1].lo);
+  q.y = const_cast<float*>(element_ptr(y, q.ys, q.out_box.lo));
   ConvSources srcs;
   srcs.n = 0;
+  q.srcs = nullptr;
   if (multi) {
-    p.x = nullptr;
+    q.x = nullptr;
+    for (int d = 0; d < 4; ++d) q.xs[d] = 0;
     for (int j = 0; j < nsrc; ++j) {
       if (volume(&inter[j]) == 0) continue;
       if (inter[j].lo[1] != in_boxes[0].lo[1] || inter[j].hi[1] != in_boxes[0].hi[1])
@@ -419,38 +468,33 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
         S.hi[i] = (int)(inter[j].hi[dims[i]] - in_boxes[0].lo[dims[i]]);
       }
     }
+    q.srcs = &srcs;
   } else {
-    effective_strides(x, xs);
-    p.x = element_ptr(x, xs, in_boxes[0].lo);
+    effective_strides(x, q.xs);
+    q.x = element_ptr(x, q.xs, in_boxes[0].lo);
   }
-  for (int d = 0; d < 4; ++d) { p.xs[d] = xs[d]; p.ws[d] = ws[d]; p.ys[d] = ys[d]; }
-  for (int d = 0; d < 4; ++d) {
-    if (xs[d] < 0 || ws[d] < 0) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: negative strides are not supported");
-    x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
-    w_span += (in_boxes[1].hi[d] - in_boxes[1].lo[d] - 1) * ws[d];
-  }
-  if (x_span >= ((int64_t)1 << 29) || w_span >= ((int64_t)1 << 29))
-    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: an operand region spans 2 GiB or more");
-  p.x_bytes = multi ? 0u : (uint32_t)(4 * x_span);
-  p.w_bytes = (uint32_t)(4 * w_span);
-  p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
-  p.IH = (int)(in_boxes[0].hi[2] - in_boxes[0].lo[2]);
-  p.IW = (int)(in_boxes[0].hi[3] - in_boxes[0].lo[3]);
-  p.plh = (int)pad_lo[0]; p.plw = (int)pad_lo[1];
-  p.LDW = (int)BW + 2;
-  p.w_fast = ws[3] == 1 && ws[2] == 3 && ws[1] == 9 && ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const ConvSources* sp = multi ? &srcs : nullptr;
+  return conv_core(q, static_cast<hipStream_t>(hip_stream));
+}
 
-  // Tile choice: 256 positions per workgroup (64x64 per wavefront) when that still leaves about two
-  // workgroups for each of the 256 compute units, else 128 positions; fewer channels per step
-  // when the staged rows are wide.
-  const int64_t tiles_m = (CO + 63) / 64;
-  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
-  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, sp, E256, stream);
-  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, sp, E128, stream);
-  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, sp, E128, stream);
-  return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)E128);
+// out[(ci * CO + co) * 9 + t] = w[co, ci, 2 - t / 3, 2 - t % 3]: the filters of the data gradient
+// seen as a forward convolution of dy.  A workgroup moves a 32 x 32 block of (co, ci) pairs
+// through LDS so that both the reads (runs along ci, tap) and the writes (runs along co, tap)
+// are contiguous when the filters are dense.
+__global__ void __launch_bounds__(256) flip_filters_kernel(float* __restrict__ out, const float* __restrict__ w, int64_t s_co,
+                                                           int64_t s_ci, int64_t s_kh, int64_t s_kw, int CO, int CI) {
+  __shared__ float tile[32][32 * 9 + 1];   // [co][ci * 9 + tap]
+  const int co0 = blockIdx.x * 32, ci0 = blockIdx.y * 32;
+  for (int i = threadIdx.x; i < 32 * 288; i += 256) {
+    const int co = i / 288, r = i - co * 288, ci = r / 9, tap = r - ci * 9;
+    float v = 0.f;
+    if (co0 + co < CO && ci0 + ci < CI) v = w[(co0 + co) * s_co + (ci0 + ci) * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw];
+    tile[co][r] = v;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 32 * 288; i += 256) {
+    const int ci = i / 288, r = i - ci * 288, co = r / 9, t = r - co * 9;
+    if (co0 + co < CO && ci0 + ci < CI) out[((int64_t)(ci0 + ci) * CO + co0 + co) * 9 + t] = tile[co][ci * 9 + 8 - t];
+  }
 }
 
 }  // namespace tofu
@@ -468,4 +512,48 @@ extern "C" int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_spli
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
   (void)workspace; (void)workspace_bytes;
   return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, hip_stream);
+}
+
+extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  using namespace tofu;
+  if (!op || op->kind != TOFU_OP_CONV2D_DGRAD) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d data gradient");
+  ConvProblem q;
+  tofu_region_t in_boxes[2];
+  int64_t pad_hi[2];
+  int32_t partial = 0;
+  int rc = tofu_op_regions(op, splits, nsplits, &q.out_box, in_boxes, q.pad_lo, pad_hi, &partial);
+  if (rc) return rc;
+  q.in_box = in_boxes[0];
+  if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad != 1)
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d data-gradient kernels implement KH = KW = 3, stride 1, pad 1");
+  if ((rc = check_tensor("dy", dy, 4, &in_boxes[0]))) return rc;
+  if ((rc = check_tensor("w", w, 4, &in_boxes[1]))) return rc;
+  if ((rc = check_tensor("dx", dx, 4, &q.out_box))) return rc;
+  if (volume(&q.out_box) == 0) return TOFU_OK;
+  const int64_t CO = in_boxes[1].hi[0] - in_boxes[1].lo[0], CI = in_boxes[1].hi[1] - in_boxes[1].lo[1];
+  if (CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
+  const size_t need = (size_t)CO * (size_t)CI * 9 * sizeof(float);
+  if (!workspace || workspace_bytes < need)
+    return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d data-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t wst[4];
+  effective_strides(w, wst);
+  hipLaunchKernelGGL(flip_filters_kernel, dim3((unsigned)((CO + 31) / 32), (unsigned)((CI + 31) / 32)), dim3(256), 0, stream,
+                     static_cast<float*>(workspace), element_ptr(w, wst, in_boxes[1].lo), wst[0], wst[1], wst[2], wst[3], (int)CO, (int)CI);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d data-gradient filter launch failed: %s", hipGetErrorString(e));
+
+  // dx = forward convolution of dy with the reversed filters [ci][co][3][3]
+  effective_strides(dy, q.xs);
+  effective_strides(dx, q.ys);
+  q.x = element_ptr(dy, q.xs, in_boxes[0].lo);
+  q.srcs = nullptr;
+  q.w = static_cast<const float*>(workspace);
+  q.ws[0] = CO * 9; q.ws[1] = 9; q.ws[2] = 3; q.ws[3] = 1;
+  q.y = const_cast<float*>(element_ptr(dx, q.ys, q.out_box.lo));
+  return conv_core(q, stream);
 }

@@ -24,6 +24,7 @@ int iter_ndim(int32_t kind) {
     case TOFU_OP_MATMUL: return 3;
     case TOFU_OP_CONV2D: return 5;
     case TOFU_OP_CONV2D_WGRAD: return 3;
+    case TOFU_OP_CONV2D_DGRAD: return 5;
     default: return 0;
   }
 }
@@ -41,7 +42,7 @@ int check_op(const tofu_op_desc_t* op) {
                   (long long)op->N, (long long)op->K);
     return TOFU_OK;
   }
-  if (op->kind == TOFU_OP_CONV2D || op->kind == TOFU_OP_CONV2D_WGRAD) {
+  if (op->kind == TOFU_OP_CONV2D || op->kind == TOFU_OP_CONV2D_WGRAD || op->kind == TOFU_OP_CONV2D_DGRAD) {
     if (op->batch < 1 || op->c_in < 1 || op->c_out < 1 || op->H < 1 || op->W < 1 || op->KH < 1 || op->KW < 1 ||
         op->stride < 1 || op->pad < 0)
       return fail(TOFU_ERR_INVALID_ARG, "conv needs positive sizes, stride >= 1 and pad >= 0");
@@ -65,6 +66,12 @@ static void iter_extents(const tofu_op_desc_t* op, int64_t* ext, int* first_redu
       ext[TOFU_CONV_DIM_W] = conv_out_extent(op->W, op->KW, op->stride, op->pad);
       ext[TOFU_CONV_DIM_CI] = op->c_in;
       *first_reduce = TOFU_CONV_DIM_CI;
+      break;
+    case TOFU_OP_CONV2D_DGRAD:
+      ext[TOFU_DGRAD_DIM_N] = op->batch; ext[TOFU_DGRAD_DIM_CI] = op->c_in;
+      ext[TOFU_DGRAD_DIM_H] = op->H; ext[TOFU_DGRAD_DIM_W] = op->W;
+      ext[TOFU_DGRAD_DIM_CO] = op->c_out;
+      *first_reduce = TOFU_DGRAD_DIM_CO;
       break;
     default:
       ext[TOFU_WGRAD_DIM_CO] = op->c_out; ext[TOFU_WGRAD_DIM_CI] = op->c_in; ext[TOFU_WGRAD_DIM_N] = op->batch;
@@ -116,6 +123,21 @@ static void window(int64_t out_lo, int64_t out_hi, int64_t ksize, int64_t stride
   int64_t need_hi = (out_hi - 1) * stride + ksize - pad;   // exclusive
   *lo = need_lo < 0 ? 0 : need_lo;
   *hi = need_hi > size ? size : need_hi;
+  *cut_lo = *lo - need_lo;
+  *cut_hi = need_hi - *hi;
+}
+
+// Output positions o whose window o*stride + d - pad, d in [0,ksize), reaches an input coordinate
+// in [in_lo,in_hi): the dy range a data-gradient shard reads, clipped to [0,out_size); cut_lo and
+// cut_hi count the positions of the unclipped range that lie outside dy.
+static void window_back(int64_t in_lo, int64_t in_hi, int64_t ksize, int64_t stride, int64_t pad, int64_t out_size,
+                        int64_t* lo, int64_t* hi, int64_t* cut_lo, int64_t* cut_hi) {
+  const int64_t a = in_lo + pad - (ksize - 1);
+  int64_t need_lo = a >= 0 ? (a + stride - 1) / stride : -((-a) / stride);   // ceil(a / stride)
+  const int64_t b = in_hi - 1 + pad;
+  int64_t need_hi = (b >= 0 ? b / stride : -((-b + stride - 1) / stride)) + 1;  // floor(b / stride) + 1
+  *lo = need_lo < 0 ? 0 : need_lo;
+  *hi = need_hi > out_size ? out_size : need_hi;
   *cut_lo = *lo - need_lo;
   *cut_hi = need_hi - *hi;
 }
@@ -249,6 +271,20 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
     lo[0] = r.lo[CO]; hi[0] = r.hi[CO]; lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
     lo[2] = 0; hi[2] = op->KH; lo[3] = 0; hi[3] = op->KW;
     set_box(&ib[1], 4, lo, hi);
+  } else if (op->kind == TOFU_OP_CONV2D_DGRAD) {
+    const int N = TOFU_DGRAD_DIM_N, CI = TOFU_DGRAD_DIM_CI, H = TOFU_DGRAD_DIM_H, W = TOFU_DGRAD_DIM_W, CO = TOFU_DGRAD_DIM_CO;
+    const int64_t ho = conv_out_extent(op->H, op->KH, op->stride, op->pad), wo = conv_out_extent(op->W, op->KW, op->stride, op->pad);
+    int64_t lo[4], hi[4];
+    lo[0] = r.lo[N]; hi[0] = r.hi[N]; lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
+    lo[2] = r.lo[H]; hi[2] = r.hi[H]; lo[3] = r.lo[W]; hi[3] = r.hi[W];
+    set_box(&ob, 4, lo, hi);
+    lo[1] = r.lo[CO]; hi[1] = r.hi[CO];
+    window_back(r.lo[H], r.hi[H], op->KH, op->stride, op->pad, ho, &lo[2], &hi[2], &plo[0], &phi[0]);
+    window_back(r.lo[W], r.hi[W], op->KW, op->stride, op->pad, wo, &lo[3], &hi[3], &plo[1], &phi[1]);
+    set_box(&ib[0], 4, lo, hi);
+    lo[0] = r.lo[CO]; hi[0] = r.hi[CO]; lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
+    lo[2] = 0; hi[2] = op->KH; lo[3] = 0; hi[3] = op->KW;
+    set_box(&ib[1], 4, lo, hi);
   } else {
     const int CO = TOFU_WGRAD_DIM_CO, CI = TOFU_WGRAD_DIM_CI, N = TOFU_WGRAD_DIM_N;
     int64_t ho = conv_out_extent(op->H, op->KH, op->stride, op->pad), wo = conv_out_extent(op->W, op->KW, op->stride, op->pad);
@@ -282,6 +318,10 @@ size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits
   }
   if (op->kind == TOFU_OP_CONV2D_WGRAD) {
     return wgrad_workspace_bytes(r.hi[0] - r.lo[0], r.hi[1] - r.lo[1], r.hi[2] - r.lo[2]);
+  }
+  if (op->kind == TOFU_OP_CONV2D_DGRAD) {   // the shard's filters, taps reversed and channels exchanged
+    return (size_t)(r.hi[TOFU_DGRAD_DIM_CI] - r.lo[TOFU_DGRAD_DIM_CI]) * (size_t)(r.hi[TOFU_DGRAD_DIM_CO] - r.lo[TOFU_DGRAD_DIM_CO]) *
+           (size_t)(op->KH * op->KW) * sizeof(float);
   }
   return 0;
 }

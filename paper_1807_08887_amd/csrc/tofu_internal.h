@@ -12,7 +12,7 @@ namespace tofu {
 // Record a thread-local error message and return `code` (printf-style).
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 
-// Number of iteration dimensions of an operator kind (3 / 5 / 3), or 0 for an unknown kind.
+// Number of iteration dimensions of an operator kind (3 / 5 / 3 / 5), or 0 for an unknown kind.
 int iter_ndim(int32_t kind);
 
 // Index range of every iteration dimension left to one worker after applying the plan.

@@ -25,6 +25,7 @@ DEV = "cuda:0"
 MM_DIMS = {"M": tofu.MM_DIM_M, "N": tofu.MM_DIM_N, "K": tofu.MM_DIM_K}
 CONV_DIMS = {"N": tofu.CONV_DIM_N, "CO": tofu.CONV_DIM_CO, "H": tofu.CONV_DIM_H, "W": tofu.CONV_DIM_W, "CI": tofu.CONV_DIM_CI}
 WGRAD_DIMS = {"CO": tofu.WGRAD_DIM_CO, "CI": tofu.WGRAD_DIM_CI, "N": tofu.WGRAD_DIM_N}
+DGRAD_DIMS = {"N": tofu.DGRAD_DIM_N, "CI": tofu.DGRAD_DIM_CI, "H": tofu.DGRAD_DIM_H, "W": tofu.DGRAD_DIM_W, "CO": tofu.DGRAD_DIM_CO}
 
 
 def dev(a):
@@ -511,6 +512,64 @@ def test_runs_are_bit_identical():
     c1 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
     c2 = run_matmul(A, B, [], a_full=dA, b_full=dB).cpu().numpy()
     assert np.array_equal(c1, c2)
+
+
+# ----------------------------------------------------------------------------- dgrad
+def run_dgrad(opd, splits, ddy, dw, dy_lo=None):
+    op = tofu.dgrad_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["H"], opd["W"], pad=opd["pad"])
+    sp = [(DGRAD_DIMS[d], k, s) for d, k, s in splits]
+    dx = torch.full((opd["batch"], opd["c_in"], opd["H"], opd["W"]), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_conv2d_dgrad(op, sp, tofu.tensor(ddy, dy_lo), tofu.tensor(dw), tofu.tensor(dx), workspace(op, sp))
+    return dx
+
+
+@pytest.mark.parametrize("batch,c_in,c_out,H,W", [(3, 70, 10, 14, 14), (2, 33, 5, 9, 11), (1, 5, 3, 1, 1), (2, 40, 9, 30, 28),
+                                                  (4, 64, 37, 7, 14)])
+def test_dgrad_shapes_unpartitioned(batch, c_in, c_out, H, W):
+    opd = dict(kind="conv2d_dgrad", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=1)
+    dy = synth.normal(61, 0, (batch, c_out, H, W), 1.0)
+    w = synth.normal(61, 1, (c_out, c_in, 3, 3), 0.3)
+    got = run_dgrad(opd, [], dev(dy), dev(w)).cpu().numpy()
+    val, absum = oracle.dgrad_box(dy, w, H, W, pad=1)
+    assert_close(got, val, absum, f"dgrad {opd}")
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_dgrad_pnr_invariant_bit_exact(k):
+    opd = dict(kind="conv2d_dgrad", batch=4, c_in=72, c_out=12, H=12, W=10, KH=3, KW=3, stride=1, pad=1)
+    dy = synth.small_int(62, 0, (4, 12, 12, 10), -3, 3)
+    w = synth.small_int(62, 1, (12, 72, 3, 3), -3, 3)
+    ddy, dw = dev(dy), dev(w)
+    want = oracle.dgrad_box(dy, w, 12, 10, pad=1)[0]
+    for dim in ["N", "CI", "H", "W", "CO"]:
+        got = assemble(opd, dim, k, lambda sp: run_dgrad(opd, sp, ddy, dw))
+        assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_dgrad_on_blocks_and_strided_filters():
+    """A <CO/2, H/2> shard from the blocks a worker holds: its half of dy's channels with the
+    halo row, and its filter block as a strided view of the whole filter tensor; the partial is
+    checked against the oracle restricted to the shard's output channels."""
+    opd = dict(kind="conv2d_dgrad", batch=3, c_in=40, c_out=16, H=14, W=14, KH=3, KW=3, stride=1, pad=1)
+    dy = synth.normal(63, 0, (3, 16, 14, 14), 1.0)
+    w = synth.normal(63, 1, (16, 40, 3, 3), 0.3)
+    dw_full = dev(w)
+    op = tofu.dgrad_desc(3, 40, 16, 14, 14)
+    for a, b in itertools.product(range(2), repeat=2):
+        plan = [("CO", 2, a), ("H", 2, b)]
+        sp = [(DGRAD_DIMS[d], k, s) for d, k, s in plan]
+        reg = R.op_regions(opd, plan)
+        lib = tofu.op_regions(op, sp)
+        assert lib["in_boxes"][0] == [tuple(t) for t in reg["in_boxes"][0]] and lib["pad_lo"] == reg["pad_lo"]
+        box = reg["in_boxes"][0]
+        blk = dev(dy[R.box_slices(box)].copy())
+        (c0, c1) = reg["ranges"]["CO"]
+        dx = torch.full((3, 40, 14, 14), float("nan"), dtype=torch.float32, device=DEV)
+        tofu.shard_conv2d_dgrad(op, sp, tofu.tensor(blk, [lo for lo, _ in box]), tofu.tensor(dw_full[c0:c1], [c0, 0, 0, 0]),
+                                tofu.tensor(dx), workspace(op, sp))
+        val, absum = oracle.dgrad_box(dy, w, 14, 14, pad=1, box=reg["out_box"], corange=(c0, c1))
+        sl = R.box_slices(reg["out_box"])
+        assert_close(dx.cpu().numpy()[sl], val, absum, f"dgrad {plan}")
 
 
 # ----------------------------------------------------------------------------- probes

@@ -44,7 +44,7 @@ def _check_reduce(leg):
 
 
 @pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_dx_nsplit", "gemm_dw_nsplit"), ("gemm_ksplit", "reduce_gates"),
-                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw")])
+                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",)])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)
     legs = tofu_workloads.build("cuda:0", group)
@@ -76,6 +76,11 @@ def test_full_size_legs(group):
             if leg.name == "conv_cout_h_fused":   # reading the blocks directly changes no bit of the result
                 fetched = next(l for l in legs if l.name == "conv_cout_h")
                 assert torch.equal(leg.out, fetched.out)
+        elif h["kind"] == "dgrad":
+            dxp = leg.out.cpu().numpy()
+            pts = _points(74, 4096, dxp.shape)
+            val, absum = oracle.dgrad_pts(h["dy"], h["w"], h["H"], h["W"], pts, stride=1, pad=1)   # the shard's output channels only
+            _close(dxp[tuple(pts.T)], val, absum, leg.name)
         elif h["kind"] == "wgrad":
             dw = leg.out.cpu().numpy()
             pts = _points(73, 2048, dw.shape)

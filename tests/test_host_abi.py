@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
         names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
-            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused"} <= names
+            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
@@ -50,6 +50,8 @@ def _desc(op):
     args = (op["batch"], op["c_in"], op["c_out"], op["H"], op["W"], op["KH"], op["KW"], op["stride"], op["pad"])
     if op["kind"] == "conv2d":
         return tofu.conv2d_desc(*args), {"N": 0, "CO": 1, "H": 2, "W": 3, "CI": 4}
+    if op["kind"] == "conv2d_dgrad":
+        return tofu.dgrad_desc(*args), {"N": 0, "CI": 1, "H": 2, "W": 3, "CO": 4}
     return tofu.wgrad_desc(*args), {"CO": 0, "CI": 1, "N": 2}
 
 
@@ -67,6 +69,9 @@ OPS = [
     dict(kind="conv2d", batch=4, c_in=4, c_out=4, H=9, W=9, KH=3, KW=3, stride=1, pad=0),
     dict(kind="conv2d_wgrad", batch=6, c_in=5, c_out=7, H=8, W=10, KH=3, KW=3, stride=1, pad=1),
     dict(kind="conv2d_wgrad", batch=6, c_in=5, c_out=7, H=9, W=10, KH=3, KW=2, stride=2, pad=0),
+    dict(kind="conv2d_dgrad", batch=5, c_in=7, c_out=6, H=11, W=9, KH=3, KW=3, stride=1, pad=1),
+    dict(kind="conv2d_dgrad", batch=4, c_in=4, c_out=4, H=9, W=9, KH=3, KW=3, stride=1, pad=0),
+    dict(kind="conv2d_dgrad", batch=4, c_in=4, c_out=4, H=12, W=13, KH=5, KW=3, stride=2, pad=2),
 ]
 
 
@@ -175,6 +180,26 @@ def test_shard_call_error_paths_are_checked_on_the_host():
         tofu.shard_conv2d_wgrad(wg, [], _t([(0, 16), (0, 64), (0, 8), (0, 8)]), _t([(0, 16), (0, 64), (0, 8), (0, 8)], FAKE + (1 << 20)),
                                 _t([(0, 64), (0, 64), (0, 3), (0, 3)], FAKE + (2 << 20)), stream=0)
     assert e.value.status == -5
+
+
+def test_dgrad_error_paths_are_checked_on_the_host():
+    dg = tofu.dgrad_desc(2, 4, 64, 8, 8)
+    dy, w = _t([(0, 2), (0, 64), (0, 8), (0, 8)]), _t([(0, 64), (0, 4), (0, 3), (0, 3)], FAKE + (1 << 20))
+    dx = _t([(0, 2), (0, 4), (0, 8), (0, 8)], FAKE + (2 << 20))
+    assert tofu.workspace_bytes(dg, []) == 64 * 4 * 9 * 4
+    assert tofu.workspace_bytes(dg, [(tofu.DGRAD_DIM_CO, 4, 1), (tofu.DGRAD_DIM_CI, 2, 0)]) == 16 * 2 * 9 * 4
+    with pytest.raises(tofu.TofuError) as e:      # no workspace for the reversed filters
+        tofu.shard_conv2d_dgrad(dg, [], dy, w, dx, stream=0)
+    assert e.value.status == -5
+    with pytest.raises(tofu.TofuError) as e:      # a forward description handed to the gradient entry point
+        tofu.shard_conv2d_dgrad(tofu.conv2d_desc(2, 4, 64, 8, 8), [], dy, w, dx, stream=0)
+    assert e.value.status == -1
+    with pytest.raises(tofu.TofuError) as e:      # halo row 4 of dy missing for the upper half of dx
+        tofu.shard_conv2d_dgrad(dg, [(tofu.DGRAD_DIM_H, 2, 0)], _t([(0, 2), (0, 64), (0, 4), (0, 8)]), w, dx, stream=0)
+    assert e.value.status == -2
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_conv2d_dgrad(tofu.dgrad_desc(2, 4, 64, 8, 8, pad=0), [], _t([(0, 2), (0, 64), (0, 6), (0, 6)]), w, dx, stream=0)
+    assert e.value.status == -6
 
 
 def test_fused_conv_error_paths_are_checked_on_the_host():

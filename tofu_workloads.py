@@ -10,6 +10,7 @@ Builds, from the seeded generator, the device buffers of the four large workload
   fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
   conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
   conv_cout_h_fused  (extra, built only when named) the same shard reading the two blocks directly
+  dgrad_cout         (extra) backward of conv_cout: partial dx from the worker's C_out/8 block of dy and of the filters
   gemm_dx_nsplit     (extra) backward of the N-split gate GEMM: partial dX = dY_s . W_s^T, W_s read transposed in place
   gemm_dw_nsplit     (extra) backward of the N-split gate GEMM: dW_s = X^T . dY_s, X read transposed in place
   wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
@@ -61,7 +62,7 @@ def _ws(op, splits, dev):
 
 STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
 # variants and backward operators outside the step, built only when named
-EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit")
+EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout")
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -195,6 +196,27 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                             _call(tofu.shard_conv2d_fused, op, sp, srcs, tw, tofu.tensor(y3, [0, co0, h0, 0])), y3,
                             dict(host_common, box=reg2["out_box"], keep=(dw, own, halo)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
+
+    if extra("dgrad_cout"):
+        # Data gradient under the forward C_out split: the worker holds dy[:, co0:co1] and its own
+        # filters; C_out is a reduction index of this operator, so dx is a full-size partial.
+        cfg = synth.CONFIGS["wresnet_conv_fwd"]
+        NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
+        opd = tofu.dgrad_desc(NB, C, C, H, W)
+        spd = [(tofu.DGRAD_DIM_CO, k, s)]
+        regd = tofu.op_regions(opd, spd)
+        (co0, co1) = regd["in_boxes"][0][1]
+        w_s = synth.draw(cfg["w"], cfg["seed"], 1, (co1 - co0, C, 3, 3))
+        dy_s = synth.normal(cfg["seed"], 2, (NB, co1 - co0, H, W), 1.0)
+        d_dy, d_w = up(dy_s), up(w_s)
+        part_dx = torch.zeros(NB, C, H, W, dtype=torch.float32, device=dev)
+        wsd = _ws(opd, spd, dev)
+        taps = _conv_valid_taps(0, H, 0, W, H, W)
+        legs.append(Leg("dgrad_cout", "mfma", 2.0 * NB * C * (co1 - co0) * taps,
+                        _call(tofu.shard_conv2d_dgrad, opd, spd, tofu.tensor(d_dy, [0, co0, 0, 0]), tofu.tensor(d_w, [co0, 0, 0, 0]),
+                              tofu.tensor(part_dx), wsd), part_dx,
+                        dict(kind="dgrad", dy=dy_s, w=w_s, H=H, W=W, keep=(d_dy, d_w, wsd)) if keep_host else dict(keep=(d_dy, d_w, wsd)),
+                        conventional_flop=2.0 * NB * C * (co1 - co0) * 9 * H * W))
 
     # ------------------------------------------------------------------ Wide-ResNet conv weight gradient
     if want("wgrad_batch", "reduce_dw"):
