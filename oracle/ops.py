@@ -188,3 +188,19 @@ def reduce(partials):
     v, s, pv, ps = _out(arrs[0].size)
     _load().oracle_reduce(ptrs, _i64(len(arrs)), _i64(arrs[0].size), pv, ps)
     return v.reshape(shape), s.reshape(shape)
+
+
+REDUCERS = {"sum": 0, "max": 1, "min": 2, "prod": 3}
+
+
+def reduce_op(partials, reducer="sum"):
+    """Element-wise Sum / Max / Min / Prod of equally shaped float32 arrays -> (value, scale)."""
+    if reducer == "sum":
+        return reduce(partials)
+    arrs = [np.ascontiguousarray(p, dtype=np.float32) for p in partials]
+    shape = arrs[0].shape
+    assert all(a.shape == shape for a in arrs)
+    ptrs = (_fp * len(arrs))(*[a.ctypes.data_as(_fp) for a in arrs])
+    v, s, pv, ps = _out(arrs[0].size)
+    _load().oracle_reduce_op(ptrs, _i64(len(arrs)), _i64(arrs[0].size), _i64(REDUCERS[reducer]), pv, ps)
+    return v.reshape(shape), s.reshape(shape)

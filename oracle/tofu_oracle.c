@@ -232,6 +232,26 @@ void oracle_reduce(const float* const* partials, i64 k, i64 count, double* val, 
   }
 }
 
+/* The other built-in reducers of the operator description language (Sec. 4.1: Sum, Max, Min,
+ * Prod): the output reduction of a Case-2 split of an operator that reduces with one of them.
+ * op: 1 = Max, 2 = Min, 3 = Prod.  Max / Min are exact (val is one of the inputs; a NaN input is
+ * skipped unless all are NaN, the fmax / fmin convention); Prod multiplies in fp64.
+ * absum[i] = |val[i]| (the scale the tolerance is measured against). */
+void oracle_reduce_op(const float* const* partials, i64 k, i64 count, i64 op, double* val, double* absum) {
+#pragma omp parallel for schedule(static)
+  for (i64 i = 0; i < count; ++i) {
+    double acc = (double)partials[0][i];
+    for (i64 j = 1; j < k; ++j) {
+      double p = (double)partials[j][i];
+      if (op == 1) acc = fmax(acc, p);
+      else if (op == 2) acc = fmin(acc, p);
+      else acc *= p;
+    }
+    val[i] = acc;
+    absum[i] = fabs(acc);
+  }
+}
+
 /* Number of OpenMP threads the loops above will use (reported by the bench). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -396,6 +396,26 @@ def test_reduce_pins():
     assert np.array_equal(oracle.reduce(ints)[0], (ints[0] + ints[1] + ints[2]).astype(np.float64))
 
 
+def test_reduce_other_reducers_pins():
+    """Max / Min / Prod (the description language's other built-in reducers) against numpy."""
+    parts = [synth.normal(9, 40 + j, (7, 19), 2.0) for j in range(5)]
+    st = np.stack(parts).astype(np.float64)
+    assert np.array_equal(oracle.reduce_op(parts, "max")[0], st.max(axis=0))
+    assert np.array_equal(oracle.reduce_op(parts, "min")[0], st.min(axis=0))
+    v, s = oracle.reduce_op(parts, "prod")
+    assert np.allclose(v, st.prod(axis=0), rtol=1e-14, atol=0) and np.array_equal(s, np.abs(v))
+    ints = [synth.small_int(9, 50 + j, (6, 6), -5, 5) for j in range(4)]
+    assert np.array_equal(oracle.reduce_op(ints, "prod")[0], (ints[0] * ints[1] * ints[2] * ints[3]).astype(np.float64))
+    assert np.array_equal(oracle.reduce_op(parts[:1], "max")[0], parts[0].astype(np.float64))   # k = 1 is a copy
+    # a NaN is skipped while another input has a number; all-NaN stays NaN
+    a = np.array([np.nan, 1.0, np.nan], np.float32); b = np.array([2.0, np.nan, np.nan], np.float32)
+    v = oracle.reduce_op([a, b], "max")[0]
+    assert v[0] == 2.0 and v[1] == 1.0 and np.isnan(v[2])
+    # Max over a K split is the partition-n-reduce form of a max-reducing operator: max over halves
+    x = synth.normal(9, 60, (4, 10), 1.0)
+    assert np.array_equal(oracle.reduce_op([x[:, :5].max(axis=1), x[:, 5:].max(axis=1)], "max")[0], x.max(axis=1).astype(np.float64))
+
+
 # ------------------------------------------------------------------ the partition-n-reduce invariant
 def _assemble(op, dim, k, evaluate):
     """Concatenate (Case-1) or sum (Case-2) the k shards produced by evaluate(region)."""
