@@ -213,6 +213,23 @@ int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits
 int tofu_partition_reduce(void* dst, const void* const* partials, int32_t k, int64_t count,
                           void* hip_stream);
 
+/* Reducers of the operator description language (Sec. 4.1) and the two orders
+ * in which k partials can be combined.  TOFU_ORDER_LINEAR folds j = 0..k-1 left
+ * to right; TOFU_ORDER_TREE folds pairwise, fold(l,r) = fold(l,m) (+) fold(m,r)
+ * with m = l + ceil((r-l)/2), the shape of the recursion's binary tree of
+ * workers (Sec. 5.2).  Max and Min are exact in any order; a NaN input is
+ * ignored while another input holds a number (fmax / fmin convention). */
+typedef enum { TOFU_REDUCE_SUM = 0, TOFU_REDUCE_MAX = 1, TOFU_REDUCE_MIN = 2, TOFU_REDUCE_PROD = 3 } tofu_reducer_t;
+typedef enum { TOFU_ORDER_LINEAR = 0, TOFU_ORDER_TREE = 1 } tofu_reduce_order_t;
+
+/* tofu_partition_reduce with a chosen reducer and order; (SUM, LINEAR) is
+ * bit-identical to tofu_partition_reduce.  A reduce-scatter share (worker j
+ * sums only its 1/k slice of every partial) is this call on offset pointers
+ * and the slice's count.  Same argument rules and errors; an unknown reducer
+ * or order -> INVALID_ARG. */
+int tofu_partition_reduce_ex(void* dst, const void* const* partials, int32_t k, int64_t count,
+                             int32_t reducer, int32_t order, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -87,10 +87,11 @@ def load():
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
+    lib.tofu_partition_reduce_ex.argtypes = [vp, P(vp), i32, i64, i32, i32, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -216,8 +217,14 @@ def shard_conv2d_dgrad(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=
     _shard(load().tofu_shard_conv2d_dgrad, op, splits, dy, w, dx, workspace, stream)
 
 
-def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, stream=None) -> None:
-    """dst, partials: CUDA float32 torch tensors (contiguous) or raw device addresses."""
+REDUCE_SUM, REDUCE_MAX, REDUCE_MIN, REDUCE_PROD = 0, 1, 2, 3
+ORDER_LINEAR, ORDER_TREE = 0, 1
+
+
+def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, stream=None, reducer: Optional[int] = None,
+                     order: int = ORDER_LINEAR) -> None:
+    """dst, partials: CUDA float32 torch tensors (contiguous) or raw device addresses.
+    With `reducer` given the call goes to tofu_partition_reduce_ex."""
     def addr(t):
         if isinstance(t, int):
             return t
@@ -227,7 +234,10 @@ def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, strea
     if count is None:
         count = dst.numel()
     ptrs = (ctypes.c_void_p * max(1, len(partials)))(*[addr(p) for p in partials])
-    _check(load().tofu_partition_reduce(ctypes.c_void_p(addr(dst)), ptrs, len(partials), count, _stream(stream)))
+    if reducer is None:
+        _check(load().tofu_partition_reduce(ctypes.c_void_p(addr(dst)), ptrs, len(partials), count, _stream(stream)))
+    else:
+        _check(load().tofu_partition_reduce_ex(ctypes.c_void_p(addr(dst)), ptrs, len(partials), count, reducer, order, _stream(stream)))
 
 
 def probe_mfma(sink, iters: int, workgroups: int, stream=None) -> None:

@@ -56,6 +56,8 @@ size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb);
 // Enqueue dst[i] = sum_j parts[j][i] (fixed order j = 0..k-1); used by the public reduce and
 // by the kernels that split their own reduction.  Pointers are device pointers.
 int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, void* stream);
+// The same with a reduction mode: 0 sum left to right, 1 sum pairwise, 2 / 3 product likewise, 4 max, 5 min.
+int launch_reduce_mode(float* dst, const float* const* parts, int k, int64_t count, int mode, void* stream);
 
 }  // namespace tofu
 

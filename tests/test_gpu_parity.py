@@ -572,6 +572,72 @@ def test_dgrad_on_blocks_and_strided_filters():
         assert_close(dx.cpu().numpy()[sl], val, absum, f"dgrad {plan}")
 
 
+# ----------------------------------------------------------------------------- reducers and orders
+def _tree_f32(parts, op):
+    """fold(l, r) = fold(l, m) op fold(m, r), m = l + ceil((r - l) / 2), in float32 like the kernel."""
+    def fold(l, r):
+        if r - l == 1:
+            return parts[l]
+        m = l + (r - l + 1) // 2
+        return op(fold(l, m), fold(m, r))
+    return fold(0, len(parts))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 8, 16])
+def test_reduce_reducers_and_orders(k):
+    n = 4 * 50021 + 3                                    # vector body plus a scalar tail
+    parts = [synth.normal(81, j, (n,), 1.5) for j in range(k)]
+    d = [dev(p) for p in parts]
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    # Max / Min: exact, equal to the oracle bit for bit
+    for red, name in [(tofu.REDUCE_MAX, "max"), (tofu.REDUCE_MIN, "min")]:
+        tofu.partition_reduce(out, d, reducer=red)
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.reduce_op(parts, name)[0]), name
+    # Sum in both orders: within tolerance of the oracle, and bit-exact against the same order in float32
+    val, absum = oracle.reduce(parts)
+    tofu.partition_reduce(out, d, reducer=tofu.REDUCE_SUM, order=tofu.ORDER_LINEAR)
+    lin = out.cpu().numpy()
+    ref = parts[0].copy()
+    for p in parts[1:]:
+        ref = ref + p
+    assert np.array_equal(lin, ref)
+    plain = torch.empty_like(out)
+    tofu.partition_reduce(plain, d)
+    assert torch.equal(plain, out)                       # (SUM, LINEAR) is the plain entry point
+    tofu.partition_reduce(out, d, reducer=tofu.REDUCE_SUM, order=tofu.ORDER_TREE)
+    tree = out.cpu().numpy()
+    assert np.array_equal(tree, _tree_f32(parts, lambda a, b: a + b))
+    assert_close(tree, val, absum, "tree sum")
+    # Prod: |gpu - oracle| <= 1e-5 |prod| (k - 1 roundings of 2^-24 each)
+    small = [synth.uniform(82, j, (n,), 0.5, 1.5) for j in range(k)]
+    ds = [dev(p) for p in small]
+    pv, ps = oracle.reduce_op(small, "prod")
+    for order in (tofu.ORDER_LINEAR, tofu.ORDER_TREE):
+        tofu.partition_reduce(out, ds, reducer=tofu.REDUCE_PROD, order=order)
+        assert_close(out.cpu().numpy(), pv, ps, f"prod order {order}")
+    tofu.partition_reduce(out, ds, reducer=tofu.REDUCE_PROD, order=tofu.ORDER_TREE)
+    assert np.array_equal(out.cpu().numpy(), _tree_f32(small, lambda a, b: a * b))
+
+
+def test_reduce_nan_convention_in_place_and_scatter_share():
+    a = np.array([np.nan, 1.0, np.nan, -2.0] * 8, np.float32)
+    b = np.array([2.0, np.nan, np.nan, 5.0] * 8, np.float32)
+    da, db = dev(a), dev(b)
+    tofu.partition_reduce(da, [da, db], reducer=tofu.REDUCE_MAX)       # in place on partials[0]
+    got = da.cpu().numpy()
+    want = oracle.reduce_op([a, b], "max")[0]
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+    # a reduce-scatter share: worker j sums slice j of every partial into slice j of the output
+    k, n = 4, 4 * 1000
+    parts = [synth.small_int(83, j, (n,), -50, 50) for j in range(k)]
+    d = [dev(p) for p in parts]
+    out = torch.full((n,), float("nan"), dtype=torch.float32, device=DEV)
+    for j in range(k):
+        lo, hi = R.shard_range(n, k, j)
+        tofu.partition_reduce(out[lo:hi], [p[lo:hi] for p in d], reducer=tofu.REDUCE_SUM, order=tofu.ORDER_TREE)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.reduce(parts)[0])
+
+
 # ----------------------------------------------------------------------------- probes
 def test_probes_copy_exactly_and_leave_the_sink_alone():
     """The measurement aids of tofu_probe.h: the copy is bit-exact on a ragged vector count,

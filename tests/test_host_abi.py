@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
         names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
-            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad"} <= names
+            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
@@ -232,6 +232,12 @@ def test_reduce_error_paths_are_checked_on_the_host():
     assert lib.tofu_partition_reduce(None, ptrs, 2, 16, None) == -1
     assert lib.tofu_partition_reduce(None, ptrs, 2, 0, None) == 0                              # empty is a no-op
     assert "k = 17" in tofu.last_error() or tofu.last_error()
+    ex = lib.tofu_partition_reduce_ex
+    assert ex(C.c_void_p(FAKE + (1 << 20)), ptrs, 2, 16, 4, 0, None) == -1      # unknown reducer
+    assert ex(C.c_void_p(FAKE + (1 << 20)), ptrs, 2, 16, 0, 2, None) == -1      # unknown order
+    assert ex(C.c_void_p(FAKE + (1 << 20)), ptrs, 17, 16, 1, 0, None) == -1
+    assert ex(C.c_void_p(FAKE + 4096 + 8), ptrs, 2, 16, 3, 1, None) == -1       # overlaps partials[1]
+    assert ex(None, ptrs, 2, 0, 1, 1, None) == 0
 
 
 def test_probe_error_paths_are_checked_on_the_host():
