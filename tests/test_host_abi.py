@@ -19,13 +19,14 @@ FAKE = 0x7F0000000000        # a non-null "device pointer"; nothing below ever d
 def test_library_exports_every_declared_symbol():
     import glob
     headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
-    assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_probe.h"]
+    assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_probe.h", "tofu_tdl.h"]
     names = set()
     for h in headers:
         names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
-            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex"} <= names
+            "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_tdl_regions", "tofu_tdl_symbolic", "tofu_tdl_from_op",
+            "tofu_tdl_fetch_elements"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
