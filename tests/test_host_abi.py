@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_probe.h", "tofu_tdl.h"]
     names = set()
     for h in headers:
-        names |= set(re.findall(r"\b(tofu_[a-z0-9_]+)\s*\(", open(h).read()))
+        names |= set(re.findall(r"^(?:int|size_t|const char\*)\s+(tofu_[a-z0-9_]+)\s*\(", open(h).read(), flags=re.M))
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
             "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_tdl_regions", "tofu_tdl_symbolic", "tofu_tdl_from_op",
