@@ -19,6 +19,8 @@
 //     32-63: ci+1); the B operand of a lane is one LDS read at (its position's row/col) + tap.
 #include <hip/hip_runtime.h>
 
+#include <string.h>
+
 #include <type_traits>
 
 #include "tofu_internal.h"
@@ -42,6 +44,12 @@ struct ConvArgs {
   int PL;           // floats per staged channel plane
   int E;            // upper bound over all tiles of the staged floats per channel (<= PL)
   int w_fast;       // 1: weights dense over (ci,kh,kw) and 16-byte aligned -> vector loads
+  // Balanced launches: the tiles [tile0, tile0 + n_tiles) times their channel steps are cut into
+  // units and dealt evenly to `groups` workgroups; every run of units inside one tile (a segment)
+  // leaves its accumulators in slot (workgroup * max_segments + segment) of `slots`.
+  // Whole-tile launches cover the same tile range with one workgroup per tile.
+  int tile0, n_tiles, groups, max_segments;
+  float* slots;
 };
 
 // Input region held by several blocks (the fetch fused into the consumer, Sec. 6): every block
@@ -73,7 +81,7 @@ struct ConvCfg {
   static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI, bool BALANCED>
 __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources* srcs) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
@@ -85,17 +93,40 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   float* Ws = lds;                           // [2][WB]: KK rows of LDM floats + scratch
   float* Xs = lds + 2 * WB;                  // [2][XB]: CK planes of PL floats + scratch
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int wm = wave / WN, wn = wave % WN;
-
   // Compute units are handed workgroups round-robin over the 8 XCDs; renumber so that
-  // consecutive logical tiles (which share staged input rows) land on the same XCD's L2.
-  const int total = p.tiles_m * p.tiles_n;
+  // consecutive logical workgroups (which share staged input rows) land on the same XCD's L2.
+  const int total = BALANCED ? p.groups : p.n_tiles;
   const int per_xcd = (total + 7) / 8;
   const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (lid >= total) return;                   // grid is padded to a multiple of 8
-  const int tile_n = lid / p.tiles_m, tile_m = lid % p.tiles_m;
+  const int steps_all = (p.CI + CK - 1) / CK;
+  // balanced: this workgroup's run of units [u, u_end) of (tile, channel step) pairs
+  const int64_t n_units = (int64_t)p.n_tiles * steps_all;
+  int64_t u = BALANCED ? lid * n_units / p.groups : 0;
+  const int64_t u_end = BALANCED ? (lid + 1) * n_units / p.groups : 0;
+  int segment = 0;
+  do {
+  // The per-lane staging lists below are rebuilt for every segment.  The thread index is made
+  // opaque once per segment so that the parts of them that do not depend on the tile are not
+  // kept in registers across the step loop of the previous segment.
+  int tid = threadIdx.x;
+  if (BALANCED) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN;
+  int tile, s_begin, s_end;
+  if (BALANCED) {
+    const int t_rel = (int)(u / steps_all);
+    tile = __builtin_amdgcn_readfirstlane(p.tile0 + t_rel);
+    s_begin = __builtin_amdgcn_readfirstlane((int)(u - (int64_t)t_rel * steps_all));
+    s_end = __builtin_amdgcn_readfirstlane((int)min((int64_t)steps_all, s_begin + (u_end - u)));
+    u += s_end - s_begin;
+  } else {
+    tile = p.tile0 + lid;
+    s_begin = 0;
+    s_end = steps_all;
+  }
+  const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
   const int m0 = tile_m * BM;
   const int p_begin = tile_n * BN;
   const int p_end = min(p.P, p_begin + BN);
@@ -152,7 +183,8 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 
   float rx[XJ];
   v4f32 rw[WV];
-  auto load_global = [&](int step) {
+  auto load_global = [&](int local_step) {
+    const int step = s_begin + local_step;      // channel step of the whole reduction
     const int ci0 = step * CK;
     const bool whole = ci0 + CK <= p.CI;        // only the last step can run past the shard's channels
     if constexpr (MULTI) {
@@ -223,7 +255,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 #pragma unroll
     for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
 
-  const int steps = (p.CI + CK - 1) / CK;
+  const int steps = s_end - s_begin;
   constexpr int KS = (CK / 2) * 9;            // MFMA k-steps per step: (channel pair, tap)
   // Staging work of one step = XJ input items + WV weight items.  In a HOT step each item (write
   // last step's registers to LDS, then reload them for the step after next) is issued between
@@ -232,7 +264,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   // step (or weights that are not dense) use the guarded loads in one block instead.
   constexpr int NI = XJ + WV, STRIDE = (KS - 2) / NI > 0 ? (KS - 2) / NI : 1;
   static_assert(1 + (NI - 1) * STRIDE < KS, "staging items must fit into one step");
-  const int n_hot = !p.w_fast ? 0 : p.CI % CK == 0 ? steps : max(0, steps - 3);
+  const int n_hot = !p.w_fast ? 0 : (p.CI % CK == 0 || s_end < steps_all) ? steps : max(0, steps - 3);
 
   // Pipeline: the tiles of step t+1 are written to LDS during step t, and right after each write
   // the global load of step t+2 is issued into the same register, so every load has a whole step
@@ -250,8 +282,8 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
     const float* xs = Xs + buf * XB;
     float* xs_next = Xs + (buf ^ 1) * XB;
     float* ws_next = Ws + (buf ^ 1) * WB;
-    const int nxt = min(t + 2, steps - 1);
-    const uint32_t x_soff = MULTI ? 0u : 4u * (uint32_t)((int64_t)nxt * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt * CK);
+    const int nxt = min(t + 2, steps - 1), nxt_abs = s_begin + nxt;
+    const uint32_t x_soff = MULTI ? 0u : 4u * (uint32_t)((int64_t)nxt_abs * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt_abs * CK);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
@@ -270,7 +302,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
           const int item = (s - 1) / STRIDE;
           if (item < XJ) {
             xs_next[x_loff[item]] = rx[item];
-            if constexpr (MULTI) rx[item] = x_ptr[item][(int64_t)nxt * x_inc[item]];
+            if constexpr (MULTI) rx[item] = x_ptr[item][(int64_t)nxt_abs * x_inc[item]];
             else rx[item] = buf_load(x_rsrc, x_voff[item], x_soff);
           } else {
             const int i = item - XJ;
@@ -294,29 +326,80 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   for (int t = 0; t < n_hot; ++t) run_step(t, std::true_type());
   for (int t = n_hot; t < steps; ++t) run_step(t, std::false_type());
 
+  if constexpr (BALANCED) {
+    // slot [(i, j, v)][thread]: every store instruction of the workgroup writes NT consecutive floats
+    float* o = p.slots + ((int64_t)lid * p.max_segments + segment) * (BM * BN) + tid;
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      if (!pos_ok[j]) continue;
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int co = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
-        if (co < p.CO) p.y[y_off[j] + (int64_t)co * p.ys[1]] = acc[i][j][v];
+        for (int v = 0; v < 16; ++v) o[((i * FN + j) * 16 + v) * NT] = acc[i][j][v];
+    __syncthreads();   // the next segment's prologue overwrites LDS buffer 0
+    ++segment;
+  } else {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        if (!pos_ok[j]) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int co = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
+          if (co < p.CO) p.y[y_off[j] + (int64_t)co * p.ys[1]] = acc[i][j][v];
+        }
       }
-    }
+  }
+  } while (BALANCED && u < u_end);
+}
+
+// Sums the slots of every balanced tile in workgroup order and writes the output box.  One
+// workgroup per (tile, 32x32 accumulator block): thread and accumulator index map to (channel,
+// position) exactly as in the convolution kernel, so reads are NT consecutive floats and writes
+// follow the output rows.
+template <int BM, int BN, int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN) conv2d_segment_sum_kernel(const ConvArgs p, int steps_all) {
+  constexpr int NT = 64 * WM * WN, TM = BM / WM, TN = BN / WN, FN = TN / 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN;
+  const int t_rel = blockIdx.x, blk = blockIdx.y, i = blk / FN, j = blk % FN;
+  const int tile = p.tile0 + t_rel, tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
+  const int64_t n_units = (int64_t)p.n_tiles * steps_all;
+  // workgroups whose unit ranges meet this tile: g(u) = floor(((u + 1) * G - 1) / N)
+  const int64_t u0 = (int64_t)t_rel * steps_all, u1 = u0 + steps_all - 1;
+  const int g_first = (int)(((u0 + 1) * p.groups - 1) / n_units), g_last = (int)(((u1 + 1) * p.groups - 1) / n_units);
+  const int pp = tile_n * BN + wn * TN + j * 32 + l32;
+  const bool pos_ok = pp < p.P;
+  const int plane = p.BH * p.BW;
+  const int img = pp / plane, q = pp - img * plane, oh = q / p.BW, ow = q - oh * p.BW;
+  const int64_t y_off = (int64_t)img * p.ys[0] + (int64_t)oh * p.ys[2] + (int64_t)ow * p.ys[3];
+  float acc[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int g = g_first; g <= g_last; ++g) {
+    const int first_tile = (int)((g * n_units / p.groups) / steps_all);   // tile of the workgroup's first unit = its segment 0
+    const float* sl = p.slots + ((int64_t)g * p.max_segments + (t_rel - first_tile)) * (BM * BN) + (i * FN + j) * 16 * NT + tid;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += sl[v * NT];
+  }
+  if (!pos_ok) return;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int co = tile_m * BM + wm * TM + i * 32 + acc_row(v, half);
+    if (co < p.CO) p.y[y_off + (int64_t)co * p.ys[1]] = acc[v];
+  }
 }
 
 // input region in one buffer
-template <int BM, int BN, int CK, int WM, int WN, int XJ>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, false>(p, nullptr);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, false, BALANCED>(p, nullptr);
 }
 
 // input region read from the blocks that hold it
-template <int BM, int BN, int CK, int WM, int WN, int XJ>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_multi_kernel(const ConvArgs p, const ConvSources srcs) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, true>(p, &srcs);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, true, BALANCED>(p, &srcs);
 }
 
 constexpr size_t kLdsLimit = 160 * 1024;
@@ -333,28 +416,92 @@ static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN) {
   return max_slots * (BW + 2);
 }
 
+constexpr int kConvSlots = 512;        // two resident workgroups on each of the 256 compute units
+
+// Which kernel shape a shard of P positions in BH x BW boxes uses, and how its tiles are launched:
+// the first `whole` tiles one workgroup each (full waves of kConvSlots), the remaining `rest`
+// tiles cut into (tile, channel step) units dealt evenly to `groups` workgroups.
+struct ConvPlan {
+  int variant;        // 0: 64 x 256 positions, 4 channels per step; 1: 64 x 128, 8 channels; 2: 64 x 128, 4 channels; -1: none fits
+  int64_t E;          // staged floats per channel
+  int64_t tiles, whole, rest;
+  int groups, max_segments;
+  int BN, CK;
+};
+
+static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
+  ConvPlan pl;
+  memset(&pl, 0, sizeof(pl));
+  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
+  // 256 positions per workgroup (64 x 64 per wavefront) whenever its staged rows fit and the shard
+  // has at least that many positions; else 128 positions, with fewer channels per step when the
+  // staged rows are wide.
+  if (P >= 256 && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
+  else if (8 * E128 <= 10 * 256) { pl.variant = 1; pl.E = E128; pl.BN = 128; pl.CK = 8; }
+  else if (4 * E128 <= 10 * 256) { pl.variant = 2; pl.E = E128; pl.BN = 128; pl.CK = 4; }
+  else { pl.variant = -1; pl.E = E128; return pl; }
+  pl.tiles = ((CO + 63) / 64) * ((P + pl.BN - 1) / pl.BN);
+  const int64_t steps = (CI + pl.CK - 1) / pl.CK;
+  pl.rest = pl.tiles % kConvSlots;
+  // a last wave that is nearly full, or a reduction too short to cut, is launched as whole tiles
+  if (pl.rest * 32 >= kConvSlots * 31 || steps < 4) pl.rest = 0;
+  pl.whole = pl.tiles - pl.rest;
+  if (pl.rest > 0) {
+    const int64_t units = pl.rest * steps;
+    pl.groups = (int)(units < kConvSlots ? units : kConvSlots);
+    const int64_t per = (units + pl.groups - 1) / pl.groups;           // most units per workgroup
+    pl.max_segments = (int)((per + steps - 2) / steps + 1);
+  }
+  return pl;
+}
+
+size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
+  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI);
+  if (pl.variant < 0 || pl.rest == 0) return 0;
+  return (size_t)pl.groups * pl.max_segments * 64 * pl.BN * sizeof(float);
+}
+
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
-static int launch_conv(ConvArgs p, const ConvSources* srcs, int64_t E, hipStream_t stream) {
+static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, hipStream_t stream) {
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
   p.tiles_m = (p.CO + BM - 1) / BM;
   p.tiles_n = (p.P + BN - 1) / BN;
-  p.E = (int)E;
+  p.E = (int)pl.E;
   p.PL = (p.E + 63) / 64 * 64 + 32;
   const size_t lds_bytes = sizeof(float) * Cfg::lds_floats(p.PL);
   if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
-  auto kern = conv2d_kernel<BM, BN, CK, WM, WN, XJ>;
-  auto kern_multi = conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ>;
-  static bool attr_set[2] = {false, false};
-  const int which = srcs ? 1 : 0;
-  if (!attr_set[which]) {
-    const void* fn = srcs ? reinterpret_cast<const void*>(kern_multi) : reinterpret_cast<const void*>(kern);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
-    attr_set[which] = true;
+  const void* fns[4] = {reinterpret_cast<const void*>(conv2d_kernel<BM, BN, CK, WM, WN, XJ, false>),
+                        reinterpret_cast<const void*>(conv2d_kernel<BM, BN, CK, WM, WN, XJ, true>),
+                        reinterpret_cast<const void*>(conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>),
+                        reinterpret_cast<const void*>(conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>)};
+  static bool attr_set = false;
+  if (!attr_set) {
+    for (const void* fn : fns) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+      if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
+    }
+    attr_set = true;
   }
-  const int total = p.tiles_m * p.tiles_n;
-  if (srcs) hipLaunchKernelGGL(kern_multi, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p, *srcs);
-  else hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8), dim3(Cfg::kThreads), lds_bytes, stream, p);
+  auto launch = [&](bool balanced, int wgs) {
+    const dim3 grid((wgs + 7) / 8 * 8), block(Cfg::kThreads);
+    if (srcs) {
+      if (balanced) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p, *srcs);
+      else hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p, *srcs);
+    } else {
+      if (balanced) hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p);
+      else hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p);
+    }
+  };
+  if (pl.whole > 0) {
+    p.tile0 = 0; p.n_tiles = (int)pl.whole; p.groups = 0; p.max_segments = 0;
+    launch(false, (int)pl.whole);
+  }
+  if (pl.rest > 0) {
+    p.tile0 = (int)pl.whole; p.n_tiles = (int)pl.rest; p.groups = pl.groups; p.max_segments = pl.max_segments;
+    launch(true, pl.groups);
+    hipLaunchKernelGGL((conv2d_segment_sum_kernel<BM, BN, WM, WN>), dim3((unsigned)pl.rest, Cfg::FM * Cfg::FN), dim3(Cfg::kThreads), 0, stream,
+                       p, (p.CI + CK - 1) / CK);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d launch failed: %s", hipGetErrorString(e));
   return TOFU_OK;
@@ -373,6 +520,8 @@ struct ConvProblem {
   int64_t ws[4];
   float* y;                  // element at out_box's low corner
   int64_t ys[4];
+  void* workspace;           // segment slots of a balanced launch (conv_workspace_bytes), may be NULL when none are needed
+  size_t workspace_bytes;
 };
 
 static int conv_core(const ConvProblem& q, hipStream_t stream) {
@@ -403,21 +552,26 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   p.LDW = (int)BW + 2;
   p.w_fast = q.ws[3] == 1 && q.ws[2] == 3 && q.ws[1] == 9 && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
 
-  // Tile choice: 256 positions per workgroup (64x64 per wavefront) when that still leaves about two
-  // workgroups for each of the 256 compute units, else 128 positions; fewer channels per step
-  // when the staged rows are wide.
-  const int64_t tiles_m = (CO + 63) / 64;
-  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
-  if (tiles_m * ((P + 255) / 256) >= 400 && 4 * E256 <= 8 * 256) return launch_conv<64, 256, 4, 1, 4, 8>(p, q.srcs, E256, stream);
-  if (8 * E128 <= 10 * 256) return launch_conv<64, 128, 8, 1, 4, 10>(p, q.srcs, E128, stream);
-  if (4 * E128 <= 10 * 256) return launch_conv<64, 128, 4, 1, 4, 10>(p, q.srcs, E128, stream);
-  return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)E128);
+  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI);
+  if (pl.variant < 0)
+    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)pl.E);
+  const size_t need = conv_workspace_bytes(P, BH, BW, CO, CI);
+  if (need > 0) {
+    if (!q.workspace || q.workspace_bytes < need)
+      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d shard needs %zu workspace bytes, got %zu", need, q.workspace ? q.workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(q.workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  }
+  p.slots = static_cast<float*>(q.workspace);
+  if (pl.variant == 0) return launch_conv<64, 256, 4, 1, 4, 8>(p, q.srcs, pl, stream);
+  if (pl.variant == 1) return launch_conv<64, 128, 8, 1, 4, 10>(p, q.srcs, pl, stream);
+  return launch_conv<64, 128, 4, 1, 4, 10>(p, q.srcs, pl, stream);
 }
 
 // Shared by the two forward entry points: `x` is the single buffer that holds the input region,
 // or NULL when the region is read from the `nsrc` blocks `x_srcs`.
 static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
-                        const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y, void* hip_stream) {
+                        const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
   if (!op || op->kind != TOFU_OP_CONV2D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d");
   ConvProblem q;
   tofu_region_t in_boxes[2];
@@ -473,6 +627,8 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
     effective_strides(x, q.xs);
     q.x = element_ptr(x, q.xs, in_boxes[0].lo);
   }
+  q.workspace = workspace;
+  q.workspace_bytes = workspace_bytes;
   return conv_core(q, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -502,16 +658,14 @@ __global__ void __launch_bounds__(256) flip_filters_kernel(float* __restrict__ o
 extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                                  const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
                                  size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   if (!x) return tofu::fail(TOFU_ERR_INVALID_ARG, "x is NULL");
-  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, hip_stream);
+  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                                        const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
-  return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, hip_stream);
+  return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
@@ -534,7 +688,10 @@ extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_spli
   if (volume(&q.out_box) == 0) return TOFU_OK;
   const int64_t CO = in_boxes[1].hi[0] - in_boxes[1].lo[0], CI = in_boxes[1].hi[1] - in_boxes[1].lo[1];
   if (CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d shard extent exceeds 2^30");
-  const size_t need = (size_t)CO * (size_t)CI * 9 * sizeof(float);
+  // workspace = reversed filters, then (from the next 256-byte boundary) the convolution's segment slots
+  const size_t flip_bytes = ((size_t)CO * (size_t)CI * 9 * sizeof(float) + 255) / 256 * 256;
+  const int64_t P = (q.out_box.hi[0] - q.out_box.lo[0]) * (q.out_box.hi[2] - q.out_box.lo[2]) * (q.out_box.hi[3] - q.out_box.lo[3]);
+  const size_t need = flip_bytes + conv_workspace_bytes(P, q.out_box.hi[2] - q.out_box.lo[2], q.out_box.hi[3] - q.out_box.lo[3], CI, CO);
   if (!workspace || workspace_bytes < need)
     return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d data-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
   if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
@@ -555,5 +712,7 @@ extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_spli
   q.w = static_cast<const float*>(workspace);
   q.ws[0] = CO * 9; q.ws[1] = 9; q.ws[2] = 3; q.ws[3] = 1;
   q.y = const_cast<float*>(element_ptr(dx, q.ys, q.out_box.lo));
+  q.workspace = static_cast<char*>(workspace) + flip_bytes;
+  q.workspace_bytes = workspace_bytes - flip_bytes;
   return conv_core(q, stream);
 }

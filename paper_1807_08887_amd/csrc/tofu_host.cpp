@@ -319,9 +319,18 @@ size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits
   if (op->kind == TOFU_OP_CONV2D_WGRAD) {
     return wgrad_workspace_bytes(r.hi[0] - r.lo[0], r.hi[1] - r.lo[1], r.hi[2] - r.lo[2]);
   }
-  if (op->kind == TOFU_OP_CONV2D_DGRAD) {   // the shard's filters, taps reversed and channels exchanged
-    return (size_t)(r.hi[TOFU_DGRAD_DIM_CI] - r.lo[TOFU_DGRAD_DIM_CI]) * (size_t)(r.hi[TOFU_DGRAD_DIM_CO] - r.lo[TOFU_DGRAD_DIM_CO]) *
-           (size_t)(op->KH * op->KW) * sizeof(float);
+  if (op->kind == TOFU_OP_CONV2D) {         // segment slots of the balanced last wave
+    const int64_t bh = r.hi[TOFU_CONV_DIM_H] - r.lo[TOFU_CONV_DIM_H], bw = r.hi[TOFU_CONV_DIM_W] - r.lo[TOFU_CONV_DIM_W];
+    if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1) return 0;
+    return conv_workspace_bytes((r.hi[TOFU_CONV_DIM_N] - r.lo[TOFU_CONV_DIM_N]) * bh * bw, bh, bw,
+                                r.hi[TOFU_CONV_DIM_CO] - r.lo[TOFU_CONV_DIM_CO], r.hi[TOFU_CONV_DIM_CI] - r.lo[TOFU_CONV_DIM_CI]);
+  }
+  if (op->kind == TOFU_OP_CONV2D_DGRAD) {   // the shard's filters, taps reversed and channels exchanged, then the slots
+    const int64_t ci = r.hi[TOFU_DGRAD_DIM_CI] - r.lo[TOFU_DGRAD_DIM_CI], co = r.hi[TOFU_DGRAD_DIM_CO] - r.lo[TOFU_DGRAD_DIM_CO];
+    const int64_t bh = r.hi[TOFU_DGRAD_DIM_H] - r.lo[TOFU_DGRAD_DIM_H], bw = r.hi[TOFU_DGRAD_DIM_W] - r.lo[TOFU_DGRAD_DIM_W];
+    const size_t flip = ((size_t)ci * (size_t)co * (size_t)(op->KH * op->KW) * sizeof(float) + 255) / 256 * 256;
+    if (op->KH != 3 || op->KW != 3 || op->stride != 1) return flip;
+    return flip + conv_workspace_bytes((r.hi[TOFU_DGRAD_DIM_N] - r.lo[TOFU_DGRAD_DIM_N]) * bh * bw, bh, bw, ci, co);
   }
   return 0;
 }

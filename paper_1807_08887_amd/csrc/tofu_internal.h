@@ -53,6 +53,10 @@ int matmul_split_k(int64_t m, int64_t n, int64_t k);
 // Workspace the weight-gradient kernel needs for a shard of co x ci output channels and nb images.
 size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb);
 
+// Workspace the convolution kernels need for a shard of P positions in BH x BW output boxes with
+// co output and ci input channels (the segment slots of its balanced last wave, possibly 0).
+size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t co, int64_t ci);
+
 // Enqueue dst[i] = sum_j parts[j][i] (fixed order j = 0..k-1); used by the public reduce and
 // by the kernels that split their own reduction.  Pointers are device pointers.
 int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, void* stream);

@@ -413,7 +413,7 @@ def test_conv2d_fused_fetch_matches_oracle_and_the_assembled_region(shape, cuts)
         sp = [(CONV_DIMS[d], k, s) for d, k, s in plan]
         reg = R.op_regions(opd, plan)
         y = torch.full((batch, c_out, H, W), float("nan"), dtype=torch.float32, device=DEV)
-        tofu.shard_conv2d_fused(op, sp, srcs, tofu.tensor(dw), tofu.tensor(y))
+        tofu.shard_conv2d_fused(op, sp, srcs, tofu.tensor(dw), tofu.tensor(y), workspace(op, sp))
         sl = R.box_slices(reg["out_box"])
         got = y.cpu().numpy()
         assert_close(got[sl], val[sl], absum[sl], f"fused conv {plan}")
@@ -434,7 +434,7 @@ def test_conv2d_fused_fetch_error_paths():
     op = tofu.conv2d_desc(2, 8, 64, 8, 8)
     y = torch.zeros(2, 64, 8, 8, dtype=torch.float32, device=DEV)
     top, bottom = dev(x[:, :, 0:4].copy()), dev(x[:, :, 4:8].copy())
-    call = lambda srcs, sp=(): tofu.shard_conv2d_fused(op, list(sp), srcs, tofu.tensor(dw), tofu.tensor(y))
+    call = lambda srcs, sp=(): tofu.shard_conv2d_fused(op, list(sp), srcs, tofu.tensor(dw), tofu.tensor(y), workspace(op, list(sp)))
     with pytest.raises(tofu.TofuError) as e:           # a missing row block is a hole, never zeros
         call([tofu.tensor(top, [0, 0, 0, 0])])
     assert e.value.status == -3

@@ -161,7 +161,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         tx, ty = tofu.tensor(dx), tofu.tensor(y, [0, co0, 0, 0])
         taps = _conv_valid_taps(0, H, 0, W, H, W)
         legs.append(Leg("conv_cout", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
-                        _call(tofu.shard_conv2d, op, sp_co, tx, tw, ty), y,
+                        _call(tofu.shard_conv2d, op, sp_co, tx, tw, ty, _ws(op, sp_co, dev)), y,
                         dict(host_common, box=reg["out_box"], keep=(dx, dw)), conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * H * W))
     if want("fetch_halo", "conv_cout_h") or extra("conv_cout_h_fused"):
         sp = sp_co + [(tofu.CONV_DIM_H, cfg["k_h"], cfg["shard_h"])]
@@ -185,7 +185,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
             if not want("fetch_halo"):
                 tofu.region_fetch(t_region, srcs)
             legs.append(Leg("conv_cout_h", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
-                            _call(tofu.shard_conv2d, op, sp, t_region, tw, ty2), y2,
+                            _call(tofu.shard_conv2d, op, sp, t_region, tw, ty2, _ws(op, sp, dev)), y2,
                             dict(host_common, box=reg2["out_box"], keep=(region, dw, own, halo)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
         if extra("conv_cout_h_fused"):
@@ -193,7 +193,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
             y3 = torch.zeros(NB, co1 - co0, h1 - h0, W, dtype=torch.float32, device=dev)
             taps = _conv_valid_taps(h0, h1, 0, W, H, W)
             legs.append(Leg("conv_cout_h_fused", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
-                            _call(tofu.shard_conv2d_fused, op, sp, srcs, tw, tofu.tensor(y3, [0, co0, h0, 0])), y3,
+                            _call(tofu.shard_conv2d_fused, op, sp, srcs, tw, tofu.tensor(y3, [0, co0, h0, 0]), _ws(op, sp, dev)), y3,
                             dict(host_common, box=reg2["out_box"], keep=(dw, own, halo)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
 
