@@ -429,13 +429,14 @@ struct ConvPlan {
   int BN, CK;
 };
 
-static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
+static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false) {
   ConvPlan pl;
   memset(&pl, 0, sizeof(pl));
   const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
   // 256 positions per workgroup (64 x 64 per wavefront) whenever its staged rows fit and the shard
   // has at least that many positions; else 128 positions, with fewer channels per step when the
   // staged rows are wide.
+  (void)multi;   // both forms use the same shapes today; the plan is asked per form so that they may differ
   if (P >= 256 && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
   else if (8 * E128 <= 10 * 256) { pl.variant = 1; pl.E = E128; pl.BN = 128; pl.CK = 8; }
   else if (4 * E128 <= 10 * 256) { pl.variant = 2; pl.E = E128; pl.BN = 128; pl.CK = 4; }
@@ -455,10 +456,15 @@ static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t
   return pl;
 }
 
-size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
-  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI);
+static size_t plan_bytes(const ConvPlan& pl) {
   if (pl.variant < 0 || pl.rest == 0) return 0;
   return (size_t)pl.groups * pl.max_segments * 64 * pl.BN * sizeof(float);
+}
+
+// enough for either entry point (one input buffer, or the region read from several blocks)
+size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
+  const size_t a = plan_bytes(conv_plan(P, BH, BW, CO, CI, false)), b = plan_bytes(conv_plan(P, BH, BW, CO, CI, true));
+  return a > b ? a : b;
 }
 
 template <int BM, int BN, int CK, int WM, int WN, int XJ>
@@ -552,10 +558,10 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   p.LDW = (int)BW + 2;
   p.w_fast = q.ws[3] == 1 && q.ws[2] == 3 && q.ws[1] == 9 && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
 
-  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI);
+  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI, q.srcs != nullptr);
   if (pl.variant < 0)
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)pl.E);
-  const size_t need = conv_workspace_bytes(P, BH, BW, CO, CI);
+  const size_t need = plan_bytes(pl);
   if (need > 0) {
     if (!q.workspace || q.workspace_bytes < need)
       return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d shard needs %zu workspace bytes, got %zu", need, q.workspace ? q.workspace_bytes : (size_t)0);
