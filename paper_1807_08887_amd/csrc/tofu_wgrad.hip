@@ -84,13 +84,17 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
   const int x_ci = tid / TPC, x_sub = tid % TPC;
 
-  int segment = 0;
-  for (int u = u_begin; u < u_end; ++segment) {
+  // Segments are numbered in unit order but processed last to first: a workgroup's run of units
+  // is shorter than one tile's images in the balanced launches, so its last segment holds the
+  // low image numbers and its first the high ones; walking them in this order makes every
+  // workgroup sweep the images upwards, and the workgroups of a moment share image planes in L2.
+  if (u_begin >= u_end) return;
+  const int first_tile = u_begin / p.NB, last_tile = (u_end - 1) / p.NB;
+  for (int segment = last_tile - first_tile; segment >= 0; --segment) {
   // ---- one segment: images [n_begin, n_end) of one tile ----
-  const int tile = u / p.NB;
-  const int n_begin = u - tile * p.NB;
-  const int n_end = min(p.NB, n_begin + (u_end - u));
-  u += n_end - n_begin;
+  const int tile = first_tile + segment;
+  const int n_begin = max(u_begin, tile * p.NB) - tile * p.NB;
+  const int n_end = min(u_end, (tile + 1) * p.NB) - tile * p.NB;
   const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
   const int m0 = tile_m * BM, c0 = tile_n * BCI;
   const int steps = (n_end - n_begin) * p.HO * p.chunks;
