@@ -102,9 +102,15 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   const int steps_all = (p.CI + CK - 1) / CK;
   // balanced: this workgroup's run of units [u, u_end) of (tile, channel step) pairs
   const int64_t n_units = (int64_t)p.n_tiles * steps_all;
-  int64_t u = BALANCED ? lid * n_units / p.groups : 0;
+  const int64_t u_begin = BALANCED ? lid * n_units / p.groups : 0;
   const int64_t u_end = BALANCED ? (lid + 1) * n_units / p.groups : 0;
-  int segment = 0;
+  if (BALANCED && u_begin >= u_end) return;
+  // Segments are numbered in unit order but processed last to first: a workgroup's run of units
+  // is at most a little longer than one tile's reduction, so its last segment covers the low
+  // channel steps and its first the high ones; in this order every workgroup sweeps the channels
+  // upwards and the workgroups of a moment read the same channels of the input (shared through L2).
+  const int first_rel = BALANCED ? (int)(u_begin / steps_all) : 0, last_rel = BALANCED ? (int)((u_end - 1) / steps_all) : 0;
+  int segment = last_rel - first_rel;
   do {
   // The per-lane staging lists below are rebuilt for every segment.  The thread index is made
   // opaque once per segment so that the parts of them that do not depend on the tile are not
@@ -116,11 +122,11 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   const int wm = wave / WN, wn = wave % WN;
   int tile, s_begin, s_end;
   if (BALANCED) {
-    const int t_rel = (int)(u / steps_all);
-    tile = __builtin_amdgcn_readfirstlane(p.tile0 + t_rel);
-    s_begin = __builtin_amdgcn_readfirstlane((int)(u - (int64_t)t_rel * steps_all));
-    s_end = __builtin_amdgcn_readfirstlane((int)min((int64_t)steps_all, s_begin + (u_end - u)));
-    u += s_end - s_begin;
+    const int t_rel = first_rel + segment;
+    const int64_t t0 = (int64_t)t_rel * steps_all;
+    tile = p.tile0 + t_rel;
+    s_begin = (int)(max(u_begin, t0) - t0);
+    s_end = (int)(min(u_end, t0 + steps_all) - t0);
   } else {
     tile = p.tile0 + lid;
     s_begin = 0;
@@ -336,7 +342,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[((i * FN + j) * 16 + v) * NT] = acc[i][j][v];
     __syncthreads();   // the next segment's prologue overwrites LDS buffer 0
-    ++segment;
+    --segment;
   } else {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -350,7 +356,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
         }
       }
   }
-  } while (BALANCED && u < u_end);
+  } while (BALANCED && segment >= 0);
 }
 
 // Sums the slots of every balanced tile in workgroup order and writes the output box.  One
