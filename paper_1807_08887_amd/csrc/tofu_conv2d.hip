@@ -645,22 +645,24 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
 }
 
 // out[(ci * CO + co) * 9 + t] = w[co, ci, 2 - t / 3, 2 - t % 3]: the filters of the data gradient
-// seen as a forward convolution of dy.  A workgroup moves a 32 x 32 block of (co, ci) pairs
+// seen as a forward convolution of dy.  A workgroup moves a block of kFlipCo x 32 (co, ci) pairs
 // through LDS so that both the reads (runs along ci, tap) and the writes (runs along co, tap)
-// are contiguous when the filters are dense.
+// are contiguous when the filters are dense; small blocks, so that a shard's filters make
+// thousands of workgroups.
+constexpr int kFlipCo = 8;
 __global__ void __launch_bounds__(256) flip_filters_kernel(float* __restrict__ out, const float* __restrict__ w, int64_t s_co,
                                                            int64_t s_ci, int64_t s_kh, int64_t s_kw, int CO, int CI) {
-  __shared__ float tile[32][32 * 9 + 1];   // [co][ci * 9 + tap]
-  const int co0 = blockIdx.x * 32, ci0 = blockIdx.y * 32;
-  for (int i = threadIdx.x; i < 32 * 288; i += 256) {
+  __shared__ float tile[kFlipCo][32 * 9 + 1];   // [co][ci * 9 + tap]
+  const int co0 = blockIdx.x * kFlipCo, ci0 = blockIdx.y * 32;
+  for (int i = threadIdx.x; i < kFlipCo * 288; i += 256) {
     const int co = i / 288, r = i - co * 288, ci = r / 9, tap = r - ci * 9;
     float v = 0.f;
     if (co0 + co < CO && ci0 + ci < CI) v = w[(co0 + co) * s_co + (ci0 + ci) * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw];
     tile[co][r] = v;
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 32 * 288; i += 256) {
-    const int ci = i / 288, r = i - ci * 288, co = r / 9, t = r - co * 9;
+  for (int i = threadIdx.x; i < 32 * kFlipCo * 9; i += 256) {
+    const int ci = i / (kFlipCo * 9), r = i - ci * (kFlipCo * 9), co = r / 9, t = r - co * 9;
     if (co0 + co < CO && ci0 + ci < CI) out[((int64_t)(ci0 + ci) * CO + co0 + co) * 9 + t] = tile[co][ci * 9 + 8 - t];
   }
 }
@@ -711,7 +713,7 @@ extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_spli
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t wst[4];
   effective_strides(w, wst);
-  hipLaunchKernelGGL(flip_filters_kernel, dim3((unsigned)((CO + 31) / 32), (unsigned)((CI + 31) / 32)), dim3(256), 0, stream,
+  hipLaunchKernelGGL(flip_filters_kernel, dim3((unsigned)((CO + kFlipCo - 1) / kFlipCo), (unsigned)((CI + 31) / 32)), dim3(256), 0, stream,
                      static_cast<float*>(workspace), element_ptr(w, wst, in_boxes[1].lo), wst[0], wst[1], wst[2], wst[3], (int)CO, (int)CI);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d data-gradient filter launch failed: %s", hipGetErrorString(e));
