@@ -255,3 +255,22 @@ def test_probe_error_paths_are_checked_on_the_host():
     assert lib.tofu_probe_copy(vp(FAKE + 4), vp(FAKE + 4096), 16, None) == -1  # misaligned
     assert lib.tofu_probe_copy(vp(FAKE), vp(FAKE + 4096), 0, None) == 0        # nothing to do, nothing launched
     assert "copy probe" in tofu.last_error() or tofu.last_error() is not None
+
+
+def test_size_limits_are_reported_not_overflowed():
+    """Extents beyond what the kernels' 32-bit indices cover return UNSUPPORTED before any launch."""
+    big = 1 << 30
+    mm = tofu.matmul_desc(big, 64, 64)
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_matmul(mm, [], _t([(0, big), (0, 64)]), _t([(0, 64), (0, 64)], FAKE + (1 << 40)), _t([(0, big), (0, 64)], FAKE + (2 << 40)), stream=0)
+    assert e.value.status == -6
+    cv = tofu.conv2d_desc(1 << 22, 4, 4, 16, 16)              # 2^30 output positions
+    x = _t([(0, 1 << 22), (0, 4), (0, 16), (0, 16)])
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_conv2d(cv, [], x, _t([(0, 4), (0, 4), (0, 3), (0, 3)], FAKE + (1 << 40)), _t([(0, 1 << 22), (0, 4), (0, 16), (0, 16)], FAKE + (2 << 40)), stream=0)
+    assert e.value.status == -6
+    with pytest.raises(tofu.TofuError) as e:                   # one row of 2^33 floats: more vectors than a launch addresses
+        tofu.region_fetch(_t([(0, 1 << 33)]), [_t([(0, 1 << 33)], FAKE + (1 << 42))], stream=0)
+    assert e.value.status == -6
+    # the integer helpers themselves work at any size
+    assert tofu.op_regions(mm, [(tofu.MM_DIM_M, 8, 7)])["out_box"][0] == (7 * big // 8, big)
