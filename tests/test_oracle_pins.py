@@ -487,3 +487,15 @@ def test_synth_is_counter_based_and_plausible():
     assert u.min() > -1 / 128 and u.max() < 1 / 128 and abs(u.var() * 3 * 128 * 128 - 1) < 0.02
     i = synth.small_int(1, 3, (10000,), -3, 3)
     assert set(np.unique(i)) == set(range(-3, 4))
+
+
+def test_synth_random_access_and_device_forms_agree():
+    """A tensor too large to draw whole on the host is drawn on the device and, for the oracle,
+    at the coordinates it needs: all three forms give the same bits."""
+    full = synth.uniform(7, 3, (37, 53), -0.25, 0.5)
+    idx = np.array([0, 1, 52, 53, 1000, 37 * 53 - 1])
+    assert np.array_equal(synth.uniform_at(7, 3, idx, -0.25, 0.5), full.ravel()[idx])
+    t = synth.uniform_torch(7, 3, torch.arange(37 * 53, dtype=torch.int64).reshape(37, 53), -0.25, 0.5)
+    assert np.array_equal(t.numpy(), full)
+    big = torch.tensor([2 ** 40 + 12345, 2 ** 33], dtype=torch.int64)
+    assert np.array_equal(synth.uniform_torch(9, 1, big, -1, 1).numpy(), synth.uniform_at(9, 1, big.numpy(), -1, 1))

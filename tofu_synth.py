@@ -61,6 +61,41 @@ def uniform(seed: int, tid: int, shape, lo: float, hi: float) -> np.ndarray:
     return _fill(shape, lambda s, c: lo + (hi - lo) * _unit(_bits(seed, tid, 0, s, c)))
 
 
+def uniform_at(seed: int, tid: int, index: np.ndarray, lo: float, hi: float) -> np.ndarray:
+    """The elements of uniform(seed, tid, ...) at the given flat (row-major) indices: the
+    generator is counter-based, so a few columns of a tensor too large to draw whole can be
+    drawn alone, bit for bit as they would appear in the whole tensor."""
+    with np.errstate(over="ignore"):
+        key = _mix(np.array([(seed * 0x100000001B3 + tid * 2) & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64))
+        bits = _mix(np.asarray(index).astype(np.uint64) ^ key[0])
+    return (lo + (hi - lo) * _unit(bits)).astype(np.float32)
+
+
+def uniform_torch(seed: int, tid: int, index, lo: float, hi: float):
+    """The same elements drawn on the device: `index` is an int64 torch tensor of flat indices
+    (any shape); returns a float32 tensor of that shape, bit-identical to uniform_at.  64-bit
+    unsigned arithmetic is emulated on int64 (wrapping multiply, masked shifts)."""
+    import torch
+
+    def s64(v):                      # the uint64 constant as the int64 with the same bits
+        v &= 0xFFFFFFFFFFFFFFFF
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    def shr(z, n):                   # logical shift right
+        return (z >> n) & ((1 << (64 - n)) - 1)
+
+    def mix(z):
+        z = z + s64(0x9E3779B97F4A7C15)
+        z = (z ^ shr(z, 30)) * s64(0xBF58476D1CE4E5B9)
+        z = (z ^ shr(z, 27)) * s64(0x94D049BB133111EB)
+        return z ^ shr(z, 31)
+    with np.errstate(over="ignore"):
+        key = int(_mix(np.array([(seed * 0x100000001B3 + tid * 2) & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64))[0])
+    bits = mix(index ^ s64(key))
+    unit = (shr(bits, 40).to(torch.float64) + 0.5) * (1.0 / 16777216.0)
+    return (lo + (hi - lo) * unit).to(torch.float32)
+
+
 def normal(seed: int, tid: int, shape, std: float = 1.0) -> np.ndarray:
     """fp32 tensor, elements N(0, std^2)."""
     def fn(s, c):
