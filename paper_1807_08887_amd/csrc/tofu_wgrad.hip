@@ -57,14 +57,22 @@ constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace
 // BALANCED: the workgroup walks a range of units and writes every segment to a workspace slot
 // (even a whole tile: one simple epilogue keeps the register count down); otherwise a workgroup
 // is one whole tile and writes dw directly.
-template <int BM, int BCI, bool FAST, bool BALANCED, int KPT = 0>
+// R, DVEC (with KPT): narrow images put R whole output rows into one step, R * CWE <= 32 positions
+// with CWE = 2 * KPT / R columns per row (the width rounded up to even; a spare column is zeros).
+// DVEC = 4: the R rows are one contiguous, 16-byte aligned run of dy (CWE == WO, dense rows);
+// DVEC = 1: dy is loaded element by element (any width, any alignment).
+template <int BM, int BCI, bool FAST, bool BALANCED, int KPT = 0, int R = 1, int DVEC = 4>
 __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(const WgradArgs p) {
   static_assert(KPT == 0 || (FAST && KPT % 2 == 0 && KPT >= 4), "a compile-time column-pair count needs the fast staging maps");
+  static_assert(R == 1 || (KPT > 0 && (2 * KPT) % R == 0 && (2 * KPT / R) % 2 == 0), "rows per step need a compile-time even row width");
   constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 2;
+  constexpr int CWE = R == 1 ? kKR : 2 * KPT / R;   // staged dy columns per row
+  constexpr int LDX = R == 1 ? kLDW : CWE + 2;      // staged x columns per row (row widened by the filter window)
+  constexpr int XROWS = R + 2;                      // staged x rows per step
   constexpr int D_ITEMS = BM * (kKR / 4), X_ITEMS = BCI * 3 * kLDW;
   constexpr int DJ = (D_ITEMS + NT - 1) / NT, XJ = (X_ITEMS + NT - 1) / NT;
   constexpr int TPC = NT / BCI;                 // threads that stage one input channel (fast path)
-  constexpr int XF = (3 * kLDW + TPC - 1) / TPC;  // elements per such thread
+  constexpr int XF = (XROWS * LDX + TPC - 1) / TPC;  // elements per such thread
   static_assert(BCI == 32 && NT % BCI == 0 && D_ITEMS % NT == 0, "staging maps assume 32 input channels and whole passes");
   static_assert(XF * TPC <= kPLX, "idle fast-path slots must land in the plane's padding");
   __shared__ float Ds[2][kKR][LDD];        // dy chunk, k-major: Ds[column][co]
@@ -97,21 +105,35 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int n_end = min(u_end, (tile + 1) * p.NB) - tile * p.NB;
   const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
   const int m0 = tile_m * BM, c0 = tile_n * BCI;
-  const int steps = (n_end - n_begin) * p.HO * p.chunks;
+  const int HG = (p.HO + R - 1) / R;             // steps per image: groups of R output rows
+  const int steps = (n_end - n_begin) * HG * p.chunks;
 
   // ---- fast-path staging maps ----
   // dy: thread -> (row = tid/8 + 32*j, columns 4*(tid%8) .. +3); x: thread -> (channel tid/TPC, elements tid%TPC + TPC*j)
-  uint32_t d_voff[DJ], x_voff[XF];
+  constexpr int DN = DVEC == 4 ? 1 : 4;          // loads per dy item
+  uint32_t d_voff[DJ][DN], x_voff[XF];
+  const int d_r = (4 * d_q) / CWE;               // staged row of this thread's four dy positions (element loads)
   if (FAST) {
 #pragma unroll
     for (int j = 0; j < DJ; ++j) {
       const int row = d_row + j * (NT / (kKR / 4));
-      d_voff[j] = (m0 + row < p.CO && 4 * d_q < p.WO) ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ds[1] + 4 * d_q) : kNoOffset;
+      if (DVEC == 4) {
+        // positions 4*d_q .. +3 of the step's run of R * CWE contiguous floats (one row when R == 1)
+        const bool ok = m0 + row < p.CO && 4 * d_q < (R == 1 ? p.WO : R * CWE);
+        d_voff[j][0] = ok ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ds[1] + 4 * d_q) : kNoOffset;
+      } else {
+#pragma unroll
+        for (int jj = 0; jj < DN; ++jj) {
+          const int c = (4 * d_q + jj) % CWE;
+          const bool ok = m0 + row < p.CO && d_r < R && c < p.WO;
+          d_voff[j][jj] = ok ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ds[1] + (int64_t)d_r * p.ds[2] + c) : kNoOffset;
+        }
+      }
     }
 #pragma unroll
     for (int j = 0; j < XF; ++j) {
-      const int e = x_sub + TPC * j, r = e / kLDW, c = e - r * kLDW, iw = c - p.plw;
-      const bool ok = e < 3 * kLDW && c0 + x_ci < p.CI && iw >= 0 && iw < p.IW;
+      const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX, iw = c - p.plw;
+      const bool ok = e < XROWS * LDX && c0 + x_ci < p.CI && iw >= 0 && iw < p.IW;
       // row offset r*xs2 is relative to input row (oh - plh); the buffer base is moved back by plh rows
       x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)iw * p.xs[3]) : kNoOffset;
     }
@@ -119,20 +141,31 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 
   v4f32 rd[DJ];
   float rx[FAST ? XF : XJ];
+  // fast-path loads of one staging item for the step whose first output row is oh
+  auto load_d = [&](int j, uint32_t d_soff, int oh) {
+    if (DVEC == 4) {
+      rd[j] = buf_load4(d_rsrc, d_voff[j][0], d_soff);
+    } else {
+      const bool row_ok = oh + d_r < p.HO;       // the last group of rows of an image may be short
+#pragma unroll
+      for (int jj = 0; jj < DN; ++jj) rd[j][jj] = buf_load(d_rsrc, row_ok ? d_voff[j][jj] : kNoOffset, d_soff);
+    }
+  };
+  auto load_x = [&](int j, uint32_t x_soff, int oh) {
+    const int e = x_sub + TPC * j, r = e / LDX;   // staged row of this element
+    const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
+    rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
+  };
   auto load_global = [&](int step) {
     const int row_id = step / p.chunks, chunk = step - row_id * p.chunks;
-    const int n = n_begin + row_id / p.HO, oh = row_id - (row_id / p.HO) * p.HO;
+    const int n = n_begin + row_id / HG, oh = (row_id - (row_id / HG) * HG) * R;   // first output row of the step
     if (FAST) {
       const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
       const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
 #pragma unroll
-      for (int j = 0; j < DJ; ++j) rd[j] = buf_load4(d_rsrc, d_voff[j], d_soff);
+      for (int j = 0; j < DJ; ++j) load_d(j, d_soff, oh);
 #pragma unroll
-      for (int j = 0; j < XF; ++j) {
-        const int e = x_sub + TPC * j, r = (e >= kLDW) + (e >= 2 * kLDW);   // staged row of this element
-        const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
-        rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
-      }
+      for (int j = 0; j < XF; ++j) load_x(j, x_soff, oh);
       return;
     }
     const int cw0 = chunk * p.CW;
@@ -199,7 +232,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     for (int t = 0; t < steps; ++t) {
       const int buf = t & 1;
       const int nxt = min(t + 2, steps - 1);
-      const int n = n_begin + nxt / p.HO, oh = nxt - (nxt / p.HO) * p.HO;
+      const int n = n_begin + nxt / HG, oh = (nxt - (nxt / HG) * HG) * R;
       const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
       const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
       const float* dsm = &Ds[buf][half][wave * 32 + l32];
@@ -207,7 +240,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
       auto fetch = [&](int kp, float& a, float (&b)[9]) {
         a = dsm[2 * kp * LDD];
 #pragma unroll
-        for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[2 * kp + (tap / 3) * kLDW + tap % 3];
+        for (int tap = 0; tap < 9; ++tap) b[tap] = xsm[((2 * kp) / CWE) * LDX + (2 * kp) % CWE + (tap / 3) * LDX + tap % 3];
       };
       auto fma9 = [&](float a, const float (&b)[9]) {
 #pragma unroll
@@ -220,13 +253,11 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
             const int row = d_row + item * (NT / (kKR / 4));
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) Ds[buf ^ 1][4 * d_q + jj][row] = rd[item][jj];
-            rd[item] = buf_load4(d_rsrc, d_voff[item], d_soff);
+            load_d(item, d_soff, oh);
           } else {
             const int j = item - DJ;
             Xs[buf ^ 1][x_ci * kPLX + x_sub + TPC * j] = rx[j];
-            const int e = x_sub + TPC * j, r = (e >= kLDW) + (e >= 2 * kLDW);
-            const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
-            rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
+            load_x(j, x_soff, oh);
           }
         }
       };
@@ -419,7 +450,15 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
     x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
     d_span += (in_boxes[1].hi[d] - in_boxes[1].lo[d] - 1) * ds[d];
   }
-  const bool fast = nonneg && p.vec && p.chunks == 1 && WO % 4 == 0 && x_span + p.plh * xs[2] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
+  const bool fits = nonneg && x_span + p.plh * xs[2] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
+  // one output row per step, rows of whole aligned vectors
+  const bool fast_row = fits && p.vec && p.chunks == 1 && WO % 4 == 0;
+  // narrow images: several whole rows per step.  14 wide: two dense rows are one aligned run of 28 floats;
+  // 7 wide: four rows, element loads (rows padded to 8 positions in LDS)
+  const bool fast_2x14 = fits && WO == 14 && HO % 2 == 0 && ds[3] == 1 && ds[2] == 14 && ds[1] % 4 == 0 && ds[0] % 4 == 0 &&
+                         (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
+  const bool fast_4x7 = fits && WO == 7 && ds[3] == 1;
+  const bool fast = fast_row || fast_2x14 || fast_4x7;
   p.x_bytes = fast ? (uint32_t)(4 * x_span) : 0;
   p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
   int groups, max_segments;
@@ -435,17 +474,21 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   const int kpe = ((p.CW + 1) / 2 + 1) & ~1;
   void (*kern)(const WgradArgs);
   if (need > 0) {
-    kern = !fast       ? wgrad_kernel<gBM, gBCI, false, true>
-           : kpe == 8  ? wgrad_kernel<gBM, gBCI, true, true, 8>
-           : kpe == 14 ? wgrad_kernel<gBM, gBCI, true, true, 14>
-           : kpe == 16 ? wgrad_kernel<gBM, gBCI, true, true, 16>
-                       : wgrad_kernel<gBM, gBCI, true, true>;
+    kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, true>
+           : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, true, 14, 2, 4>
+           : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, true, 16, 4, 1>
+           : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, true, 8>
+           : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, true, 14>
+           : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, true, 16>
+                                 : wgrad_kernel<gBM, gBCI, true, true>;
   } else {
-    kern = !fast       ? wgrad_kernel<gBM, gBCI, false, false>
-           : kpe == 8  ? wgrad_kernel<gBM, gBCI, true, false, 8>
-           : kpe == 14 ? wgrad_kernel<gBM, gBCI, true, false, 14>
-           : kpe == 16 ? wgrad_kernel<gBM, gBCI, true, false, 16>
-                       : wgrad_kernel<gBM, gBCI, true, false>;
+    kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, false>
+           : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, false, 14, 2, 4>
+           : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, false, 16, 4, 1>
+           : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, false, 8>
+           : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, false, 14>
+           : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, false, 16>
+                                 : wgrad_kernel<gBM, gBCI, true, false>;
   }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);

@@ -467,7 +467,12 @@ def run_wgrad(opd, splits, dx, ddy):
                                                       # widths 16 / 32 / 28 take the unrolled steps, 24 the looped fast one;
                                                       # H = 1 gives workgroups a single step
                                                       (2, 32, 128, 16, 16, 1), (3, 33, 40, 6, 32, 1), (2, 20, 30, 5, 24, 1),
-                                                      (1, 8, 8, 1, 16, 1), (5, 64, 256, 2, 28, 1)])
+                                                      (1, 8, 8, 1, 16, 1), (5, 64, 256, 2, 28, 1),
+                                                      # 14 wide: two rows per step (even heights); 7 wide: four rows per step,
+                                                      # heights that leave a short last group; odd height 14 wide takes the guarded path
+                                                      (3, 40, 130, 14, 14, 1), (2, 33, 64, 6, 14, 1), (4, 64, 140, 7, 7, 1),
+                                                      (2, 20, 30, 5, 7, 1), (3, 32, 128, 1, 7, 1), (2, 16, 32, 9, 14, 1),
+                                                      (2, 24, 40, 9, 9, 0), (3, 16, 32, 16, 16, 0)])
 def test_wgrad_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
     opd = dict(kind="conv2d_wgrad", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=pad)
     ho, wo = H + 2 * pad - 2, W + 2 * pad - 2
@@ -476,6 +481,19 @@ def test_wgrad_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
     got = run_wgrad(opd, [], dev(x), dev(dy)).cpu().numpy()
     val, absum = oracle.wgrad_box(x, dy, 3, 3, pad=pad)
     assert_close(got, val, absum, f"wgrad {opd}")
+
+
+@pytest.mark.parametrize("H,W", [(14, 14), (7, 7)])
+def test_wgrad_narrow_images_pnr_invariant_bit_exact(H, W):
+    """Several output rows per step: every split dimension, small integers, bit-exact."""
+    opd = dict(kind="conv2d_wgrad", batch=6, c_in=40, c_out=136, H=H, W=W, KH=3, KW=3, stride=1, pad=1)
+    x = synth.small_int(54, 0, (6, 40, H, W), -3, 3)
+    dy = synth.small_int(54, 1, (6, 136, H, W), -3, 3)
+    dx, ddy = dev(x), dev(dy)
+    want = oracle.wgrad_box(x, dy, 3, 3, pad=1)[0]
+    for dim, k in itertools.product(["CO", "CI", "N"], [2, 3]):
+        got = assemble(opd, dim, k, lambda sp: run_wgrad(opd, sp, dx, ddy))
+        assert np.array_equal(got.astype(np.float64), want), (dim, k)
 
 
 @pytest.mark.parametrize("k", [2, 3, 4])
