@@ -50,10 +50,12 @@ constexpr int kLDW = kKR + 2;        // staged x columns per row: chunk widened 
 constexpr int kPLX = 3 * kLDW + 3;
 constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace: [tap][128 co][32 ci]   // staged floats per input channel; odd -> 32 channels hit 32 banks
 
-// FAST: one chunk per output row, dy rows are whole aligned vectors, every operand offset fits
-// 32 bits.  Then each lane's staging addresses are fixed byte offsets, a step only changes a
-// scalar offset, and all padding comes from out-of-range buffer reads -- no branches, no
-// per-step index arithmetic.  Otherwise a generic guarded path is used.
+// FAST: dy rows are whole aligned vectors (or one of the narrow-image forms below applies) and
+// every operand offset fits 32 bits.  Then each lane's staging addresses are fixed byte offsets,
+// a step only changes a scalar offset, and all padding comes from out-of-range buffer reads
+// selected by one comparison per item -- no branches, no per-step index arithmetic.  Rows wider
+// than 32 columns are cut into equal chunks, one chunk per step.  Otherwise a generic guarded
+// path is used.
 // BALANCED: the workgroup walks a range of units and writes every segment to a workspace slot
 // (even a whole tile: one simple epilogue keeps the register count down); otherwise a workgroup
 // is one whole tile and writes dw directly.
@@ -88,7 +90,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int u_begin = (int)(g * n_units / p.groups), u_end = (int)((g + 1) * n_units / p.groups);
   const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
   const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
-  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x - (int64_t)p.plh * p.xs[2], p.x_bytes + 4u * (uint32_t)(p.plh * p.xs[2]));
+  // the x buffer starts plh rows and plw columns before the box, so that staged element (r, c) of a
+  // step has the non-negative offset r * xs2 + c * xs3; the border itself is never read (predicated)
+  const int64_t x_back = (int64_t)p.plh * p.xs[2] + (int64_t)p.plw * p.xs[3];
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.x - x_back, p.x_bytes + 4u * (uint32_t)x_back);
   const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
   const int x_ci = tid / TPC, x_sub = tid % TPC;
 
@@ -119,7 +124,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
       const int row = d_row + j * (NT / (kKR / 4));
       if (DVEC == 4) {
         // positions 4*d_q .. +3 of the step's run of R * CWE contiguous floats (one row when R == 1)
-        const bool ok = m0 + row < p.CO && 4 * d_q < (R == 1 ? p.WO : R * CWE);
+        const bool ok = m0 + row < p.CO && 4 * d_q < (R == 1 ? p.CW : R * CWE);
         d_voff[j][0] = ok ? 4u * (uint32_t)((int64_t)(m0 + row) * p.ds[1] + 4 * d_q) : kNoOffset;
       } else {
 #pragma unroll
@@ -132,40 +137,42 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     }
 #pragma unroll
     for (int j = 0; j < XF; ++j) {
-      const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX, iw = c - p.plw;
-      const bool ok = e < XROWS * LDX && c0 + x_ci < p.CI && iw >= 0 && iw < p.IW;
-      // row offset r*xs2 is relative to input row (oh - plh); the buffer base is moved back by plh rows
-      x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)iw * p.xs[3]) : kNoOffset;
+      const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX;
+      const bool ok = e < XROWS * LDX && c0 + x_ci < p.CI;
+      // offsets are relative to input row (oh - plh) and input column (chunk start - plw)
+      x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)c * p.xs[3]) : kNoOffset;
     }
   }
 
   v4f32 rd[DJ];
   float rx[FAST ? XF : XJ];
   // fast-path loads of one staging item for the step whose first output row is oh
-  auto load_d = [&](int j, uint32_t d_soff, int oh) {
+  auto load_d = [&](int j, uint32_t d_soff, int oh, int cw0) {
     if (DVEC == 4) {
-      rd[j] = buf_load4(d_rsrc, d_voff[j][0], d_soff);
+      const bool col_ok = R > 1 || cw0 + 4 * d_q < p.WO;   // the last chunk of a row may be short (whole vectors)
+      rd[j] = buf_load4(d_rsrc, col_ok ? d_voff[j][0] : kNoOffset, d_soff);
     } else {
       const bool row_ok = oh + d_r < p.HO;       // the last group of rows of an image may be short
 #pragma unroll
       for (int jj = 0; jj < DN; ++jj) rd[j][jj] = buf_load(d_rsrc, row_ok ? d_voff[j][jj] : kNoOffset, d_soff);
     }
   };
-  auto load_x = [&](int j, uint32_t x_soff, int oh) {
-    const int e = x_sub + TPC * j, r = e / LDX;   // staged row of this element
-    const bool row_ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
-    rx[j] = buf_load(x_rsrc, row_ok ? x_voff[j] : kNoOffset, x_soff);
+  auto load_x = [&](int j, uint32_t x_soff, int oh, int cw0) {
+    const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX;   // staged row and column of this element
+    const bool ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH && (unsigned)(cw0 + c - p.plw) < (unsigned)p.IW;
+    rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNoOffset, x_soff);
   };
   auto load_global = [&](int step) {
     const int row_id = step / p.chunks, chunk = step - row_id * p.chunks;
     const int n = n_begin + row_id / HG, oh = (row_id - (row_id / HG) * HG) * R;   // first output row of the step
     if (FAST) {
-      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
-      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
+      const int cw0 = chunk * p.CW;
+      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2] + cw0);
+      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2] + (int64_t)cw0 * p.xs[3]);
 #pragma unroll
-      for (int j = 0; j < DJ; ++j) load_d(j, d_soff, oh);
+      for (int j = 0; j < DJ; ++j) load_d(j, d_soff, oh, cw0);
 #pragma unroll
-      for (int j = 0; j < XF; ++j) load_x(j, x_soff, oh);
+      for (int j = 0; j < XF; ++j) load_x(j, x_soff, oh, cw0);
       return;
     }
     const int cw0 = chunk * p.CW;
@@ -232,9 +239,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     for (int t = 0; t < steps; ++t) {
       const int buf = t & 1;
       const int nxt = min(t + 2, steps - 1);
-      const int n = n_begin + nxt / HG, oh = (nxt - (nxt / HG) * HG) * R;
-      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2]);
-      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2]);
+      const int row_id = nxt / p.chunks, cw0 = (nxt - row_id * p.chunks) * p.CW;
+      const int n = n_begin + row_id / HG, oh = (row_id - (row_id / HG) * HG) * R;
+      const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2] + cw0);
+      const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2] + (int64_t)cw0 * p.xs[3]);
       const float* dsm = &Ds[buf][half][wave * 32 + l32];
       const float* xsm = &Xs[buf][l32 * kPLX + half];
       auto fetch = [&](int kp, float& a, float (&b)[9]) {
@@ -253,11 +261,11 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
             const int row = d_row + item * (NT / (kKR / 4));
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) Ds[buf ^ 1][4 * d_q + jj][row] = rd[item][jj];
-            load_d(item, d_soff, oh);
+            load_d(item, d_soff, oh, cw0);
           } else {
             const int j = item - DJ;
             Xs[buf ^ 1][x_ci * kPLX + x_sub + TPC * j] = rx[j];
-            load_x(j, x_soff, oh);
+            load_x(j, x_soff, oh, cw0);
           }
         }
       };
@@ -450,15 +458,16 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
     x_span += (in_boxes[0].hi[d] - in_boxes[0].lo[d] - 1) * xs[d];
     d_span += (in_boxes[1].hi[d] - in_boxes[1].lo[d] - 1) * ds[d];
   }
-  const bool fits = nonneg && x_span + p.plh * xs[2] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
-  // one output row per step, rows of whole aligned vectors
-  const bool fast_row = fits && p.vec && p.chunks == 1 && WO % 4 == 0;
-  // narrow images: several whole rows per step.  14 wide: two dense rows are one aligned run of 28 floats;
-  // 7 wide: four rows, element loads (rows padded to 8 positions in LDS)
-  const bool fast_2x14 = fits && WO == 14 && HO % 2 == 0 && ds[3] == 1 && ds[2] == 14 && ds[1] % 4 == 0 && ds[0] % 4 == 0 &&
-                         (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
+  const bool fits = nonneg && x_span + p.plh * xs[2] + p.plw * xs[3] < ((int64_t)1 << 29) && d_span < ((int64_t)1 << 29);
+  // one output row (or one chunk of at most 32 columns of it) per step, rows of whole aligned vectors
+  const bool fast_row = fits && p.vec && WO % 4 == 0;
+  // narrow images: several whole rows per step.  14 or 16 wide: two dense rows are one aligned run of
+  // 28 or 32 floats; 7 wide: four rows, element loads (rows padded to 8 positions in LDS)
+  const bool two_rows = fits && HO % 2 == 0 && ds[3] == 1 && ds[2] == WO && ds[1] % 4 == 0 && ds[0] % 4 == 0 &&
+                        (reinterpret_cast<uintptr_t>(p.dy) & 15) == 0;
+  const bool fast_2x14 = two_rows && WO == 14, fast_2x16 = two_rows && WO == 16;
   const bool fast_4x7 = fits && WO == 7 && ds[3] == 1;
-  const bool fast = fast_row || fast_2x14 || fast_4x7;
+  const bool fast = fast_row || fast_2x14 || fast_2x16 || fast_4x7;
   p.x_bytes = fast ? (uint32_t)(4 * x_span) : 0;
   p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
   int groups, max_segments;
@@ -476,6 +485,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   if (need > 0) {
     kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, true>
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, true, 14, 2, 4>
+           : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, true, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, true, 16, 4, 1>
            : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, true, 8>
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, true, 14>
@@ -484,6 +494,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   } else {
     kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, false>
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, false, 14, 2, 4>
+           : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, false, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, false, 16, 4, 1>
            : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, false, 8>
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, false, 14>

@@ -472,7 +472,11 @@ def run_wgrad(opd, splits, dx, ddy):
                                                       # heights that leave a short last group; odd height 14 wide takes the guarded path
                                                       (3, 40, 130, 14, 14, 1), (2, 33, 64, 6, 14, 1), (4, 64, 140, 7, 7, 1),
                                                       (2, 20, 30, 5, 7, 1), (3, 32, 128, 1, 7, 1), (2, 16, 32, 9, 14, 1),
-                                                      (2, 24, 40, 9, 9, 0), (3, 16, 32, 16, 16, 0)])
+                                                      (2, 24, 40, 9, 9, 0), (3, 16, 32, 16, 16, 0),
+                                                      # rows wider than 32 columns are cut into chunks: 56 = 2 x 28, 40 = 2 x 20,
+                                                      # 36 = 20 + 16 (a short last chunk), 100 = 4 x 28 with a short last chunk
+                                                      (2, 16, 40, 5, 56, 1), (1, 8, 32, 3, 40, 1), (2, 9, 20, 4, 36, 1), (1, 5, 16, 2, 100, 1),
+                                                      (2, 8, 16, 6, 58, 0)])
 def test_wgrad_shapes_unpartitioned(batch, c_in, c_out, H, W, pad):
     opd = dict(kind="conv2d_wgrad", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=pad)
     ho, wo = H + 2 * pad - 2, W + 2 * pad - 2
