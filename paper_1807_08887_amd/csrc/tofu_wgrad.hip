@@ -63,8 +63,11 @@ constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace
 // with CWE = 2 * KPT / R columns per row (the width rounded up to even; a spare column is zeros).
 // DVEC = 4: the R rows are one contiguous, 16-byte aligned run of dy (CWE == WO, dense rows);
 // DVEC = 1: dy is loaded element by element (any width, any alignment).
-template <int BM, int BCI, bool FAST, bool BALANCED, int KPT = 0, int R = 1, int DVEC = 4>
+// CHUNKED: output rows are wider than 32 columns and a step is one chunk of a row; which staged
+// columns lie outside the image then depends on the step (else it is folded into the offsets).
+template <int BM, int BCI, bool FAST, bool BALANCED, int KPT = 0, int R = 1, int DVEC = 4, bool CHUNKED = false>
 __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(const WgradArgs p) {
+  static_assert(!CHUNKED || (FAST && R == 1), "chunks are cut from single rows");
   static_assert(KPT == 0 || (FAST && KPT % 2 == 0 && KPT >= 4), "a compile-time column-pair count needs the fast staging maps");
   static_assert(R == 1 || (KPT > 0 && (2 * KPT) % R == 0 && (2 * KPT / R) % 2 == 0), "rows per step need a compile-time even row width");
   constexpr int NW = BM / 32, NT = 64 * NW, LDD = BM + 2;
@@ -138,7 +141,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 #pragma unroll
     for (int j = 0; j < XF; ++j) {
       const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX;
-      const bool ok = e < XROWS * LDX && c0 + x_ci < p.CI;
+      const bool ok = e < XROWS * LDX && c0 + x_ci < p.CI && (CHUNKED || (unsigned)(c - p.plw) < (unsigned)p.IW);
       // offsets are relative to input row (oh - plh) and input column (chunk start - plw)
       x_voff[j] = ok ? 4u * (uint32_t)((int64_t)(c0 + x_ci) * p.xs[1] + (int64_t)r * p.xs[2] + (int64_t)c * p.xs[3]) : kNoOffset;
     }
@@ -149,7 +152,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   // fast-path loads of one staging item for the step whose first output row is oh
   auto load_d = [&](int j, uint32_t d_soff, int oh, int cw0) {
     if (DVEC == 4) {
-      const bool col_ok = R > 1 || cw0 + 4 * d_q < p.WO;   // the last chunk of a row may be short (whole vectors)
+      const bool col_ok = !CHUNKED || cw0 + 4 * d_q < p.WO;   // the last chunk of a row may be short (whole vectors)
       rd[j] = buf_load4(d_rsrc, col_ok ? d_voff[j][0] : kNoOffset, d_soff);
     } else {
       const bool row_ok = oh + d_r < p.HO;       // the last group of rows of an image may be short
@@ -158,8 +161,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     }
   };
   auto load_x = [&](int j, uint32_t x_soff, int oh, int cw0) {
-    const int e = x_sub + TPC * j, r = e / LDX, c = e - r * LDX;   // staged row and column of this element
-    const bool ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH && (unsigned)(cw0 + c - p.plw) < (unsigned)p.IW;
+    const int e = x_sub + TPC * j;
+    const int r = R == 1 ? (e >= LDX) + (e >= 2 * LDX) : e / LDX;   // staged row of this element
+    bool ok = (unsigned)(oh + r - p.plh) < (unsigned)p.IH;
+    if (CHUNKED) ok = ok && (unsigned)(cw0 + e - r * LDX - p.plw) < (unsigned)p.IW;
     rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNoOffset, x_soff);
   };
   auto load_global = [&](int step) {
@@ -487,6 +492,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, true, 14, 2, 4>
            : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, true, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, true, 16, 4, 1>
+           : p.chunks > 1        ? (kpe == 14 ? wgrad_kernel<gBM, gBCI, true, true, 14, 1, 4, true> : wgrad_kernel<gBM, gBCI, true, true, 0, 1, 4, true>)
            : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, true, 8>
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, true, 14>
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, true, 16>
@@ -496,6 +502,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, false, 14, 2, 4>
            : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, false, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, false, 16, 4, 1>
+           : p.chunks > 1        ? (kpe == 14 ? wgrad_kernel<gBM, gBCI, true, false, 14, 1, 4, true> : wgrad_kernel<gBM, gBCI, true, false, 0, 1, 4, true>)
            : kpe == 8            ? wgrad_kernel<gBM, gBCI, true, false, 8>
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, false, 14>
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, false, 16>
