@@ -131,7 +131,14 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
                     int64_t* pad_lo, int64_t* pad_hi, int32_t* is_partial);
 
 /* Bytes of device workspace the shard call for (op, splits) may use; the
- * caller passes a buffer at least this large (0 means none is needed). */
+ * caller passes a 16-byte aligned DEVICE buffer at least this large (0 means
+ * none is needed; a smaller buffer -> WORKSPACE_TOO_SMALL).  The kernels cut
+ * their own reductions to fill the GPU -- K slices of a tall-skinny matmul,
+ * (tile, channel step) or (tile, image) segments of the convolutions -- and the
+ * workspace holds those partial tiles until a second kernel sums them in a
+ * fixed order; the data gradient also keeps its reversed filters there.  The
+ * content is scratch: nothing is carried from one call to the next, and calls
+ * that run concurrently need separate workspaces. */
 size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits);
 
 /* Thread-local text for the last non-zero status returned on this thread. */

@@ -17,6 +17,12 @@
 //     the virtual rows [T_a, T_b] its positions need.
 //   * One MFMA contracts the same tap of two adjacent input channels (lanes 0-31: ci, lanes
 //     32-63: ci+1); the B operand of a lane is one LDS read at (its position's row/col) + tap.
+//   * Launch: full waves of 512 tiles run one workgroup per tile.  The tiles of the last, partial
+//     wave are cut into (tile, channel step) units dealt evenly to 512 workgroups -- the same
+//     even split as a shard range -- whose runs inside one tile (segments) go to workspace slots;
+//     a second kernel sums each tile's slots in workgroup order (fixed, no atomics).
+// The same kernel serves the variant that reads its input region from several blocks (the fetch
+// fused into the consumer, Sec. 6) and, on reversed filters, the data gradient.
 #include <hip/hip_runtime.h>
 
 #include <string.h>

@@ -7,17 +7,20 @@
 // Kernel: GEMM  [co] x [(ci,tap)] over K = (n,h,w) on fp32 MFMA 32x32x2 tiles.
 //   * A workgroup owns BM output channels x 32 input channels x all 9 taps; wavefront w owns 32 of
 //     the output channels and nine 32x32 accumulator blocks, one per tap (lane = input channel).
-//   * One step of the K loop is one output row (n,h): dy[n, co tile, h, :] is staged k-major
-//     (Ds[w][co]) and x[n, ci tile, h-pad .. h-pad+2, :] is staged with its zero border, so the
-//     nine taps are nine shifted reads of the same three staged rows.  One MFMA contracts two
+//   * One step of the K loop is up to 32 output positions of one image: one output row (or a
+//     chunk of at most 32 columns of a wider row), or several whole rows of a narrow image.
+//     dy[n, co tile, those positions] is staged k-major (Ds[position][co]) and the x rows they
+//     touch, x[n, ci tile, h-pad .. h+R-1-pad+2, :], are staged with their zero border, so the
+//     nine taps are nine shifted reads of the same staged rows.  One MFMA contracts two
 //     adjacent output columns (lanes 0-31: w, lanes 32-63: w+1).
 //   * Load balance: the work is T tiles x NB images ("units", tile-major).  400 tiles cannot fill
 //     512 workgroup slots evenly, so workgroup g takes the units [g*N/G, (g+1)*N/G) -- the same
-//     even split as a shard range.  A run of units inside one tile is a segment; a segment that
-//     is a whole tile is written straight to dw, any other goes tap-major to a workspace slot
-//     and a second kernel sums each tile's segments in workgroup order (fixed, no atomics) and
-//     restores the [co][ci][kh][kw] layout.  Each workgroup writes at most a few slots, so the
-//     workspace is about 2.5x the output instead of one full copy per image.
+//     even split as a shard range.  A run of units inside one tile is a segment; every segment
+//     goes tap-major to a workspace slot and a second kernel sums each tile's segments in
+//     workgroup order (fixed, no atomics) and restores the [co][ci][kh][kw] layout.  Each
+//     workgroup writes at most a few slots, so the workspace is about 2.5x the output instead
+//     of one full copy per image.  Shards with very many tiles, tiles that divide 512, or a
+//     single image run one workgroup per tile and write dw directly.
 #include <hip/hip_runtime.h>
 
 #include "tofu_internal.h"
