@@ -414,7 +414,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_multi_kernel(const Con
   conv2d_body<BM, BN, CK, WM, WN, XJ, true, BALANCED>(p, &srcs);
 }
 
-constexpr size_t kLdsLimit = 160 * 1024;
+constexpr size_t kLdsLimit = 64 * 1024;   // dynamic LDS a launch may ask for without raising the kernel's limit; the plans stay below it
 
 // Most floats per channel any tile of BN consecutive positions stages (rows touched + halo rows).
 static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN) {
@@ -488,18 +488,6 @@ static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, 
   p.PL = (p.E + 63) / 64 * 64 + 32;
   const size_t lds_bytes = sizeof(float) * Cfg::lds_floats(p.PL);
   if (lds_bytes > kLdsLimit) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: staging needs %zu bytes of LDS", lds_bytes);
-  const void* fns[4] = {reinterpret_cast<const void*>(conv2d_kernel<BM, BN, CK, WM, WN, XJ, false>),
-                        reinterpret_cast<const void*>(conv2d_kernel<BM, BN, CK, WM, WN, XJ, true>),
-                        reinterpret_cast<const void*>(conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>),
-                        reinterpret_cast<const void*>(conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>)};
-  static bool attr_set = false;
-  if (!attr_set) {
-    for (const void* fn : fns) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-      if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d: cannot raise the LDS limit: %s", hipGetErrorString(e));
-    }
-    attr_set = true;
-  }
   auto launch = [&](bool balanced, int wgs) {
     const dim3 grid((wgs + 7) / 8 * 8), block(Cfg::kThreads);
     if (srcs) {
