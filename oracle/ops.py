@@ -204,3 +204,14 @@ def reduce_op(partials, reducer="sum"):
     v, s, pv, ps = _out(arrs[0].size)
     _load().oracle_reduce_op(ptrs, _i64(len(arrs)), _i64(arrs[0].size), _i64(REDUCERS[reducer]), pv, ps)
     return v.reshape(shape), s.reshape(shape)
+
+
+def lstm_cell(gates, c_prev):
+    """gates [..., 4] (input, forget, cell, output pre-activations), c_prev [...] ->
+    (c_new, h_new, scale_c) float64 arrays of c_prev's shape."""
+    g, pg = _f32(gates); c, pc = _f32(c_prev)
+    assert g.shape == c.shape + (4,)
+    n = c.size
+    cn, hn, sc = (np.empty(n, dtype=np.float64) for _ in range(3))
+    _load().oracle_lstm_cell(pg, pc, _i64(n), cn.ctypes.data_as(_dp), hn.ctypes.data_as(_dp), sc.ctypes.data_as(_dp))
+    return cn.reshape(c.shape), hn.reshape(c.shape), sc.reshape(c.shape)

@@ -31,6 +31,7 @@ ITER_DIMS = {
     "conv2d": (("N", "CO", "H", "W"), ("CI",)),
     "conv2d_wgrad": (("CO", "CI"), ("N",)),
     "conv2d_dgrad": (("N", "CI", "H", "W"), ("CO",)),     # H, W: rows / columns of the forward INPUT
+    "lstm_cell": (("B", "H"), ()),                          # element-wise over (batch, hidden unit)
 }
 
 
@@ -49,12 +50,16 @@ def iteration_extents(op: dict) -> dict:
     kind = op["kind"]
     if kind == "matmul":
         return {"M": op["M"], "N": op["N"], "K": op["K"]}
+    if kind == "lstm_cell":
+        return {"B": op["batch"], "H": op["hidden"]}
     ho = conv_out_size(op["H"], op["KH"], op["stride"], op["pad"])
     wo = conv_out_size(op["W"], op["KW"], op["stride"], op["pad"])
     if kind == "conv2d":
         return {"N": op["batch"], "CO": op["c_out"], "H": ho, "W": wo, "CI": op["c_in"]}
     if kind == "conv2d_wgrad":
         return {"CO": op["c_out"], "CI": op["c_in"], "N": op["batch"]}
+    if kind == "lstm_cell":
+        return {"B": op["batch"], "H": op["hidden"]}
     if kind == "conv2d_dgrad":
         return {"N": op["batch"], "CI": op["c_in"], "H": op["H"], "W": op["W"], "CO": op["c_out"]}
     raise ValueError(kind)
@@ -117,6 +122,9 @@ def op_regions(op: dict, splits):
         out_box = [r["CO"], r["CI"], (0, op["KH"]), (0, op["KW"])]
         in_boxes = [[r["N"], r["CI"], hbox, wbox],
                     [r["N"], r["CO"], (0, ho), (0, wo)]]
+    elif kind == "lstm_cell":     # element-wise: every input is read exactly where the output is written
+        out_box = [r["B"], r["H"]]
+        in_boxes = [[r["B"], r["H"], (0, 4)], [r["B"], r["H"]]]
     elif kind == "conv2d_dgrad":
         ho = conv_out_size(op["H"], op["KH"], op["stride"], op["pad"])
         wo = conv_out_size(op["W"], op["KW"], op["stride"], op["pad"])

@@ -252,6 +252,25 @@ void oracle_reduce_op(const float* const* partials, i64 k, i64 count, i64 op, do
   }
 }
 
+/* ---- LSTM cell update after the gate GEMM --------------------------------------
+ * The element-wise stage that consumes the gate pre-activations (Sec. 5.1: consecutive
+ * element-wise operators are merged and share their producer's partition).  gates[b][h][4] holds
+ * the pre-activations of the input, forget, cell and output gates of hidden unit h:
+ *   c_new = sigmoid(f) * c_prev + sigmoid(i) * tanh(g),   h_new = sigmoid(o) * tanh(c_new).
+ * scale_c = |sigmoid(f) * c_prev| + |sigmoid(i) * tanh(g)| and scale_h = 1 are the magnitudes
+ * the tolerance is measured against. */
+void oracle_lstm_cell(const float* gates, const float* c_prev, i64 count, double* c_new, double* h_new, double* scale_c) {
+#pragma omp parallel for schedule(static)
+  for (i64 e = 0; e < count; ++e) {
+    double gi = gates[4 * e], gf = gates[4 * e + 1], gg = gates[4 * e + 2], go = gates[4 * e + 3];
+    double si = 1.0 / (1.0 + exp(-gi)), sf = 1.0 / (1.0 + exp(-gf)), so = 1.0 / (1.0 + exp(-go));
+    double a = sf * (double)c_prev[e], b = si * tanh(gg);
+    c_new[e] = a + b;
+    h_new[e] = so * tanh(a + b);
+    scale_c[e] = fabs(a) + fabs(b);
+  }
+}
+
 /* Number of OpenMP threads the loops above will use (reported by the bench). */
 #ifdef _OPENMP
 #include <omp.h>

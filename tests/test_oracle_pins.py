@@ -499,3 +499,40 @@ def test_synth_random_access_and_device_forms_agree():
     assert np.array_equal(t.numpy(), full)
     big = torch.tensor([2 ** 40 + 12345, 2 ** 33], dtype=torch.int64)
     assert np.array_equal(synth.uniform_torch(9, 1, big, -1, 1).numpy(), synth.uniform_at(9, 1, big.numpy(), -1, 1))
+
+
+def test_lstm_cell_against_torch_fp64_and_closed_forms():
+    """The element-wise stage after the gate GEMM, against torch's fp64 formulas and at points
+    where the result is known in closed form."""
+    g = synth.normal(14, 0, (5, 9, 4), 2.0)
+    c = synth.normal(14, 1, (5, 9), 1.0)
+    cn, hn, sc = oracle.lstm_cell(g, c)
+    tg, tc = torch.from_numpy(g).double(), torch.from_numpy(c).double()
+    i, f, gg, o = (tg[..., k] for k in range(4))
+    want_c = torch.sigmoid(f) * tc + torch.sigmoid(i) * torch.tanh(gg)
+    want_h = torch.sigmoid(o) * torch.tanh(want_c)
+    assert np.allclose(cn, want_c.numpy(), rtol=0, atol=1e-14) and np.allclose(hn, want_h.numpy(), rtol=0, atol=1e-14)
+    assert (sc >= np.abs(cn) - 1e-14).all()
+    # all pre-activations zero: every sigmoid is 1/2 and tanh(0) = 0
+    z = np.zeros((3, 4), np.float32)
+    cz, hz, _ = oracle.lstm_cell(z, np.array([2.0, -4.0, 0.0], np.float32))
+    assert np.array_equal(cz, [1.0, -2.0, 0.0]) and np.allclose(hz, 0.5 * np.tanh([1.0, -2.0, 0.0]), rtol=0, atol=1e-16)
+    # gate order (input, forget, cell, output): a wide-open forget gate alone carries the cell through,
+    # a wide-open input gate alone writes tanh(g), a closed output gate silences h
+    big = 40.0
+    g1 = np.array([[-big, big, 0.3, big]], np.float32)
+    c1, h1, _ = oracle.lstm_cell(g1, np.array([0.7], np.float32))
+    assert abs(c1[0] - np.float64(np.float32(0.7))) < 1e-15 and abs(h1[0] - np.tanh(np.float64(np.float32(0.7)))) < 1e-15
+    g2 = np.array([[big, -big, 0.3, -big]], np.float32)
+    c2, h2, _ = oracle.lstm_cell(g2, np.array([0.7], np.float32))
+    assert abs(c2[0] - np.tanh(np.float64(np.float32(0.3)))) < 1e-15 and abs(h2[0]) < 1e-15
+    # element-wise: any split of batch or hidden units reproduces the whole, bit for bit
+    op = dict(kind="lstm_cell", batch=5, hidden=9)
+    for dim, k in [("B", 2), ("B", 5), ("H", 3)]:
+        out = np.zeros((5, 9))
+        for s_ in range(k):
+            reg = R.op_regions(op, [(dim, k, s_)])
+            assert reg["in_boxes"][0][:2] == reg["out_box"] and reg["in_boxes"][1] == reg["out_box"] and not reg["is_partial"]
+            sl = R.box_slices(reg["out_box"])
+            out[sl] = oracle.lstm_cell(g[sl], c[sl])[0]
+        assert np.array_equal(out, cn)
