@@ -33,6 +33,7 @@ LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced> + conv2d_seg
                "wgrad_batch": "wgrad_kernel<128,32,fast,balanced,14> + wgrad_segment_sum_kernel",
                "gemm_ksplit": "matmul_kernel<128,64,32,2,2>", "gemm_nsplit": "matmul_kernel<128,64,32,2,2> + slice_sum_kernel"}
 EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
+               "lstm_cell_nsplit": "element-wise LSTM cell update on the N-split worker's 128 x 1024 hidden units (3.7 MB: launch-bound)",
                "dgrad_cout": "backward of conv_cout: partial dx[128,2560,14,14] from the C_out/8 blocks of dy and the filters (filter reversal included)",
                "gemm_dx_nsplit": "backward of gemm_nsplit: partial dX = dY_s . W_s^T (128x16384x4096), W_s read transposed in place",
                "gemm_dw_nsplit": "backward of gemm_nsplit: dW_s = X^T . dY_s (16384x4096x128), X read transposed in place"}
@@ -223,8 +224,10 @@ def main():
             e[10].record()
             torch.cuda.synchronize()
             ms = sorted(e[i].elapsed_time(e[i + 1]) for i in range(10))[5]
-            extras.append({"leg": leg.name, "bound": "mfma", "ms": round(ms, 4), "achieved": round(leg.work / ms * 1e-9, 2),
-                           "unit": "TFLOP/s", "frac": round(leg.work / ms * 1e-9 / PEAK["mfma"][0], 4),
+            peak, unit = PEAK[leg.bound]
+            rate = leg.work / ms * (1e-9 if leg.bound == "mfma" else 1e-6)
+            extras.append({"leg": leg.name, "bound": leg.bound, "ms": round(ms, 4), "achieved": round(rate, 2),
+                           "unit": unit, "frac": round(rate / peak, 4),
                            "note": EXTRA_NOTES.get(leg.name, "") + "; median of 10 launches back to back"})
         out["extras"] = extras
     if not args.no_cpu_baseline:

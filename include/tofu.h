@@ -80,8 +80,10 @@ typedef enum {
   TOFU_OP_MATMUL = 0,               /* C[m,n]      = sum_k A[m,k] B[k,n]                                     */
   TOFU_OP_CONV2D = 1,               /* y[n,co,h,w] = sum_{ci,kh,kw} x[n,ci,h*s+kh-p,w*s+kw-p] w[co,ci,kh,kw] */
   TOFU_OP_CONV2D_WGRAD = 2,         /* dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] x[n,ci,h*s+kh-p,w*s+kw-p]  */
-  TOFU_OP_CONV2D_DGRAD = 3          /* dx[n,ci,ih,iw]  = sum_{co,kh,kw} dy[n,co,h,w] w[co,ci,kh,kw] over the
+  TOFU_OP_CONV2D_DGRAD = 3,         /* dx[n,ci,ih,iw]  = sum_{co,kh,kw} dy[n,co,h,w] w[co,ci,kh,kw] over the
                                        (h,w) with h*s+kh-p = ih, w*s+kw-p = iw                               */
+  TOFU_OP_LSTM_CELL = 4             /* element-wise over (b,h): c' = sig(f) c + sig(i) tanh(g), h' = sig(o) tanh(c')
+                                       with (i,f,g,o) = gates[b,h,0..3]; shapes: batch = M, hidden units = N  */
 } tofu_op_kind_t;
 
 /* Iteration dimensions a split may name.  Output dimensions give Case-1
@@ -91,6 +93,7 @@ enum { TOFU_MM_DIM_M = 0, TOFU_MM_DIM_N = 1, TOFU_MM_DIM_K = 2 /* reduction */ }
 enum { TOFU_CONV_DIM_N = 0, TOFU_CONV_DIM_CO = 1, TOFU_CONV_DIM_H = 2, TOFU_CONV_DIM_W = 3,
        TOFU_CONV_DIM_CI = 4 /* reduction */ };
 enum { TOFU_WGRAD_DIM_CO = 0, TOFU_WGRAD_DIM_CI = 1, TOFU_WGRAD_DIM_N = 2 /* reduction */ };
+enum { TOFU_LSTM_DIM_B = 0, TOFU_LSTM_DIM_H = 1 };   /* element-wise: no reduction dimension */
 /* data gradient: H and W are the rows / columns of dx, i.e. of the forward INPUT */
 enum { TOFU_DGRAD_DIM_N = 0, TOFU_DGRAD_DIM_CI = 1, TOFU_DGRAD_DIM_H = 2, TOFU_DGRAD_DIM_W = 3,
        TOFU_DGRAD_DIM_CO = 4 /* reduction */ };
@@ -115,8 +118,8 @@ int tofu_shard_range(int64_t extent, int32_t k, int32_t shard, int64_t* lo, int6
  * operator's iteration space and returns
  *   out_box      the box of the output tensor this shard writes (the whole
  *                output when only reduction dimensions were split),
- *   in_boxes[0]  the box of the first input it reads  (A | x | x  | dy),
- *   in_boxes[1]  the box of the second input it reads (B | w | dy | w),
+ *   in_boxes[0]  the box of the first input it reads  (A | x | x  | dy | gates),
+ *   in_boxes[1]  the box of the second input it reads (B | w | dy | w  | c_prev),
  *   pad_lo/hi[2] conv only: rows/columns (index 0 = H, 1 = W) of the needed
  *                window that fall outside the global input on the low/high
  *                side and are therefore zeros; in_boxes[0] is already clipped,
@@ -210,6 +213,23 @@ int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits
 int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                             const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* LSTM cell update that consumes the gate GEMM's output (the element-wise
+ * stage of the layer; Sec. 5.1: consecutive element-wise operators are merged
+ * and share their producer's partition).  op->kind = TOFU_OP_LSTM_CELL with
+ * op->M = batch and op->N = hidden units; splits name TOFU_LSTM_DIM_B / _H.
+ *   gates   [batch, hidden, 4]  pre-activations of the input, forget, cell and
+ *           output gate of each hidden unit (the gate GEMM's N index is
+ *           4 * h + gate, so an N shard that is a multiple of 4 holds whole units),
+ *   c_prev  [batch, hidden]     cell state before the step,
+ *   c_new, h_new [batch, hidden] written over the shard's box only;
+ *           c_new may be the same buffer as c_prev (each element is read before
+ *           it is written by the same thread), no other aliasing.
+ * All four are addressed by global coordinate through their extents, like the
+ * other shard calls; the innermost stride of gates must be 1.  No workspace. */
+int tofu_shard_lstm_cell(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                         const tofu_tensor_t* gates, const tofu_tensor_t* c_prev,
+                         const tofu_tensor_t* c_new, const tofu_tensor_t* h_new, void* hip_stream);
 
 /* Partition-n-reduce output step (Sec. 3.1 way 2; Sec. 6): dst[i] =
  * partials[0][i] + partials[1][i] + ... + partials[k-1][i], summed in that

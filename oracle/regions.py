@@ -58,8 +58,6 @@ def iteration_extents(op: dict) -> dict:
         return {"N": op["batch"], "CO": op["c_out"], "H": ho, "W": wo, "CI": op["c_in"]}
     if kind == "conv2d_wgrad":
         return {"CO": op["c_out"], "CI": op["c_in"], "N": op["batch"]}
-    if kind == "lstm_cell":
-        return {"B": op["batch"], "H": op["hidden"]}
     if kind == "conv2d_dgrad":
         return {"N": op["batch"], "CI": op["c_in"], "H": op["H"], "W": op["W"], "CO": op["c_out"]}
     raise ValueError(kind)

@@ -11,7 +11,8 @@ import os
 from typing import Optional, Sequence
 
 TOFU_MAX_DIMS = 6
-OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD = 0, 1, 2, 3
+OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD, OP_LSTM_CELL = 0, 1, 2, 3, 4
+LSTM_DIM_B, LSTM_DIM_H = 0, 1
 MM_DIM_M, MM_DIM_N, MM_DIM_K = 0, 1, 2
 CONV_DIM_N, CONV_DIM_CO, CONV_DIM_H, CONV_DIM_W, CONV_DIM_CI = 0, 1, 2, 3, 4
 WGRAD_DIM_CO, WGRAD_DIM_CI, WGRAD_DIM_N = 0, 1, 2
@@ -87,11 +88,12 @@ def load():
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
+    lib.tofu_shard_lstm_cell.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), P(Tensor), vp]
     lib.tofu_partition_reduce_ex.argtypes = [vp, P(vp), i32, i64, i32, i32, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_shard_lstm_cell"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -128,6 +130,12 @@ def conv2d_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1, kind=OP_C
 
 def wgrad_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1) -> OpDesc:
     return conv2d_desc(batch, c_in, c_out, H, W, KH, KW, stride, pad, kind=OP_CONV2D_WGRAD)
+
+
+def lstm_cell_desc(batch: int, hidden: int) -> OpDesc:
+    d = OpDesc()
+    d.kind, d.M, d.N = OP_LSTM_CELL, batch, hidden
+    return d
 
 
 def dgrad_desc(batch, c_in, c_out, H, W, KH=3, KW=3, stride=1, pad=1) -> OpDesc:
@@ -215,6 +223,12 @@ def shard_conv2d_wgrad(op, splits, x: Tensor, dy: Tensor, dw: Tensor, workspace=
 
 def shard_conv2d_dgrad(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=None, stream=None) -> None:
     _shard(load().tofu_shard_conv2d_dgrad, op, splits, dy, w, dx, workspace, stream)
+
+
+def shard_lstm_cell(op, splits, gates: Tensor, c_prev: Tensor, c_new: Tensor, h_new: Tensor, stream=None) -> None:
+    sp, n = _splits(splits)
+    _check(load().tofu_shard_lstm_cell(ctypes.byref(op), sp, n, ctypes.byref(gates), ctypes.byref(c_prev), ctypes.byref(c_new),
+                                       ctypes.byref(h_new), _stream(stream)))
 
 
 REDUCE_SUM, REDUCE_MAX, REDUCE_MIN, REDUCE_PROD = 0, 1, 2, 3

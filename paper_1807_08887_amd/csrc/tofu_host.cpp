@@ -25,6 +25,7 @@ int iter_ndim(int32_t kind) {
     case TOFU_OP_CONV2D: return 5;
     case TOFU_OP_CONV2D_WGRAD: return 3;
     case TOFU_OP_CONV2D_DGRAD: return 5;
+    case TOFU_OP_LSTM_CELL: return 2;
     default: return 0;
   }
 }
@@ -36,6 +37,10 @@ int64_t conv_out_extent(int64_t size, int64_t ksize, int64_t stride, int64_t pad
 
 int check_op(const tofu_op_desc_t* op) {
   if (!op) return fail(TOFU_ERR_INVALID_ARG, "operator description is NULL");
+  if (op->kind == TOFU_OP_LSTM_CELL) {
+    if (op->M < 1 || op->N < 1) return fail(TOFU_ERR_INVALID_ARG, "lstm cell needs batch (M) and hidden units (N) >= 1");
+    return TOFU_OK;
+  }
   if (op->kind == TOFU_OP_MATMUL) {
     if (op->M < 1 || op->N < 1 || op->K < 1)
       return fail(TOFU_ERR_INVALID_ARG, "matmul needs M,N,K >= 1 (got %lld,%lld,%lld)", (long long)op->M,
@@ -66,6 +71,10 @@ static void iter_extents(const tofu_op_desc_t* op, int64_t* ext, int* first_redu
       ext[TOFU_CONV_DIM_W] = conv_out_extent(op->W, op->KW, op->stride, op->pad);
       ext[TOFU_CONV_DIM_CI] = op->c_in;
       *first_reduce = TOFU_CONV_DIM_CI;
+      break;
+    case TOFU_OP_LSTM_CELL:
+      ext[TOFU_LSTM_DIM_B] = op->M; ext[TOFU_LSTM_DIM_H] = op->N;
+      *first_reduce = 2;          // no reduction dimension
       break;
     case TOFU_OP_CONV2D_DGRAD:
       ext[TOFU_DGRAD_DIM_N] = op->batch; ext[TOFU_DGRAD_DIM_CI] = op->c_in;
@@ -271,6 +280,11 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
     lo[0] = r.lo[CO]; hi[0] = r.hi[CO]; lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
     lo[2] = 0; hi[2] = op->KH; lo[3] = 0; hi[3] = op->KW;
     set_box(&ib[1], 4, lo, hi);
+  } else if (op->kind == TOFU_OP_LSTM_CELL) {   // element-wise: inputs are read where the output is written
+    int64_t lo[3] = {r.lo[0], r.lo[1], 0}, hi[3] = {r.hi[0], r.hi[1], 4};
+    set_box(&ob, 2, lo, hi);
+    set_box(&ib[0], 3, lo, hi);
+    set_box(&ib[1], 2, lo, hi);
   } else if (op->kind == TOFU_OP_CONV2D_DGRAD) {
     const int N = TOFU_DGRAD_DIM_N, CI = TOFU_DGRAD_DIM_CI, H = TOFU_DGRAD_DIM_H, W = TOFU_DGRAD_DIM_W, CO = TOFU_DGRAD_DIM_CO;
     const int64_t ho = conv_out_extent(op->H, op->KH, op->stride, op->pad), wo = conv_out_extent(op->W, op->KW, op->stride, op->pad);

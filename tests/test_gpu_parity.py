@@ -660,6 +660,53 @@ def test_reduce_nan_convention_in_place_and_scatter_share():
     assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.reduce(parts)[0])
 
 
+# ----------------------------------------------------------------------------- lstm cell
+@pytest.mark.parametrize("B,H", [(128, 1024), (5, 33), (1, 1), (64, 250)])
+def test_lstm_cell_against_oracle_and_splits(B, H):
+    """Element-wise stage after the gate GEMM: within 1e-5 of the fp64 oracle (c against
+    |sig(f) c| + |sig(i) tanh(g)|, h against 1), and every split of batch or hidden units writes
+    exactly the bits of the unsplit call."""
+    g = synth.normal(91, 0, (B, H, 4), 3.0)
+    g[0, 0] = [-100.0, 100.0, 50.0, 100.0]          # saturated gates stay finite
+    c = synth.normal(91, 1, (B, H), 1.0)
+    cn, hn, sc = oracle.lstm_cell(g, c)
+    dg, dc = dev(g), dev(c)
+    op = tofu.lstm_cell_desc(B, H)
+    out_c = torch.full((B, H), float("nan"), dtype=torch.float32, device=DEV)
+    out_h = torch.full((B, H), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_lstm_cell(op, [], tofu.tensor(dg), tofu.tensor(dc), tofu.tensor(out_c), tofu.tensor(out_h))
+    assert_close(out_c.cpu().numpy(), cn, sc, "lstm c")
+    assert_close(out_h.cpu().numpy(), hn, np.ones_like(hn), "lstm h")
+    for dim, k in [(tofu.LSTM_DIM_B, 2), (tofu.LSTM_DIM_H, 3), (tofu.LSTM_DIM_H, 8)]:
+        if (B if dim == tofu.LSTM_DIM_B else H) < k:
+            continue
+        pc = torch.full((B, H), float("nan"), dtype=torch.float32, device=DEV)
+        ph = torch.full((B, H), float("nan"), dtype=torch.float32, device=DEV)
+        for s in range(k):
+            tofu.shard_lstm_cell(op, [(dim, k, s)], tofu.tensor(dg), tofu.tensor(dc), tofu.tensor(pc), tofu.tensor(ph))
+        assert torch.equal(pc, out_c) and torch.equal(ph, out_h)
+
+
+def test_lstm_cell_on_a_gate_gemm_shard_in_place():
+    """The N-split worker's view: its block of gate columns (hidden units [h0,h1), four gates each)
+    as produced by its GEMM shard, its block of the cell state updated in place."""
+    B, H, k, s = 16, 64, 4, 2
+    h0, h1 = R.shard_range(H, k, s)
+    g = synth.normal(92, 0, (B, H, 4), 2.0)
+    c = synth.normal(92, 1, (B, H), 1.0)
+    cn, hn, sc = oracle.lstm_cell(g, c)
+    g_blk = dev(g[:, h0:h1].copy())                       # [B, H/k, 4]: the GEMM shard's output columns 4*h0 .. 4*h1
+    c_blk = dev(c[:, h0:h1].copy())
+    h_full = torch.full((B, H), float("nan"), dtype=torch.float32, device=DEV)
+    op = tofu.lstm_cell_desc(B, H)
+    sp = [(tofu.LSTM_DIM_H, k, s)]
+    tofu.shard_lstm_cell(op, sp, tofu.tensor(g_blk, [0, h0, 0]), tofu.tensor(c_blk, [0, h0]), tofu.tensor(c_blk, [0, h0]), tofu.tensor(h_full))
+    assert_close(c_blk.cpu().numpy(), cn[:, h0:h1], sc[:, h0:h1], "in-place c block")
+    got_h = h_full.cpu().numpy()
+    assert_close(got_h[:, h0:h1], hn[:, h0:h1], np.ones((B, h1 - h0)), "h block")
+    assert np.isnan(got_h[:, :h0]).all() and np.isnan(got_h[:, h1:]).all()
+
+
 # ----------------------------------------------------------------------------- probes
 def test_probes_copy_exactly_and_leave_the_sink_alone():
     """The measurement aids of tofu_probe.h: the copy is bit-exact on a ragged vector count,

@@ -44,7 +44,7 @@ def _check_reduce(leg):
 
 
 @pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_dx_nsplit", "gemm_dw_nsplit"), ("gemm_ksplit", "reduce_gates"),
-                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",)])
+                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",), ("lstm_cell_nsplit",)])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)
     legs = tofu_workloads.build("cuda:0", group)
@@ -76,6 +76,10 @@ def test_full_size_legs(group):
             if leg.name == "conv_cout_h_fused":   # reading the blocks directly changes no bit of the result
                 fetched = next(l for l in legs if l.name == "conv_cout_h")
                 assert torch.equal(leg.out, fetched.out)
+        elif h["kind"] == "lstm":
+            cn, hn, sc = oracle.lstm_cell(h["gates"], h["c"])
+            _close(leg.out.cpu().numpy().ravel(), cn.ravel(), sc.ravel(), leg.name + " c")
+            _close(h["h_out"].cpu().numpy().ravel(), hn.ravel(), np.ones(hn.size), leg.name + " h")
         elif h["kind"] == "dgrad":
             dxp = leg.out.cpu().numpy()
             pts = _points(74, 4096, dxp.shape)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
             "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_tdl_regions", "tofu_tdl_symbolic", "tofu_tdl_from_op",
-            "tofu_tdl_fetch_elements"} <= names
+            "tofu_tdl_fetch_elements", "tofu_shard_lstm_cell"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
@@ -46,6 +46,8 @@ def test_shard_range_matches_oracle_exhaustively():
 
 
 def _desc(op):
+    if op["kind"] == "lstm_cell":
+        return tofu.lstm_cell_desc(op["batch"], op["hidden"]), {"B": 0, "H": 1}
     if op["kind"] == "matmul":
         return tofu.matmul_desc(op["M"], op["N"], op["K"]), {"M": 0, "N": 1, "K": 2}
     args = (op["batch"], op["c_in"], op["c_out"], op["H"], op["W"], op["KH"], op["KW"], op["stride"], op["pad"])
@@ -73,6 +75,7 @@ OPS = [
     dict(kind="conv2d_dgrad", batch=5, c_in=7, c_out=6, H=11, W=9, KH=3, KW=3, stride=1, pad=1),
     dict(kind="conv2d_dgrad", batch=4, c_in=4, c_out=4, H=9, W=9, KH=3, KW=3, stride=1, pad=0),
     dict(kind="conv2d_dgrad", batch=4, c_in=4, c_out=4, H=12, W=13, KH=5, KW=3, stride=2, pad=2),
+    dict(kind="lstm_cell", batch=6, hidden=10),
 ]
 
 
@@ -204,6 +207,24 @@ def test_dgrad_error_paths_are_checked_on_the_host():
     with pytest.raises(tofu.TofuError) as e:
         tofu.shard_conv2d_dgrad(tofu.dgrad_desc(2, 4, 64, 8, 8, pad=0), [], _t([(0, 2), (0, 64), (0, 6), (0, 6)]), w, dx, stream=0)
     assert e.value.status == -6
+
+
+def test_lstm_cell_error_paths_are_checked_on_the_host():
+    op = tofu.lstm_cell_desc(4, 8)
+    g, c = _t([(0, 4), (0, 8), (0, 4)]), _t([(0, 4), (0, 8)], FAKE + (1 << 20))
+    cn, hn = _t([(0, 4), (0, 8)], FAKE + (2 << 20)), _t([(0, 4), (0, 8)], FAKE + (3 << 20))
+    with pytest.raises(tofu.TofuError) as e:      # the gates of only half the hidden units
+        tofu.shard_lstm_cell(op, [], _t([(0, 4), (0, 4), (0, 4)]), c, cn, hn, stream=0)
+    assert e.value.status == -2
+    with pytest.raises(tofu.TofuError) as e:      # h_new in c_new's buffer
+        tofu.shard_lstm_cell(op, [], g, c, cn, cn, stream=0)
+    assert e.value.status == -1
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_lstm_cell(tofu.matmul_desc(4, 8, 2), [], g, c, cn, hn, stream=0)
+    assert e.value.status == -1
+    assert tofu.workspace_bytes(op, [(tofu.LSTM_DIM_H, 2, 1)]) == 0
+    r = tofu.op_regions(op, [(tofu.LSTM_DIM_H, 2, 1)])
+    assert r["in_boxes"] == [[(0, 4), (4, 8), (0, 4)], [(0, 4), (4, 8)]] and not r["is_partial"]
 
 
 def test_fused_conv_error_paths_are_checked_on_the_host():

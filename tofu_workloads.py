@@ -10,6 +10,7 @@ Builds, from the seeded generator, the device buffers of the four large workload
   fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
   conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
   conv_cout_h_fused  (extra, built only when named) the same shard reading the two blocks directly
+  lstm_cell_nsplit   (extra) element-wise LSTM cell update on the N-split worker's 1024 hidden units (28 bytes per element)
   dgrad_cout         (extra) backward of conv_cout: partial dx from the worker's C_out/8 block of dy and of the filters
   gemm_dx_nsplit     (extra) backward of the N-split gate GEMM: partial dX = dY_s . W_s^T, W_s read transposed in place
   gemm_dw_nsplit     (extra) backward of the N-split gate GEMM: dW_s = X^T . dY_s, X read transposed in place
@@ -62,7 +63,7 @@ def _ws(op, splits, dev):
 
 STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
 # variants and backward operators outside the step, built only when named
-EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout")
+EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout", "lstm_cell_nsplit")
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -118,6 +119,22 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                             _call(tofu.shard_matmul, opw, spw, tofu.tensor(dX.t()), tofu.tensor(ddY, [0, n0]), tofu.tensor(gW, [0, n0]), wsw_), gW,
                             dict(kind="matmul", A=np.ascontiguousarray(X.T), B=dYs, box=[(0, K), (0, n1 - n0)], krange=(0, M), b_col0=0,
                                  keep=(dX, ddY, wsw_)) if keep_host else dict(keep=(dX, ddY, wsw_))))
+    if which is not None and "lstm_cell_nsplit" in which:
+        # the element-wise stage shares the gate GEMM's N partition: 8192 hidden units, 8 workers
+        cfg = synth.CONFIGS["lstm_gates_nsplit"]
+        Bt, Hd, k, s = 128, 8192, cfg["k"], cfg["shard"]
+        opl = tofu.lstm_cell_desc(Bt, Hd)
+        spl = [(tofu.LSTM_DIM_H, k, s)]
+        h0, h1 = tofu.shard_range(Hd, k, s)
+        g_s = synth.normal(cfg["seed"], 3, (Bt, h1 - h0, 4), 2.0)
+        c_s = synth.normal(cfg["seed"], 4, (Bt, h1 - h0), 1.0)
+        d_g, d_c = up(g_s), up(c_s)
+        c_new = torch.zeros(Bt, h1 - h0, dtype=torch.float32, device=dev)
+        h_new = torch.zeros(Bt, h1 - h0, dtype=torch.float32, device=dev)
+        legs.append(Leg("lstm_cell_nsplit", "hbm", 28.0 * Bt * (h1 - h0),
+                        _call(tofu.shard_lstm_cell, opl, spl, tofu.tensor(d_g, [0, h0, 0]), tofu.tensor(d_c, [0, h0]),
+                              tofu.tensor(c_new, [0, h0]), tofu.tensor(h_new, [0, h0])), c_new,
+                        dict(kind="lstm", gates=g_s, c=c_s, h_out=h_new, keep=(d_g, d_c, h_new)) if keep_host else dict(keep=(d_g, d_c, h_new))))
     if want("gemm_ksplit", "reduce_gates"):
         cfg = synth.CONFIGS["lstm_gates_ksplit"]
         s = cfg["shard"]
