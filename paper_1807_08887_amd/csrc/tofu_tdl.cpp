@@ -67,6 +67,15 @@ extern "C" int tofu_tdl_from_op(const tofu_op_desc_t* op, tofu_tdl_op_t* out) {
     a.size[d] = size;
     return a.index[d];
   };
+  if (op->kind == TOFU_OP_LSTM_CELL) {                   // vars: b, h | gate (the four gates of a unit are all read)
+    out->n_vars = 3; out->n_out = 2; out->n_inputs = 2;
+    out->extent[0] = op->M; out->extent[1] = op->N; out->extent[2] = 4;
+    tofu_tdl_access_t &g = out->input[0], &c = out->input[1];
+    g.ndim = 3; c.ndim = 2;
+    dim(g, 0, op->M).coef[0] = 1; dim(g, 1, op->N).coef[1] = 1; dim(g, 2, 4).coef[2] = 1;
+    dim(c, 0, op->M).coef[0] = 1; dim(c, 1, op->N).coef[1] = 1;
+    return TOFU_OK;
+  }
   if (op->kind == TOFU_OP_MATMUL) {                      // vars: m, n | k
     out->n_vars = 3; out->n_out = 2; out->n_inputs = 2;
     out->extent[0] = op->M; out->extent[1] = op->N; out->extent[2] = op->K;
