@@ -129,6 +129,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--legs", type=str, default="", help="comma-separated subset of legs (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step into a HIP graph and report its replay time (launch gaps removed)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain elementwise copy of 256 MiB before the timed steps, so that a "
                          "hardware-counter run holds a kernel of known traffic to scale its counters by")
@@ -210,6 +212,24 @@ def main():
         "attainable": peaks,
         "legs": leg_out,
     }
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_replay_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
     if extra_legs:
         # outside the step: the fused-fetch convolution and the backward GEMMs, timed right after
         # the steps (warm clocks)
