@@ -22,9 +22,9 @@ PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 ma
 # hardware-counter runs summarised in profiles/all_legs_hbm_traffic.txt: (FETCH_SIZE, WRITE_SIZE)
 # per dispatch, each scaled by the factor that makes the same counter match the 256 MiB
 # calibration copy of that run (2.0 for reads, 1.0 for writes).
-TRAFFIC_KIB = {"conv_cout": (533177.0 + 32049.8, 64000.0 + 35699.8),        # conv2d_kernel + conv2d_segment_sum_kernel
+TRAFFIC_KIB = {"conv_cout": (532281.0 + 32050.0, 64000.0 + 35699.1),        # conv2d_kernel + conv2d_segment_sum_kernel
                "conv_cout_h": (792903.0 + 24241.7, 48384.0 + 19107.9),
-               "wgrad_batch": (1102110.0 + 63400.0, 126720.0 + 57668.8),    # wgrad_kernel + wgrad_segment_sum_kernel
+               "wgrad_batch": (1089900.0 + 63396.5, 126720.0 + 57763.5),    # wgrad_kernel + wgrad_segment_sum_kernel
                "gemm_ksplit": (149577.0, 16384.0),
                "gemm_nsplit": (149577.0 + 8210.5, 16384.0 + 2048.0)}        # matmul_kernel + slice_sum_kernel
 TRAFFIC_SCALE = (2.0, 1.0)
