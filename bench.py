@@ -33,6 +33,8 @@ LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced> + conv2d_seg
                "wgrad_batch": "wgrad_kernel<128,32,fast,balanced,14> + wgrad_segment_sum_kernel",
                "gemm_ksplit": "matmul_kernel<128,64,32,2,2>", "gemm_nsplit": "matmul_kernel<128,64,32,2,2> + slice_sum_kernel"}
 EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
+               "gemm_ksplit_accumulate": "gemm_ksplit adding into a resident [128,32768] buffer (reduction fused into the epilogue)",
+               "wgrad_batch_accumulate": "wgrad_batch adding into a resident dW (reduction fused into the segment sum)",
                "lstm_cell_nsplit": "element-wise LSTM cell update on the N-split worker's 128 x 1024 hidden units (3.7 MB: launch-bound)",
                "dgrad_cout": "backward of conv_cout: partial dx[128,2560,14,14] from the C_out/8 blocks of dy and the filters (filter reversal included)",
                "gemm_dx_nsplit": "backward of gemm_nsplit: partial dX = dY_s . W_s^T (128x16384x4096), W_s read transposed in place",

@@ -250,12 +250,47 @@ typedef enum { TOFU_REDUCE_SUM = 0, TOFU_REDUCE_MAX = 1, TOFU_REDUCE_MIN = 2, TO
 typedef enum { TOFU_ORDER_LINEAR = 0, TOFU_ORDER_TREE = 1 } tofu_reduce_order_t;
 
 /* tofu_partition_reduce with a chosen reducer and order; (SUM, LINEAR) is
- * bit-identical to tofu_partition_reduce.  A reduce-scatter share (worker j
- * sums only its 1/k slice of every partial) is this call on offset pointers
- * and the slice's count.  Same argument rules and errors; an unknown reducer
- * or order -> INVALID_ARG. */
+ * bit-identical to tofu_partition_reduce.  Same argument rules and errors; an
+ * unknown reducer or order -> INVALID_ARG. */
 int tofu_partition_reduce_ex(void* dst, const void* const* partials, int32_t k, int64_t count,
                              int32_t reducer, int32_t order, void* hip_stream);
+
+/* One worker's share of the spread-out reduction (Sec. 6: the reduction work is
+ * divided over all workers instead of one aggregating everything): combine only
+ * the elements [lo, hi) = [floor(share*count/shares), floor((share+1)*count/shares))
+ * of the k partials and write dst[lo..hi); everything outside that range is left
+ * untouched.  dst and every partial point at element 0 of the full-length
+ * arrays.  The values written are bit-identical to those tofu_partition_reduce_ex
+ * writes at the same indices, so running all `shares` shares reproduces it.
+ * 1 <= shares, 0 <= share < shares, else INVALID_ARG; an empty share is a no-op.
+ * Other rules as for tofu_partition_reduce_ex. */
+int tofu_partition_reduce_scatter(void* dst, const void* const* partials, int32_t k, int64_t count,
+                                  int32_t shares, int32_t share, int32_t reducer, int32_t order,
+                                  void* hip_stream);
+
+/* Reduction fused into the producer (Sec. 7.2: gradients of a large model are
+ * aggregated in place rather than kept as separate partials): the same shard
+ * calls, but the shard's result is ADDED to what the output box already holds,
+ * out = out + result, one fp32 addition per element after the shard's own sum is
+ * complete.  Running the k shards of a Case-2 split one after another on one
+ * stream, the first through the plain call and the others through these, leaves
+ * exactly what k separate partials followed by tofu_partition_reduce (left to
+ * right) would: ((P0 + P1) + P2) + ..., bit for bit, without the k partial
+ * buffers or the reduce pass.  Arguments, workspace, limits and errors are those
+ * of the plain calls; calls that add to one output box must be ordered (same
+ * stream), concurrent ones race. */
+int tofu_shard_matmul_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+int tofu_shard_conv2d_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+int tofu_shard_conv2d_wgrad_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+int tofu_shard_conv2d_dgrad_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -84,16 +84,20 @@ def load():
     lib.tofu_workspace_bytes.restype = sz
     lib.tofu_workspace_bytes.argtypes = [P(OpDesc), P(Split), i32]
     lib.tofu_region_fetch.argtypes = [P(Tensor), P(Tensor), i32, vp]
-    for name in ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad", "tofu_shard_conv2d_dgrad"):
+    shard_calls = ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad", "tofu_shard_conv2d_dgrad")
+    accumulate_calls = tuple(n + "_accumulate" for n in shard_calls)
+    for name in shard_calls + accumulate_calls:
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
     lib.tofu_shard_lstm_cell.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), P(Tensor), vp]
     lib.tofu_partition_reduce_ex.argtypes = [vp, P(vp), i32, i64, i32, i32, vp]
+    lib.tofu_partition_reduce_scatter.argtypes = [vp, P(vp), i32, i64, i32, i32, i32, i32, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
-                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_shard_lstm_cell"):
+                 "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_shard_lstm_cell",
+                 "tofu_partition_reduce_scatter") + accumulate_calls:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -225,6 +229,22 @@ def shard_conv2d_dgrad(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=
     _shard(load().tofu_shard_conv2d_dgrad, op, splits, dy, w, dx, workspace, stream)
 
 
+def shard_matmul_accumulate(op, splits, A: Tensor, B: Tensor, C: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_matmul_accumulate, op, splits, A, B, C, workspace, stream)
+
+
+def shard_conv2d_accumulate(op, splits, x: Tensor, w: Tensor, y: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d_accumulate, op, splits, x, w, y, workspace, stream)
+
+
+def shard_conv2d_wgrad_accumulate(op, splits, x: Tensor, dy: Tensor, dw: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d_wgrad_accumulate, op, splits, x, dy, dw, workspace, stream)
+
+
+def shard_conv2d_dgrad_accumulate(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv2d_dgrad_accumulate, op, splits, dy, w, dx, workspace, stream)
+
+
 def shard_lstm_cell(op, splits, gates: Tensor, c_prev: Tensor, c_new: Tensor, h_new: Tensor, stream=None) -> None:
     sp, n = _splits(splits)
     _check(load().tofu_shard_lstm_cell(ctypes.byref(op), sp, n, ctypes.byref(gates), ctypes.byref(c_prev), ctypes.byref(c_new),
@@ -235,16 +255,29 @@ REDUCE_SUM, REDUCE_MAX, REDUCE_MIN, REDUCE_PROD = 0, 1, 2, 3
 ORDER_LINEAR, ORDER_TREE = 0, 1
 
 
+def _addr(t) -> int:
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or t.dtype.itemsize != 4 or not t.is_contiguous():
+        raise TypeError("partition_reduce needs contiguous float32 device tensors")
+    return t.data_ptr()
+
+
+def partition_reduce_scatter(dst, partials: Sequence, shares: int, share: int, count: Optional[int] = None, stream=None,
+                             reducer: int = REDUCE_SUM, order: int = ORDER_LINEAR) -> None:
+    """tofu_partition_reduce_scatter: combine only share `share` of `shares` of the flat index range."""
+    if count is None:
+        count = dst.numel()
+    ptrs = (ctypes.c_void_p * max(1, len(partials)))(*[_addr(p) for p in partials])
+    _check(load().tofu_partition_reduce_scatter(ctypes.c_void_p(_addr(dst)), ptrs, len(partials), count, shares, share, reducer, order,
+                                                _stream(stream)))
+
+
 def partition_reduce(dst, partials: Sequence, count: Optional[int] = None, stream=None, reducer: Optional[int] = None,
                      order: int = ORDER_LINEAR) -> None:
     """dst, partials: CUDA float32 torch tensors (contiguous) or raw device addresses.
     With `reducer` given the call goes to tofu_partition_reduce_ex."""
-    def addr(t):
-        if isinstance(t, int):
-            return t
-        if not t.is_cuda or t.dtype.itemsize != 4 or not t.is_contiguous():
-            raise TypeError("partition_reduce needs contiguous float32 device tensors")
-        return t.data_ptr()
+    addr = _addr
     if count is None:
         count = dst.numel()
     ptrs = (ctypes.c_void_p * max(1, len(partials)))(*[addr(p) for p in partials])

@@ -38,6 +38,7 @@ struct ConvArgs {
   const float* x;   // element at the low corner of the (clipped) input box
   const float* w;   // element (co_lo, ci_lo, 0, 0)
   float* y;         // element at the low corner of the output box
+  int accumulate;   // 1: the shard's result is added to what the output box holds
   int64_t xs[4], ws[4], ys[4];   // element strides (n, c, h, w) / (co, ci, kh, kw) / (n, co, h, w)
   uint32_t x_bytes, w_bytes;     // bytes spanned by the input box / the filter box (buffer bounds)
   int NB, CO, CI;   // images, output channels and input channels of the shard
@@ -358,14 +359,18 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int co = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
-          if (co < p.CO) p.y[y_off[j] + (int64_t)co * p.ys[1]] = acc[i][j][v];
+          if (co < p.CO) {
+            float* o = p.y + y_off[j] + (int64_t)co * p.ys[1];
+            *o = p.accumulate ? *o + acc[i][j][v] : acc[i][j][v];
+          }
         }
       }
   }
   } while (BALANCED && segment >= 0);
 }
 
-// Sums the slots of every balanced tile in workgroup order and writes the output box.  One
+// Sums the slots of every balanced tile in workgroup order and writes the output box (or adds
+// the sum to it).  One
 // workgroup per (tile, 32x32 accumulator block): thread and accumulator index map to (channel,
 // position) exactly as in the convolution kernel, so reads are NT consecutive floats and writes
 // follow the output rows.
@@ -398,7 +403,10 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_segment_sum_kernel(const 
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int co = tile_m * BM + wm * TM + i * 32 + acc_row(v, half);
-    if (co < p.CO) p.y[y_off + (int64_t)co * p.ys[1]] = acc[v];
+    if (co < p.CO) {
+      float* o = p.y + y_off + (int64_t)co * p.ys[1];
+      *o = p.accumulate ? *o + acc[v] : acc[v];
+    }
   }
 }
 
@@ -528,11 +536,13 @@ struct ConvProblem {
   int64_t ys[4];
   void* workspace;           // segment slots of a balanced launch (conv_workspace_bytes), may be NULL when none are needed
   size_t workspace_bytes;
+  bool accumulate;           // add to the output box instead of overwriting it
 };
 
 static int conv_core(const ConvProblem& q, hipStream_t stream) {
   ConvArgs p;
   p.x = q.x; p.w = q.w; p.y = q.y;
+  p.accumulate = q.accumulate ? 1 : 0;
   const int64_t NB = q.out_box.hi[0] - q.out_box.lo[0], CO = q.out_box.hi[1] - q.out_box.lo[1];
   const int64_t BH = q.out_box.hi[2] - q.out_box.lo[2], BW = q.out_box.hi[3] - q.out_box.lo[3];
   const int64_t CI = q.in_box.hi[1] - q.in_box.lo[1];
@@ -577,7 +587,7 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
 // or NULL when the region is read from the `nsrc` blocks `x_srcs`.
 static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
                         const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
-                        size_t workspace_bytes, void* hip_stream) {
+                        size_t workspace_bytes, void* hip_stream, bool accumulate) {
   if (!op || op->kind != TOFU_OP_CONV2D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d");
   ConvProblem q;
   tofu_region_t in_boxes[2];
@@ -635,6 +645,7 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
   }
   q.workspace = workspace;
   q.workspace_bytes = workspace_bytes;
+  q.accumulate = accumulate;
   return conv_core(q, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -667,19 +678,26 @@ extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* s
                                  const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
                                  size_t workspace_bytes, void* hip_stream) {
   if (!x) return tofu::fail(TOFU_ERR_INVALID_ARG, "x is NULL");
-  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, workspace, workspace_bytes, hip_stream);
+  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" int tofu_shard_conv2d_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                            const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  if (!x) return tofu::fail(TOFU_ERR_INVALID_ARG, "x is NULL");
+  return tofu::shard_conv2d(op, splits, nsplits, x, nullptr, 0, w, y, workspace, workspace_bytes, hip_stream, true);
 }
 
 extern "C" int tofu_shard_conv2d_fused(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                                        const tofu_tensor_t* x_srcs, int32_t nsrc, const tofu_tensor_t* w, const tofu_tensor_t* y,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, workspace, workspace_bytes, hip_stream);
+  return tofu::shard_conv2d(op, splits, nsplits, nullptr, x_srcs, nsrc, w, y, workspace, workspace_bytes, hip_stream, false);
 }
 
-extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
-                                       const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx, void* workspace,
-                                       size_t workspace_bytes, void* hip_stream) {
-  using namespace tofu;
+namespace tofu {
+static int shard_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* dy,
+                       const tofu_tensor_t* w, const tofu_tensor_t* dx, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       bool accumulate) {
   if (!op || op->kind != TOFU_OP_CONV2D_DGRAD) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d data gradient");
   ConvProblem q;
   tofu_region_t in_boxes[2];
@@ -722,5 +740,19 @@ extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_spli
   q.y = const_cast<float*>(element_ptr(dx, q.ys, q.out_box.lo));
   q.workspace = static_cast<char*>(workspace) + flip_bytes;
   q.workspace_bytes = workspace_bytes - flip_bytes;
+  q.accumulate = accumulate;
   return conv_core(q, stream);
+}
+}  // namespace tofu
+
+extern "C" int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_dgrad(op, splits, nsplits, dy, w, dx, workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" int tofu_shard_conv2d_dgrad_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                                  const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
+                                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_dgrad(op, splits, nsplits, dy, w, dx, workspace, workspace_bytes, hip_stream, true);
 }

@@ -34,6 +34,7 @@ struct MatmulArgs {
   int m, n, k;      // shard extents
   int k_slice;      // K elements per slice (multiple of BK); slices = gridDim.y
   int tiles_n;      // number of tiles along n
+  int accumulate;   // 1: the product is added to what the output box holds (only without K slices; the slice sum adds otherwise)
   int fast;         // 1: each operand contiguous along one index, 16-byte aligned, 32-bit offsets -> buffer vector loads
   uint32_t a_bytes, b_bytes;   // bytes spanned by the two input boxes (buffer bounds, fast path)
 };
@@ -247,15 +248,19 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm * Cfg::TM + i * 32 + acc_row(v, half);
-        if (row < p.m && col < p.n) C[(int64_t)row * p.c_rs + (int64_t)col * p.c_cs] = acc[i][j][v];
+        if (row < p.m && col < p.n) {
+          float* c = C + (int64_t)row * p.c_rs + (int64_t)col * p.c_cs;
+          *c = p.accumulate ? *c + acc[i][j][v] : acc[i][j][v];
+        }
       }
     }
 }
 
 // Sum of the K slices held in the workspace ([slices][m][n], dense) into the output box, in
-// fixed order.  The output may be a strided block of a larger tensor.
+// fixed order; with `accumulate` the sum of the slices is then added to what the box holds.
+// The output may be a strided block of a larger tensor.
 __global__ void __launch_bounds__(256) slice_sum_kernel(float* __restrict__ C, int64_t c_rs, int64_t c_cs, const float* __restrict__ ws,
-                                                         int slices, int m, int n, int vec) {
+                                                         int slices, int m, int n, int vec, int accumulate) {
   const int64_t per_row = n / vec, items = (int64_t)m * per_row, slice = (int64_t)m * n;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t row = i / per_row, col = (i - row * per_row) * vec;
@@ -263,11 +268,13 @@ __global__ void __launch_bounds__(256) slice_sum_kernel(float* __restrict__ C, i
     if (vec == 4) {
       v4f32 acc = *reinterpret_cast<const v4f32*>(src);
       for (int j = 1; j < slices; ++j) acc += *reinterpret_cast<const v4f32*>(src + j * slice);
-      *reinterpret_cast<v4f32*>(C + row * c_rs + col) = acc;
+      v4f32* c = reinterpret_cast<v4f32*>(C + row * c_rs + col);
+      *c = accumulate ? *c + acc : acc;
     } else {
       float acc = src[0];
       for (int j = 1; j < slices; ++j) acc += src[j * slice];
-      C[row * c_rs + col * c_cs] = acc;
+      float* c = C + row * c_rs + col * c_cs;
+      *c = accumulate ? *c + acc : acc;
     }
   }
 }
@@ -286,12 +293,9 @@ int matmul_split_k(int64_t m, int64_t n, int64_t k) {
   return (int)s;
 }
 
-}  // namespace tofu
-
-extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
-                                 const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
-  using namespace tofu;
+static int shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* A,
+                        const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace, size_t workspace_bytes, void* hip_stream,
+                        bool accumulate) {
   if (!op || op->kind != TOFU_OP_MATMUL) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a matmul");
   tofu_region_t out_box, in_boxes[2];
   int32_t partial = 0;
@@ -335,10 +339,12 @@ extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* s
       return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "matmul shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
     p.C = static_cast<float*>(workspace);
+    p.accumulate = 0;
     p.c_rs = n; p.c_cs = 1; p.c_slice = m * n;
     p.k_slice = (int)(((k + split - 1) / split + kBK - 1) / kBK * kBK);
   } else {
     p.C = c_out;
+    p.accumulate = accumulate ? 1 : 0;
     p.c_rs = cs[0]; p.c_cs = cs[1]; p.c_slice = 0;
     p.k_slice = (int)((k + kBK - 1) / kBK * kBK);
   }
@@ -357,9 +363,23 @@ extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* s
     const int64_t items = m * (n / vec);
     const int blocks = (int)((items + 255) / 256 < 4096 ? (items + 255) / 256 : 4096);
     hipLaunchKernelGGL(slice_sum_kernel, dim3(blocks), dim3(256), 0, s, c_out, cs[0], cs[1], static_cast<const float*>(workspace),
-                       slices, (int)m, (int)n, vec);
+                       slices, (int)m, (int)n, vec, accumulate ? 1 : 0);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "matmul slice sum launch failed: %s", hipGetErrorString(e));
   }
   return TOFU_OK;
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_matmul(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_matmul(op, splits, nsplits, A, B, C, workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" int tofu_shard_matmul_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                            const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_matmul(op, splits, nsplits, A, B, C, workspace, workspace_bytes, hip_stream, true);
 }

@@ -58,9 +58,14 @@ __device__ __forceinline__ T fold(const T* v) {
 }
 
 template <int K, int UNROLL, bool NT, int MODE>
-__global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restrict__ dst, ReducePtrs src, int64_t n_vec, int64_t count) {
+__global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restrict__ dst_all, ReducePtrs src_all, int64_t n_vec, int64_t count, int head) {
+  // elements [head, head + 4 * n_vec) are whole aligned vectors; the `head` elements before them and the rest after are scalar work
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  float* dst = dst_all + head;
+  ReducePtrs src;
+#pragma unroll
+  for (int j = 0; j < K; ++j) src.p[j] = src_all.p[j] + head;
   // main part: UNROLL vectors per trip, all loads first
   for (; i + (UNROLL - 1) * stride < n_vec; i += UNROLL * stride) {
     v4f v[UNROLL][K];
@@ -78,25 +83,27 @@ __global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restric
     for (int j = 0; j < K; ++j) v[j] = ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[j]) + i);
     __builtin_nontemporal_store(fold<MODE, K>(v), reinterpret_cast<v4f*>(dst) + i);
   }
-  // scalar tail (count not a multiple of 4, or the whole array when pointers are not 16-byte aligned)
-  for (int64_t e = n_vec * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += stride) {
+  // scalar work: the head, the tail, or the whole array when the pointers do not share one 16-byte phase
+  const int64_t left = count - n_vec * 4;
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < left; r += stride) {
+    const int64_t e = r < head ? r : r + n_vec * 4;
     float v[K];
 #pragma unroll
-    for (int j = 0; j < K; ++j) v[j] = src.p[j][e];
-    dst[e] = fold<MODE, K>(v);
+    for (int j = 0; j < K; ++j) v[j] = src_all.p[j][e];
+    dst_all[e] = fold<MODE, K>(v);
   }
 }
 
 template <int K, int MODE>
-static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int blocks, hipStream_t s) {
+static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, int blocks, hipStream_t s) {
   constexpr int U = K <= 4 ? 4 : K <= 8 ? 2 : 1;
-  hipLaunchKernelGGL((reduce_kernel<K, U, true, MODE>), dim3(blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count);
+  hipLaunchKernelGGL((reduce_kernel<K, U, true, MODE>), dim3(blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count, head);
 }
 
 template <int MODE>
-static bool launch_mode(int k, float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int blocks, hipStream_t s) {
+static bool launch_mode(int k, float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, int blocks, hipStream_t s) {
   switch (k) {
-#define TOFU_CASE(K) case K: launch_k<K, MODE>(dst, src, n_vec, count, blocks, s); return true;
+#define TOFU_CASE(K) case K: launch_k<K, MODE>(dst, src, n_vec, count, head, blocks, s); return true;
     TOFU_CASE(1) TOFU_CASE(2) TOFU_CASE(3) TOFU_CASE(4) TOFU_CASE(5) TOFU_CASE(6) TOFU_CASE(7) TOFU_CASE(8)
     TOFU_CASE(9) TOFU_CASE(10) TOFU_CASE(11) TOFU_CASE(12) TOFU_CASE(13) TOFU_CASE(14) TOFU_CASE(15) TOFU_CASE(16)
 #undef TOFU_CASE
@@ -111,12 +118,17 @@ int launch_reduce(float* dst, const float* const* parts, int k, int64_t count, v
 int launch_reduce_mode(float* dst, const float* const* parts, int k, int64_t count, int mode, void* stream) {
   if (count == 0) return TOFU_OK;
   ReducePtrs src;
-  bool aligned = (reinterpret_cast<uintptr_t>(dst) & 15) == 0;
+  // vector path: every pointer has the same offset into a 16-byte line (a whole number of floats);
+  // the elements up to the next line start are done one by one
+  const uintptr_t phase = reinterpret_cast<uintptr_t>(dst) & 15;
+  bool aligned = phase % 4 == 0;
   for (int j = 0; j < kMaxReduceK; ++j) {
     src.p[j] = parts[j < k ? j : 0];
-    aligned = aligned && (reinterpret_cast<uintptr_t>(src.p[j]) & 15) == 0;
+    aligned = aligned && (reinterpret_cast<uintptr_t>(src.p[j]) & 15) == phase;
   }
-  const int64_t n_vec = aligned ? count / 4 : 0;
+  int head = aligned ? (int)((16 - phase) % 16 / 4) : 0;
+  if (head > count) head = (int)count;
+  const int64_t n_vec = aligned ? (count - head) / 4 : 0;
   // Enough resident lanes to cover HBM latency, few enough that every lane streams several vectors.
   int64_t work = n_vec > 0 ? n_vec : count;
   int64_t want = (work + kReduceThreads - 1) / kReduceThreads;
@@ -124,12 +136,12 @@ int launch_reduce_mode(float* dst, const float* const* parts, int k, int64_t cou
   hipStream_t s = static_cast<hipStream_t>(stream);
   bool ok = false;
   switch (mode) {
-    case 0: ok = launch_mode<0>(k, dst, src, n_vec, count, blocks, s); break;
-    case 1: ok = launch_mode<1>(k, dst, src, n_vec, count, blocks, s); break;
-    case 2: ok = launch_mode<2>(k, dst, src, n_vec, count, blocks, s); break;
-    case 3: ok = launch_mode<3>(k, dst, src, n_vec, count, blocks, s); break;
-    case 4: ok = launch_mode<4>(k, dst, src, n_vec, count, blocks, s); break;
-    case 5: ok = launch_mode<5>(k, dst, src, n_vec, count, blocks, s); break;
+    case 0: ok = launch_mode<0>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 1: ok = launch_mode<1>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 2: ok = launch_mode<2>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 3: ok = launch_mode<3>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 4: ok = launch_mode<4>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 5: ok = launch_mode<5>(k, dst, src, n_vec, count, head, blocks, s); break;
     default: break;
   }
   if (!ok) return fail(TOFU_ERR_INVALID_ARG, "k = %d outside [1,%d] or unknown reduction mode %d", k, kMaxReduceK, mode);
@@ -178,4 +190,22 @@ extern "C" int tofu_partition_reduce_ex(void* dst, const void* const* partials, 
   const bool tree = order == TOFU_ORDER_TREE;
   const int mode = reducer == TOFU_REDUCE_SUM ? (tree ? 1 : 0) : reducer == TOFU_REDUCE_PROD ? (tree ? 3 : 2) : reducer == TOFU_REDUCE_MAX ? 4 : 5;
   return launch_reduce_mode(static_cast<float*>(dst), reinterpret_cast<const float* const*>(partials), k, count, mode, hip_stream);
+}
+
+extern "C" int tofu_partition_reduce_scatter(void* dst, const void* const* partials, int32_t k, int64_t count, int32_t shares,
+                                             int32_t share, int32_t reducer, int32_t order, void* hip_stream) {
+  using namespace tofu;
+  if (reducer < TOFU_REDUCE_SUM || reducer > TOFU_REDUCE_PROD) return fail(TOFU_ERR_INVALID_ARG, "unknown reducer %d", (int)reducer);
+  if (order != TOFU_ORDER_LINEAR && order != TOFU_ORDER_TREE) return fail(TOFU_ERR_INVALID_ARG, "unknown reduction order %d", (int)order);
+  int rc = check_reduce_args(dst, partials, k, count);
+  if (rc) return rc;
+  if (shares < 1 || share < 0 || share >= shares) return fail(TOFU_ERR_INVALID_ARG, "share %d of %d is not a valid share", (int)share, (int)shares);
+  // balanced cut of the flat index range, the same rule as for tensor dimensions; shares may be empty when count < shares
+  const int64_t lo = (int64_t)((__int128)share * count / shares), hi = (int64_t)((__int128)(share + 1) * count / shares);
+  if (hi == lo) return TOFU_OK;
+  const float* parts[kMaxReduceK];
+  for (int j = 0; j < k; ++j) parts[j] = static_cast<const float*>(partials[j]) + lo;
+  const bool tree = order == TOFU_ORDER_TREE;
+  const int mode = reducer == TOFU_REDUCE_SUM ? (tree ? 1 : 0) : reducer == TOFU_REDUCE_PROD ? (tree ? 3 : 2) : reducer == TOFU_REDUCE_MAX ? 4 : 5;
+  return launch_reduce_mode(static_cast<float*>(dst) + lo, parts, k, hi - lo, mode, hip_stream);
 }

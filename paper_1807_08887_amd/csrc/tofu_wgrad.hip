@@ -32,6 +32,7 @@ struct WgradArgs {
   const float* x;    // element at the low corner of the (clipped) input box
   const float* dy;   // element (n_lo, co_lo, 0, 0)
   float* out;        // dw element (co_lo, ci_lo, 0, 0)
+  int accumulate;    // 1: the shard's sum is added to what the output box holds
   float* slots;      // workspace: [groups * max_segments] partial tiles of kSlotFloats floats
   int64_t xs[4], ds[4], os[4];   // element strides: x (n,c,h,w), dy (n,co,h,w), out (co,ci,kh,kw)
   uint32_t x_bytes, dy_bytes;    // bytes spanned by the two input boxes (buffer bounds, fast path)
@@ -348,8 +349,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int co = m0 + wave * 32 + acc_row(v, half);
-        if (co < p.CO && ci < p.CI)
-          p.out[(int64_t)co * p.os[0] + (int64_t)ci * p.os[1] + (tap / 3) * p.os[2] + (tap % 3) * p.os[3]] = acc[tap][v];
+        if (co < p.CO && ci < p.CI) {
+          float* o = p.out + (int64_t)co * p.os[0] + (int64_t)ci * p.os[1] + (tap / 3) * p.os[2] + (tap % 3) * p.os[3];
+          *o = p.accumulate ? *o + acc[tap][v] : acc[tap][v];
+        }
       }
   }
   __syncthreads();   // the next segment's prologue overwrites LDS buffer 0
@@ -357,11 +360,11 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 }
 
 // Sums every tile's segments (one to a few workspace slots) in workgroup order and writes
-// dw[co][ci][kh][kw].  One thread per (co, ci): its nine reads per slot are coalesced
+// dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine reads per slot are coalesced
 // across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
 __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
                                                                  const float* __restrict__ slots, int groups, int max_segments, int NB,
-                                                                 int tiles_m, int tiles_n, int CO, int CI) {
+                                                                 int tiles_m, int tiles_n, int CO, int CI, int accumulate) {
   constexpr int BM = 128, BCI = 32;
   const int64_t n_units = (int64_t)tiles_m * tiles_n * NB;
   const int64_t items = (int64_t)tiles_m * tiles_n * BM * BCI;
@@ -383,7 +386,10 @@ __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restric
       for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
     }
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) dw[co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw] = acc[tap];
+    for (int tap = 0; tap < 9; ++tap) {
+      float* o = dw + co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw;
+      *o = accumulate ? *o + acc[tap] : acc[tap];
+    }
   }
 }
 
@@ -413,12 +419,9 @@ size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb) {
   return groups == tiles ? 0 : (size_t)groups * max_segments * kSlotFloats * sizeof(float);
 }
 
-}  // namespace tofu
-
-extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
-                                       const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw, void* workspace,
-                                       size_t workspace_bytes, void* hip_stream) {
-  using namespace tofu;
+static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
+                       const tofu_tensor_t* dy, const tofu_tensor_t* dw, void* workspace, size_t workspace_bytes, void* hip_stream,
+                       bool accumulate) {
   if (!op || op->kind != TOFU_OP_CONV2D_WGRAD) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv2d weight gradient");
   tofu_region_t out_box, in_boxes[2];
   int64_t pad_lo[2], pad_hi[2];
@@ -483,6 +486,7 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
   p.groups = groups;
   p.max_segments = max_segments;
   p.out = dw_out;
+  p.accumulate = accumulate ? 1 : 0;
   p.slots = static_cast<float*>(workspace);
   const size_t need = wgrad_workspace_bytes(CO, CI, NB);
   if (need > 0 && (!workspace || workspace_bytes < need))
@@ -519,9 +523,23 @@ extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_spli
     const int64_t items = (int64_t)p.tiles_m * p.tiles_n * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
     hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
-                       static_cast<const float*>(workspace), groups, max_segments, (int)NB, p.tiles_m, p.tiles_n, (int)CO, (int)CI);
+                       static_cast<const float*>(workspace), groups, max_segments, (int)NB, p.tiles_m, p.tiles_n, (int)CO, (int)CI, accumulate ? 1 : 0);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient segment sum launch failed: %s", hipGetErrorString(e));
   }
   return TOFU_OK;
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                       const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_wgrad(op, splits, nsplits, x, dy, dw, workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" int tofu_shard_conv2d_wgrad_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                                  const tofu_tensor_t* x, const tofu_tensor_t* dy, const tofu_tensor_t* dw,
+                                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_wgrad(op, splits, nsplits, x, dy, dw, workspace, workspace_bytes, hip_stream, true);
 }

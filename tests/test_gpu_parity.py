@@ -719,3 +719,153 @@ def test_probes_copy_exactly_and_leave_the_sink_alone():
     tofu.probe_mfma(sink, 16, 8)
     torch.cuda.synchronize()
     assert (sink == 3.0).all()
+
+
+# ----------------------------------------------------------------------------- reduce-scatter share, fused accumulation
+@pytest.mark.parametrize("count,shares", [(4 * 1000, 4), (10007, 3), (37, 8), (5, 8), ((1 << 20) + 3, 7)])
+def test_reduce_scatter_shares_reproduce_the_whole_reduction(count, shares):
+    """Every share writes only its range; all shares together equal tofu_partition_reduce_ex bit for bit
+    (odd range starts exercise the kernel's scalar head before the aligned vectors)."""
+    k = 5
+    parts = [synth.normal(91, j, (count,), 1.0) for j in range(k)]
+    d = [dev(p) for p in parts]
+    for reducer, order, name in [(tofu.REDUCE_SUM, tofu.ORDER_LINEAR, "sum"), (tofu.REDUCE_SUM, tofu.ORDER_TREE, "sum"),
+                                 (tofu.REDUCE_MAX, tofu.ORDER_LINEAR, "max")]:
+        whole = torch.empty(count, dtype=torch.float32, device=DEV)
+        tofu.partition_reduce(whole, d, reducer=reducer, order=order)
+        out = torch.full((count,), float("nan"), dtype=torch.float32, device=DEV)
+        for s in range(shares):
+            before = out.clone()
+            tofu.partition_reduce_scatter(out, d, shares, s, reducer=reducer, order=order)
+            lo, hi = (s * count) // shares, ((s + 1) * count) // shares
+            changed = (out != before) & ~(torch.isnan(out) & torch.isnan(before))
+            idx = torch.nonzero(changed).flatten()
+            assert idx.numel() == hi - lo and (idx.numel() == 0 or (int(idx.min()) == lo and int(idx.max()) == hi - 1)), (s, lo, hi)
+        assert torch.equal(out, whole)
+        val, absum = oracle.reduce_op(parts, name)
+        if name == "sum":
+            assert_close(out.cpu().numpy(), val, absum, "reduce-scatter sum")
+        else:
+            assert np.array_equal(out.cpu().numpy().astype(np.float64), val)
+    # in place on partials[0]: share 1 of 3 only
+    d0 = d[0].clone()
+    tofu.partition_reduce_scatter(d0, [d0] + d[1:], 3, 1)
+    lo, hi = count // 3, (2 * count) // 3
+    ref = torch.empty(count, dtype=torch.float32, device=DEV)
+    tofu.partition_reduce(ref, d)
+    assert torch.equal(d0[lo:hi], ref[lo:hi]) and torch.equal(d0[:lo], d[0][:lo]) and torch.equal(d0[hi:], d[0][hi:])
+
+
+def test_reduce_pointers_sharing_a_misalignment_take_the_vector_path_and_stay_exact():
+    n = 70001
+    parts = [synth.normal(92, j, (n + 3,), 2.0) for j in range(3)]
+    d = [dev(p) for p in parts]
+    for off in (1, 2, 3):
+        out = torch.full((n + 3,), float("nan"), dtype=torch.float32, device=DEV)
+        tofu.partition_reduce(out[off:off + n], [p[off:off + n] for p in d])
+        val, absum = oracle.reduce([p[off:off + n] for p in parts])
+        got = out.cpu().numpy()
+        assert np.isnan(got[:off]).all() and np.isnan(got[off + n:]).all()
+        assert_close(got[off:off + n], val, absum, f"reduce at offset {off}")
+        # mixed phases fall back to element work and give the same bits
+        out2 = torch.empty(n, dtype=torch.float32, device=DEV)
+        tofu.partition_reduce(out2, [p[off:off + n].clone() if j else p[off:off + n] for j, p in enumerate(d)])
+        assert torch.equal(out2, out[off:off + n])
+
+
+def _accumulated(k, first, rest, out):
+    """Shard 0 through the plain call, shards 1..k-1 through the accumulate call, all into `out`."""
+    first(0, out)
+    for s in range(1, k):
+        rest(s, out)
+    return out
+
+
+@pytest.mark.parametrize("M,N,K,k", [(72, 136, 200, 4), (128, 256, 8192, 2), (33, 65, 1030, 3)])
+def test_matmul_accumulate_equals_partials_then_reduce(M, N, K, k):
+    """K-split shards added into one buffer == k partial buffers + left-to-right reduce, bit for bit
+    (with and without the kernel's own K slices), and within tolerance of the oracle."""
+    A = synth.normal(93, 0, (M, K), 1.0); B = synth.normal(93, 1, (K, N), 1.0)
+    dA, dB = dev(A), dev(B)
+    op = tofu.matmul_desc(M, N, K)
+    tA, tB = tofu.tensor(dA), tofu.tensor(dB)
+    parts = []
+    for s in range(k):
+        sp = [(tofu.MM_DIM_K, k, s)]
+        C = torch.empty((M, N), dtype=torch.float32, device=DEV)
+        tofu.shard_matmul(op, sp, tA, tB, tofu.tensor(C), workspace(op, sp))
+        parts.append(C)
+    want = torch.empty_like(parts[0])
+    tofu.partition_reduce(want, parts)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    for s in range(k):
+        sp = [(tofu.MM_DIM_K, k, s)]
+        (tofu.shard_matmul if s == 0 else tofu.shard_matmul_accumulate)(op, sp, tA, tB, tofu.tensor(out), workspace(op, sp))
+    assert torch.equal(out, want)
+    val, absum = oracle.matmul_box(A, B)
+    assert_close(out.cpu().numpy(), val, absum, "accumulated K split")
+    # an output block of a larger, strided buffer: only the box is touched, and it is added to
+    big = torch.full((M + 2, N + 5), 3.0, dtype=torch.float32, device=DEV)
+    view = big[1:M + 1, 2:N + 2]
+    tofu.shard_matmul_accumulate(op, [], tA, tB, tofu.tensor(view), workspace(op, []))
+    whole = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    tofu.shard_matmul(op, [], tA, tB, tofu.tensor(whole), workspace(op, []))
+    assert torch.equal(view, whole + 3.0)
+    edge = big.clone(); edge[1:M + 1, 2:N + 2] = 3.0
+    assert torch.equal(edge, torch.full_like(big, 3.0))
+
+
+def test_conv_family_accumulate_equals_partials_then_reduce():
+    """The three convolution operators with their reduction index split: accumulate == partials + reduce."""
+    batch, c_in, c_out, H, W = 6, 40, 70, 12, 10
+    x = synth.normal(94, 0, (batch, c_in, H, W), 1.0)
+    w = synth.normal(94, 1, (c_out, c_in, 3, 3), 0.1)
+    dy = synth.normal(94, 2, (batch, c_out, H, W), 1.0)
+    dx_, dw_, ddy = dev(x), dev(w), dev(dy)
+    cases = [
+        ("conv2d CI split", tofu.conv2d_desc(batch, c_in, c_out, H, W), tofu.CONV_DIM_CI, 4, (dx_, dw_), (batch, c_out, H, W),
+         tofu.shard_conv2d, tofu.shard_conv2d_accumulate, lambda: oracle.conv2d_box(x, w, pad=1)),
+        ("wgrad N split", tofu.wgrad_desc(batch, c_in, c_out, H, W), tofu.WGRAD_DIM_N, 3, (dx_, ddy), (c_out, c_in, 3, 3),
+         tofu.shard_conv2d_wgrad, tofu.shard_conv2d_wgrad_accumulate, lambda: oracle.wgrad_box(x, dy, 3, 3, pad=1)),
+        ("dgrad CO split", tofu.dgrad_desc(batch, c_in, c_out, H, W), tofu.DGRAD_DIM_CO, 5, (ddy, dw_), (batch, c_in, H, W),
+         tofu.shard_conv2d_dgrad, tofu.shard_conv2d_dgrad_accumulate, lambda: oracle.dgrad_box(dy, w, H, W, pad=1)),
+    ]
+    for name, op, dim, k, (a, b), shape, plain, acc, ref in cases:
+        ta, tb = tofu.tensor(a), tofu.tensor(b)
+        parts = []
+        for s in range(k):
+            o = torch.empty(shape, dtype=torch.float32, device=DEV)
+            plain(op, [(dim, k, s)], ta, tb, tofu.tensor(o), workspace(op, [(dim, k, s)]))
+            parts.append(o)
+        want = torch.empty_like(parts[0])
+        tofu.partition_reduce(want, parts)
+        out = torch.full(shape, float("nan"), dtype=torch.float32, device=DEV)
+        for s in range(k):
+            (plain if s == 0 else acc)(op, [(dim, k, s)], ta, tb, tofu.tensor(out), workspace(op, [(dim, k, s)]))
+        assert torch.equal(out, want), name
+        val, absum = ref()
+        assert_close(out.cpu().numpy(), val, absum, name)
+
+
+def test_wgrad_accumulate_through_workspace_segments():
+    """A batch-split weight gradient whose tiles are summed from workspace segments adds to dw after the segment sum."""
+    co, ci, nb = 256, 96, 8
+    opd = dict(batch=nb, c_in=ci, c_out=co, H=14, W=14, pad=1)
+    x = synth.normal(95, 0, (nb, ci, 14, 14), 1.0)
+    dy = synth.normal(95, 1, (nb, co, 14, 14), 1.0)
+    op = tofu.wgrad_desc(nb, ci, co, 14, 14)
+    assert tofu.workspace_bytes(op, [(tofu.WGRAD_DIM_N, 2, 0)]) > 0
+    d_x, d_dy = dev(x), dev(dy)          # the descriptors hold addresses only: keep the buffers alive
+    tx, tdy = tofu.tensor(d_x), tofu.tensor(d_dy)
+    parts = []
+    for s in range(2):
+        o = torch.empty((co, ci, 3, 3), dtype=torch.float32, device=DEV)
+        tofu.shard_conv2d_wgrad(op, [(tofu.WGRAD_DIM_N, 2, s)], tx, tdy, tofu.tensor(o), workspace(op, [(tofu.WGRAD_DIM_N, 2, s)]))
+        parts.append(o)
+    out = parts[0].clone()
+    tofu.shard_conv2d_wgrad_accumulate(op, [(tofu.WGRAD_DIM_N, 2, 1)], tx, tdy, tofu.tensor(out), workspace(op, [(tofu.WGRAD_DIM_N, 2, 1)]))
+    want = torch.empty_like(out)
+    tofu.partition_reduce(want, parts)
+    assert torch.equal(out, want)
+    val, absum = oracle.wgrad_box(x, dy, 3, 3, pad=1)
+    assert_close(out.cpu().numpy(), val, absum, "accumulated wgrad")

@@ -44,7 +44,8 @@ def _check_reduce(leg):
 
 
 @pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_dx_nsplit", "gemm_dw_nsplit"), ("gemm_ksplit", "reduce_gates"),
-                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",), ("lstm_cell_nsplit",)])
+                                   ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",), ("lstm_cell_nsplit",),
+                                   ("gemm_ksplit_accumulate",), ("wgrad_batch_accumulate",)])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)
     legs = tofu_workloads.build("cuda:0", group)

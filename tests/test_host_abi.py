@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
     assert {"tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad",
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
             "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_tdl_regions", "tofu_tdl_symbolic", "tofu_tdl_from_op",
-            "tofu_tdl_fetch_elements", "tofu_shard_lstm_cell"} <= names
+            "tofu_tdl_fetch_elements", "tofu_shard_lstm_cell", "tofu_partition_reduce_scatter", "tofu_shard_matmul_accumulate",
+            "tofu_shard_conv2d_accumulate", "tofu_shard_conv2d_wgrad_accumulate", "tofu_shard_conv2d_dgrad_accumulate"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
@@ -263,6 +264,39 @@ def test_reduce_error_paths_are_checked_on_the_host():
     assert ex(C.c_void_p(FAKE + (1 << 20)), ptrs, 17, 16, 1, 0, None) == -1
     assert ex(C.c_void_p(FAKE + 4096 + 8), ptrs, 2, 16, 3, 1, None) == -1       # overlaps partials[1]
     assert ex(None, ptrs, 2, 0, 1, 1, None) == 0
+    sc = lib.tofu_partition_reduce_scatter
+    sc.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+    dst = C.c_void_p(FAKE + (1 << 20))
+    assert sc(dst, ptrs, 2, 16, 0, 0, 0, 0, None) == -1       # no shares
+    assert sc(dst, ptrs, 2, 16, 4, 4, 0, 0, None) == -1       # share outside [0, shares)
+    assert sc(dst, ptrs, 2, 16, 4, -1, 0, 0, None) == -1
+    assert sc(dst, ptrs, 2, 16, 4, 0, 9, 0, None) == -1       # unknown reducer
+    assert sc(dst, ptrs, 17, 16, 4, 0, 0, 0, None) == -1
+    assert sc(C.c_void_p(FAKE + 4096 + 8), ptrs, 2, 16, 4, 0, 0, 0, None) == -1   # overlap is judged on the full arrays
+    assert sc(dst, ptrs, 2, 3, 8, 0, 0, 0, None) == 0         # floor(0*3/8) = floor(1*3/8): an empty share launches nothing
+    assert sc(dst, ptrs, 2, 0, 8, 3, 0, 0, None) == 0
+
+
+def test_accumulate_calls_check_their_arguments_like_the_plain_calls():
+    mm = tofu.matmul_desc(64, 96, 128)
+    A, B, Cc = _t([(0, 64), (0, 128)]), _t([(0, 128), (0, 96)], FAKE + (1 << 20)), _t([(0, 64), (0, 96)], FAKE + (2 << 20))
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_matmul_accumulate(mm, [(tofu.MM_DIM_K, 2, 1)], A, _t([(0, 64), (0, 96)], FAKE + (1 << 20)), Cc, stream=0)
+    assert e.value.status == -2
+    for call in (tofu.shard_conv2d_accumulate, tofu.shard_conv2d_wgrad_accumulate, tofu.shard_conv2d_dgrad_accumulate):
+        with pytest.raises(tofu.TofuError) as e:  # wrong operator kind for the entry point
+            call(mm, [], A, B, Cc, stream=0)
+        assert e.value.status == -1
+    big = tofu.matmul_desc(128, 4096, 16384)
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_matmul_accumulate(big, [], _t([(0, 128), (0, 16384)]), _t([(0, 16384), (0, 4096)], FAKE + (1 << 30)),
+                                     _t([(0, 128), (0, 4096)], FAKE + (2 << 30)), stream=0)
+    assert e.value.status == -5
+    wg = tofu.wgrad_desc(16, 64, 64, 8, 8)
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_conv2d_wgrad_accumulate(wg, [], _t([(0, 16), (0, 64), (0, 8), (0, 8)]), _t([(0, 16), (0, 64), (0, 8), (0, 8)], FAKE + (1 << 20)),
+                                           _t([(0, 64), (0, 64), (0, 3), (0, 3)], FAKE + (2 << 20)), stream=0)
+    assert e.value.status == -5
 
 
 def test_probe_error_paths_are_checked_on_the_host():

@@ -14,6 +14,8 @@ Builds, from the seeded generator, the device buffers of the four large workload
   dgrad_cout         (extra) backward of conv_cout: partial dx from the worker's C_out/8 block of dy and of the filters
   gemm_dx_nsplit     (extra) backward of the N-split gate GEMM: partial dX = dY_s . W_s^T, W_s read transposed in place
   gemm_dw_nsplit     (extra) backward of the N-split gate GEMM: dW_s = X^T . dY_s, X read transposed in place
+  gemm_ksplit_accumulate, wgrad_batch_accumulate  (extra) the two Case-2 shards adding into a resident full-size buffer
+                     instead of writing a partial (out = out + shard; the buffer starts at zero)
   wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
   reduce_dw     that partial + 7 remote partials -> dW                           (partition-n-reduce)
 
@@ -63,7 +65,8 @@ def _ws(op, splits, dev):
 
 STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
 # variants and backward operators outside the step, built only when named
-EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout", "lstm_cell_nsplit")
+EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout", "lstm_cell_nsplit", "gemm_ksplit_accumulate",
+              "wgrad_batch_accumulate")
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -73,7 +76,8 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
     up = lambda a: torch.from_numpy(a).to(dev)
 
     # ------------------------------------------------------------------ LSTM gate GEMM
-    if want("gemm_nsplit", "gemm_ksplit", "reduce_gates"):
+    extra = lambda name: which is not None and name in which
+    if want("gemm_nsplit", "gemm_ksplit", "reduce_gates") or extra("gemm_ksplit_accumulate"):
         M, N, K, k = 128, 32768, 16384, 8
         op = tofu.matmul_desc(M, N, K)
     if want("gemm_nsplit"):
@@ -135,7 +139,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                         _call(tofu.shard_lstm_cell, opl, spl, tofu.tensor(d_g, [0, h0, 0]), tofu.tensor(d_c, [0, h0]),
                               tofu.tensor(c_new, [0, h0]), tofu.tensor(h_new, [0, h0])), c_new,
                         dict(kind="lstm", gates=g_s, c=c_s, h_out=h_new, keep=(d_g, d_c, h_new)) if keep_host else dict(keep=(d_g, d_c, h_new))))
-    if want("gemm_ksplit", "reduce_gates"):
+    if want("gemm_ksplit", "reduce_gates") or extra("gemm_ksplit_accumulate"):
         cfg = synth.CONFIGS["lstm_gates_ksplit"]
         s = cfg["shard"]
         splits = [(tofu.MM_DIM_K, k, s)]
@@ -147,9 +151,13 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         part = torch.zeros(M, N, dtype=torch.float32, device=dev)
         ws = _ws(op, splits, dev)
         tA, tB, tC = tofu.tensor(dX), tofu.tensor(dW, [k0, 0]), tofu.tensor(part)   # X is read strided, in place
-        legs.append(Leg("gemm_ksplit", "mfma", 2.0 * M * N * (k1 - k0),
-                        _call(tofu.shard_matmul, op, splits, tA, tB, tC, ws), part,
-                        dict(kind="matmul", A=X, B=Wr, box=reg["out_box"], krange=(k0, k1), b_row0=k0, keep=(dX, dW, ws)) if keep_host else dict(keep=(dX, dW, ws))))
+        host_k = dict(kind="matmul", A=X, B=Wr, box=reg["out_box"], krange=(k0, k1), b_row0=k0, keep=(dX, dW, ws)) if keep_host else dict(keep=(dX, dW, ws))
+        if want("gemm_ksplit", "reduce_gates"):
+            legs.append(Leg("gemm_ksplit", "mfma", 2.0 * M * N * (k1 - k0), _call(tofu.shard_matmul, op, splits, tA, tB, tC, ws), part, host_k))
+        if extra("gemm_ksplit_accumulate"):
+            total = torch.zeros(M, N, dtype=torch.float32, device=dev)
+            legs.append(Leg("gemm_ksplit_accumulate", "mfma", 2.0 * M * N * (k1 - k0),
+                            _call(tofu.shard_matmul_accumulate, op, splits, tA, tB, tofu.tensor(total), ws), total, host_k))
         if want("reduce_gates"):
             remote = [synth.normal(cfg["seed"], 10 + j, (M, N), cfg["partial_std"]) for j in range(k - 1)]
             d_remote = [up(r) for r in remote]
@@ -160,7 +168,6 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                             dict(kind="reduce", remote=remote, own_index=s, own=part, keep=order) if keep_host else dict(keep=order)))
 
     # ------------------------------------------------------------------ Wide-ResNet conv forward
-    extra = lambda name: which is not None and name in which
     if want("conv_cout", "fetch_halo", "conv_cout_h") or extra("conv_cout_h_fused"):
         cfg = synth.CONFIGS["wresnet_conv_fwd"]
         NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
@@ -236,7 +243,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                         conventional_flop=2.0 * NB * C * (co1 - co0) * 9 * H * W))
 
     # ------------------------------------------------------------------ Wide-ResNet conv weight gradient
-    if want("wgrad_batch", "reduce_dw"):
+    if want("wgrad_batch", "reduce_dw") or extra("wgrad_batch_accumulate"):
         cfg = synth.CONFIGS["wresnet_conv_wgrad"]
         NB, C, H, W, k, s = cfg["batch"], cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["shard"]
         opw = tofu.wgrad_desc(NB, C, C, H, W)
@@ -250,10 +257,16 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         wsw = _ws(opw, splits_w, dev)
         txw, tdy, tdw = tofu.tensor(dxs, [n0, 0, 0, 0]), tofu.tensor(ddys, [n0, 0, 0, 0]), tofu.tensor(part_w)
         taps = _conv_valid_taps(0, H, 0, W, H, W)
-        legs.append(Leg("wgrad_batch", "mfma", 2.0 * (n1 - n0) * C * C * taps,
-                        _call(tofu.shard_conv2d_wgrad, opw, splits_w, txw, tdy, tdw, wsw), part_w,
-                        dict(kind="wgrad", x=xs_, dy=dys, n0=n0, keep=(dxs, ddys, wsw)) if keep_host else dict(keep=(dxs, ddys, wsw)),
-                        conventional_flop=2.0 * (n1 - n0) * C * C * 9 * H * W))
+        host_w = dict(kind="wgrad", x=xs_, dy=dys, n0=n0, keep=(dxs, ddys, wsw)) if keep_host else dict(keep=(dxs, ddys, wsw))
+        if want("wgrad_batch", "reduce_dw"):
+            legs.append(Leg("wgrad_batch", "mfma", 2.0 * (n1 - n0) * C * C * taps,
+                            _call(tofu.shard_conv2d_wgrad, opw, splits_w, txw, tdy, tdw, wsw), part_w, host_w,
+                            conventional_flop=2.0 * (n1 - n0) * C * C * 9 * H * W))
+        if extra("wgrad_batch_accumulate"):
+            total_w = torch.zeros(C, C, 3, 3, dtype=torch.float32, device=dev)
+            legs.append(Leg("wgrad_batch_accumulate", "mfma", 2.0 * (n1 - n0) * C * C * taps,
+                            _call(tofu.shard_conv2d_wgrad_accumulate, opw, splits_w, txw, tdy, tofu.tensor(total_w), wsw), total_w, host_w,
+                            conventional_flop=2.0 * (n1 - n0) * C * C * 9 * H * W))
         if want("reduce_dw"):
             remote = [synth.normal(cfg["seed"], 10 + j, (C, C, 3, 3), cfg["partial_std"]) for j in range(k - 1)]
             d_remote = [up(r) for r in remote]
