@@ -19,7 +19,7 @@ FAKE = 0x7F0000000000        # a non-null "device pointer"; nothing below ever d
 def test_library_exports_every_declared_symbol():
     import glob
     headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
-    assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_probe.h", "tofu_tdl.h"]
+    assert [os.path.basename(h) for h in headers] == ["tofu.h", "tofu_plan.h", "tofu_probe.h", "tofu_tdl.h"]
     names = set()
     for h in headers:
         names |= set(re.findall(r"^(?:int|size_t|const char\*)\s+(tofu_[a-z0-9_]+)\s*\(", open(h).read(), flags=re.M))
@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
             "tofu_partition_reduce", "tofu_shard_range", "tofu_op_regions", "tofu_workspace_bytes",
             "tofu_last_error", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_tdl_regions", "tofu_tdl_symbolic", "tofu_tdl_from_op",
             "tofu_tdl_fetch_elements", "tofu_shard_lstm_cell", "tofu_partition_reduce_scatter", "tofu_shard_matmul_accumulate",
-            "tofu_shard_conv2d_accumulate", "tofu_shard_conv2d_wgrad_accumulate", "tofu_shard_conv2d_dgrad_accumulate"} <= names
+            "tofu_shard_conv2d_accumulate", "tofu_shard_conv2d_wgrad_accumulate", "tofu_shard_conv2d_dgrad_accumulate",
+            "tofu_plan_strategy_cost", "tofu_plan_cost", "tofu_plan_basic", "tofu_plan_recursive"} <= names
     lib = ctypes.CDLL(tofu.lib_path())
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
