@@ -34,6 +34,7 @@ LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced> + conv2d_seg
                "gemm_ksplit": "matmul_kernel<128,64,32,2,2>", "gemm_nsplit": "matmul_kernel<128,64,32,2,2> + slice_sum_kernel"}
 EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
                "gemm_ksplit_accumulate": "gemm_ksplit adding into a resident [128,32768] buffer (reduction fused into the epilogue)",
+               "conv1d_cout": "the paper's conv1d (Fig. 1): 2048 channels, window 3, 512 outputs per row, batch 64, C_out/8 shard; filters [ci][co][dx] re-ordered inside the call",
                "wgrad_batch_accumulate": "wgrad_batch adding into a resident dW (reduction fused into the segment sum)",
                "lstm_cell_nsplit": "element-wise LSTM cell update on the N-split worker's 128 x 1024 hidden units (3.7 MB: launch-bound)",
                "dgrad_cout": "backward of conv_cout: partial dx[128,2560,14,14] from the C_out/8 blocks of dy and the filters (filter reversal included)",

@@ -82,8 +82,12 @@ typedef enum {
   TOFU_OP_CONV2D_WGRAD = 2,         /* dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] x[n,ci,h*s+kh-p,w*s+kw-p]  */
   TOFU_OP_CONV2D_DGRAD = 3,         /* dx[n,ci,ih,iw]  = sum_{co,kh,kw} dy[n,co,h,w] w[co,ci,kh,kw] over the
                                        (h,w) with h*s+kh-p = ih, w*s+kw-p = iw                               */
-  TOFU_OP_LSTM_CELL = 4             /* element-wise over (b,h): c' = sig(f) c + sig(i) tanh(g), h' = sig(o) tanh(c')
+  TOFU_OP_LSTM_CELL = 4,            /* element-wise over (b,h): c' = sig(f) c + sig(i) tanh(g), h' = sig(o) tanh(c')
                                        with (i,f,g,o) = gates[b,h,0..3]; shapes: batch = M, hidden units = N  */
+  TOFU_OP_CONV1D = 5                /* the paper's running example (Fig. 1 and 3):
+                                       out[b,co,x] = sum_{ci,dx} data[b,ci,x+dx] filters[ci,co,dx]; data is
+                                       [batch, c_in, W], filters [c_in, c_out, KW], out [batch, c_out, W-KW+1];
+                                       no padding, no stride (H, KH, stride, pad are not read)               */
 } tofu_op_kind_t;
 
 /* Iteration dimensions a split may name.  Output dimensions give Case-1
@@ -97,6 +101,10 @@ enum { TOFU_LSTM_DIM_B = 0, TOFU_LSTM_DIM_H = 1 };   /* element-wise: no reducti
 /* data gradient: H and W are the rows / columns of dx, i.e. of the forward INPUT */
 enum { TOFU_DGRAD_DIM_N = 0, TOFU_DGRAD_DIM_CI = 1, TOFU_DGRAD_DIM_H = 2, TOFU_DGRAD_DIM_W = 3,
        TOFU_DGRAD_DIM_CO = 4 /* reduction */ };
+
+/* conv1d: an X split reads a window-widened range of data (never padding: the data tensor is
+ * longer than the output by KW - 1) */
+enum { TOFU_CONV1D_DIM_B = 0, TOFU_CONV1D_DIM_CO = 1, TOFU_CONV1D_DIM_X = 2, TOFU_CONV1D_DIM_CI = 3 /* reduction */ };
 
 /* Operator description with the shapes of the UNPARTITIONED operator. */
 typedef struct {
@@ -213,6 +221,27 @@ int tofu_shard_conv2d_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits
 int tofu_shard_conv2d_dgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                             const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Shard of the paper's running example, the 1-D convolution of Fig. 1 / Fig. 3:
+ *   out[b,co,x] = sum_{ci,dx} data[b,ci,x+dx] * filters[ci,co,dx]
+ * op->kind = TOFU_OP_CONV1D with batch, c_in, c_out, W (length of data) and KW (window); splits
+ * name TOFU_CONV1D_DIM_B / _CO / _X (Case-1; an X split reads its output range widened by the
+ * window, Sec. 4.2) or _CI (Case-2: out receives a full-size partial).
+ *   data    [batch, c_in, W]        filters [c_in, c_out, KW]  (the index order of Fig. 1)
+ *   out     [batch, c_out, W-KW+1]
+ * all addressed by global coordinate through their extents and strides.  Implemented for
+ * KW = 3 -> otherwise UNSUPPORTED.  Filters whose memory order is [c_out][c_in][KW] (strides
+ * (3, 3*n, 1) with n a multiple of 4, 16-byte aligned) are read in place; any other layout is
+ * first re-ordered into the workspace.  The shard's X range is cut into equal chunks of at most
+ * 272 columns; a range whose length has no suitable divisor (say a large prime) is UNSUPPORTED.
+ * tofu_workspace_bytes covers the re-ordered filters and the kernel's segment slots.  The
+ * _accumulate form adds to what the output box holds, like the other accumulate calls. */
+int tofu_shard_conv1d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                      const tofu_tensor_t* data, const tofu_tensor_t* filters, const tofu_tensor_t* out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+int tofu_shard_conv1d_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* data, const tofu_tensor_t* filters, const tofu_tensor_t* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* LSTM cell update that consumes the gate GEMM's output (the element-wise
  * stage of the layer; Sec. 5.1: consecutive element-wise operators are merged

@@ -53,7 +53,7 @@ typedef struct {
  * tofu_op_regions.  Variables (output indices | reduction variables):
  *   matmul   m, n | k                      conv2d   n, co, h, w | ci, kh, kw
  *   wgrad    co, ci, kh, kw | n, h, w      dgrad    n, ci, ih, iw | co, kh, kw
- *   lstm     b, h | gate
+ *   lstm     b, h | gate                   conv1d   b, co, x | ci, dx
  * so a TOFU_*_DIM_* name is the variable of the same position, except TOFU_WGRAD_DIM_N, which
  * is variable 4.  UNSUPPORTED for a data gradient with stride > 1 (its index is not affine in
  * integers). */

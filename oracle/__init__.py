@@ -6,5 +6,5 @@ never imports the product.  `regions` holds the integer range/region definitions
 fetch; `ops` wraps the fp64 loop nests of tofu_oracle.c.
 """
 from . import regions  # noqa: F401
-from .ops import (build, conv2d_box, conv2d_pts, dgrad_box, dgrad_pts, lstm_cell, matmul_box, matmul_pts, reduce, reduce_op, threads,  # noqa: F401
+from .ops import (build, conv1d_box, conv2d_box, conv2d_pts, dgrad_box, dgrad_pts, lstm_cell, matmul_box, matmul_pts, reduce, reduce_op, threads,  # noqa: F401
                   wgrad_box, wgrad_pts)

@@ -121,6 +121,23 @@ def conv2d_pts(x, w, pts, stride=1, pad=0, cirange=None):
     return v, s
 
 
+def conv1d_box(data, filters, box=None, cirange=None):
+    """Fig. 1's conv1d over box [(b),(co),(x)] (default all): data [B, CI, X + DX - 1], filters [CI, CO, DX]."""
+    data, pd = _f32(data); filters, pf = _f32(filters)
+    batch, c_in, L = data.shape
+    assert filters.shape[0] == c_in
+    c_out, DX = filters.shape[1], filters.shape[2]
+    X = L - DX + 1
+    box = box or ((0, batch), (0, c_out), (0, X))
+    shape = [b[1] - b[0] for b in box]
+    c0, c1 = cirange or (0, c_in)
+    lo = (ctypes.c_int64 * 3)(*[b[0] for b in box])
+    hi = (ctypes.c_int64 * 3)(*[b[1] for b in box])
+    v, s, pv, ps = _out(int(np.prod(shape)))
+    _load().oracle_conv1d_box(pd, pf, _i64(batch), _i64(c_in), _i64(c_out), _i64(X), _i64(DX), lo, hi, _i64(c0), _i64(c1), pv, ps)
+    return v.reshape(shape), s.reshape(shape)
+
+
 def wgrad_box(x, dy, KH, KW, stride=1, pad=0, box=None, nrange=None):
     """dw over box [(co),(ci),(kh),(kw)] (default all), summing n over nrange (default all)."""
     x, px = _f32(x); dy, pd = _f32(dy)

@@ -32,6 +32,7 @@ ITER_DIMS = {
     "conv2d_wgrad": (("CO", "CI"), ("N",)),
     "conv2d_dgrad": (("N", "CI", "H", "W"), ("CO",)),     # H, W: rows / columns of the forward INPUT
     "lstm_cell": (("B", "H"), ()),                          # element-wise over (batch, hidden unit)
+    "conv1d": (("B", "CO", "X"), ("CI",)),                  # Fig. 1: data [B, CI, X + DX - 1], filters [CI, CO, DX]
 }
 
 
@@ -52,6 +53,8 @@ def iteration_extents(op: dict) -> dict:
         return {"M": op["M"], "N": op["N"], "K": op["K"]}
     if kind == "lstm_cell":
         return {"B": op["batch"], "H": op["hidden"]}
+    if kind == "conv1d":
+        return {"B": op["batch"], "CO": op["c_out"], "X": op["W"] - op["KW"] + 1, "CI": op["c_in"]}
     ho = conv_out_size(op["H"], op["KH"], op["stride"], op["pad"])
     wo = conv_out_size(op["W"], op["KW"], op["stride"], op["pad"])
     if kind == "conv2d":
@@ -120,6 +123,10 @@ def op_regions(op: dict, splits):
         out_box = [r["CO"], r["CI"], (0, op["KH"]), (0, op["KW"])]
         in_boxes = [[r["N"], r["CI"], hbox, wbox],
                     [r["N"], r["CO"], (0, ho), (0, wo)]]
+    elif kind == "conv1d":        # data[b, ci, x + dx]: the x range widened by the window; the data tensor is that much longer
+        x0, x1 = r["X"]
+        out_box = [r["B"], r["CO"], r["X"]]
+        in_boxes = [[r["B"], r["CI"], (x0, x1 + op["KW"] - 1)], [r["CI"], r["CO"], (0, op["KW"])]]
     elif kind == "lstm_cell":     # element-wise: every input is read exactly where the output is written
         out_box = [r["B"], r["H"]]
         in_boxes = [[r["B"], r["H"], (0, 4)], [r["B"], r["H"]]]

@@ -117,6 +117,34 @@ void oracle_conv2d_pts(const float* x, const float* wt, i64 batch, i64 c_in, i64
     conv_elem(x, wt, &c, pts[4 * i], pts[4 * i + 1], pts[4 * i + 2], pts[4 * i + 3], ci0, ci1, &val[i], &absum[i]);
 }
 
+/* ---- 1-D convolution, the paper's running example (Fig. 1: the loop nest; Fig. 3: its
+ * description): out[b,co,x] = sum_{ci,dx} data[b,ci,x+dx] * filters[ci,co,dx].
+ * data is [batch, c_in, X + DX - 1], filters [c_in, c_out, DX], out [batch, c_out, X]: no
+ * padding and no stride; filters are indexed (ci, co, dx) as printed there.
+ * Box lo[3]..hi[3] over (b,co,x), ci summed over [ci0,ci1). */
+void oracle_conv1d_box(const float* data, const float* filters, i64 batch, i64 c_in, i64 c_out, i64 X, i64 DX,
+                       const i64* lo, const i64* hi, i64 ci0, i64 ci1, double* val, double* absum) {
+  (void)batch;
+  i64 L = X + DX - 1;
+  i64 d0 = hi[0] - lo[0], d1 = hi[1] - lo[1], d2 = hi[2] - lo[2];
+#pragma omp parallel for schedule(static)
+  for (i64 e = 0; e < d0 * d1 * d2; ++e) {
+    i64 r = e;
+    i64 x = lo[2] + r % d2; r /= d2;
+    i64 co = lo[1] + r % d1; r /= d1;
+    i64 b = lo[0] + r;
+    double acc = 0.0, as = 0.0;
+    for (i64 ci = ci0; ci < ci1; ++ci)
+      for (i64 dx = 0; dx < DX; ++dx) {
+        double p = (double)data[(b * c_in + ci) * L + x + dx] * (double)filters[(ci * c_out + co) * DX + dx];
+        acc += p;
+        as += fabs(p);
+      }
+    val[e] = acc;
+    absum[e] = as;
+  }
+}
+
 /* ---- weight gradient of that convolution ------------------------------------
  * dw[co,ci,kh,kw] = sum_{n,h,w} dy[n,co,h,w] * x[n,ci,h*s+kh-p,w*s+kw-p],
  * the derivative of sum(dy*y) with respect to wt[co,ci,kh,kw]. */

@@ -11,8 +11,9 @@ import os
 from typing import Optional, Sequence
 
 TOFU_MAX_DIMS = 6
-OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD, OP_LSTM_CELL = 0, 1, 2, 3, 4
+OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD, OP_LSTM_CELL, OP_CONV1D = 0, 1, 2, 3, 4, 5
 LSTM_DIM_B, LSTM_DIM_H = 0, 1
+CONV1D_DIM_B, CONV1D_DIM_CO, CONV1D_DIM_X, CONV1D_DIM_CI = 0, 1, 2, 3
 MM_DIM_M, MM_DIM_N, MM_DIM_K = 0, 1, 2
 CONV_DIM_N, CONV_DIM_CO, CONV_DIM_H, CONV_DIM_W, CONV_DIM_CI = 0, 1, 2, 3, 4
 WGRAD_DIM_CO, WGRAD_DIM_CI, WGRAD_DIM_N = 0, 1, 2
@@ -84,7 +85,7 @@ def load():
     lib.tofu_workspace_bytes.restype = sz
     lib.tofu_workspace_bytes.argtypes = [P(OpDesc), P(Split), i32]
     lib.tofu_region_fetch.argtypes = [P(Tensor), P(Tensor), i32, vp]
-    shard_calls = ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad", "tofu_shard_conv2d_dgrad")
+    shard_calls = ("tofu_shard_matmul", "tofu_shard_conv2d", "tofu_shard_conv2d_wgrad", "tofu_shard_conv2d_dgrad", "tofu_shard_conv1d")
     accumulate_calls = tuple(n + "_accumulate" for n in shard_calls)
     for name in shard_calls + accumulate_calls:
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
@@ -243,6 +244,22 @@ def shard_conv2d_wgrad_accumulate(op, splits, x: Tensor, dy: Tensor, dw: Tensor,
 
 def shard_conv2d_dgrad_accumulate(op, splits, dy: Tensor, w: Tensor, dx: Tensor, workspace=None, stream=None) -> None:
     _shard(load().tofu_shard_conv2d_dgrad_accumulate, op, splits, dy, w, dx, workspace, stream)
+
+
+def conv1d_desc(batch: int, c_in: int, c_out: int, length: int, window: int = 3) -> OpDesc:
+    """Fig. 1's conv1d: data [batch, c_in, length], filters [c_in, c_out, window], out [batch, c_out, length - window + 1]."""
+    d = OpDesc()
+    d.kind, d.batch, d.c_in, d.c_out, d.W, d.KW = OP_CONV1D, batch, c_in, c_out, length, window
+    d.H, d.KH, d.stride, d.pad = 1, 1, 1, 0
+    return d
+
+
+def shard_conv1d(op, splits, data: Tensor, filters: Tensor, out: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv1d, op, splits, data, filters, out, workspace, stream)
+
+
+def shard_conv1d_accumulate(op, splits, data: Tensor, filters: Tensor, out: Tensor, workspace=None, stream=None) -> None:
+    _shard(load().tofu_shard_conv1d_accumulate, op, splits, data, filters, out, workspace, stream)
 
 
 def shard_lstm_cell(op, splits, gates: Tensor, c_prev: Tensor, c_new: Tensor, h_new: Tensor, stream=None) -> None:

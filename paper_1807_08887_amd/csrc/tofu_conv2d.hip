@@ -74,24 +74,25 @@ struct ConvSources {
 // Lanes with nothing to read (zero border, idle staging slots) load from here in the multi-block kernels.
 __device__ float kZeroWords[64];
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, int KH = 3, int KW = 3>
 struct ConvCfg {
   static constexpr int kThreads = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
-  static constexpr int KK = CK * 9;            // GEMM-K per step
+  static constexpr int T = KH * KW;            // filter taps
+  static constexpr int KK = CK * T;            // GEMM-K per step
   static constexpr int LDM = BM + 1;           // Ws[kk][m]; odd pitch keeps the transposing writes spread over the banks
   static constexpr int WV = (BM * KK / 4 + kThreads - 1) / kThreads;   // weight vectors per thread per step
   // each LDS buffer ends with scratch floats that absorb the writes of idle staging slots
   static constexpr int WB = KK * LDM + 3 * LDM + 64;                   // floats per weight buffer
   static int xb(int PL) { return CK * PL + 64; }                       // floats per input buffer
-  static_assert(TM % 32 == 0 && TN % 32 == 0 && CK % 4 == 0, "bad tile");
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && CK % 4 == 0, "bad tile");   // CK % 4: KK holds whole vectors, channels pair up
   static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI, bool BALANCED>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI, bool BALANCED, int KH = 3, int KW = 3>
 __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources* srcs) {
-  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
-  constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV;
+  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ, KH, KW>;
+  constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV, T = Cfg::T;
   constexpr uint32_t kNone = kNoOffset;
   extern __shared__ float lds[];
   const int PL = p.PL, LDW = p.LDW;
@@ -143,13 +144,13 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   const int m0 = tile_m * BM;
   const int p_begin = tile_n * BN;
   const int p_end = min(p.P, p_begin + BN);
-  const int img_rows = p.BH + 2;              // padded rows per image in virtual-row order
+  const int img_rows = p.BH + KH - 1;         // window-widened rows per image in virtual-row order
   const int plane = p.BH * p.BW;
 
   // virtual rows staged by this tile
   const int ra = p_begin / p.BW, rb = (p_end - 1) / p.BW;
   const int T_a = (ra / p.BH) * img_rows + ra % p.BH;
-  const int T_b = (rb / p.BH) * img_rows + rb % p.BH + 2;
+  const int T_b = (rb / p.BH) * img_rows + rb % p.BH + KH - 1;
   const int E = (T_b - T_a + 1) * LDW;        // staged floats per channel for this tile
 
   // ---- per-thread staging lists, fixed for the whole K loop ----
@@ -221,7 +222,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
       }
     }
     if (p.w_fast && whole) {
-      const uint32_t w_soff = 36u * (uint32_t)ci0;
+      const uint32_t w_soff = 4u * T * (uint32_t)ci0;
 #pragma unroll
       for (int i = 0; i < WV; ++i) rw[i] = buf_load4(w_rsrc, w_voff[i], w_soff);
     } else {
@@ -230,7 +231,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
         const int idx = tid + i * NT, row = idx / (KK / 4), q = idx - row * (KK / 4);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-          const int kk = 4 * q + jj, ci_l = kk / 9, tap = kk - ci_l * 9, kh = tap / 3, kw = tap - kh * 3;
+          const int kk = 4 * q + jj, ci_l = kk / T, tap = kk - ci_l * T, kh = tap / KW, kw = tap - kh * KW;
           const bool ok = idx < BM * KK / 4 && m0 + row < p.CO && ci0 + ci_l < p.CI;
           rw[i][jj] = ok ? p.w[(int64_t)(m0 + row) * p.ws[0] + (int64_t)(ci0 + ci_l) * p.ws[1] + kh * p.ws[2] + kw * p.ws[3]] : 0.f;
         }
@@ -269,7 +270,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
     for (int j = 0; j < FN; ++j) acc[i][j] = acc_zero();
 
   const int steps = s_end - s_begin;
-  constexpr int KS = (CK / 2) * 9;            // MFMA k-steps per step: (channel pair, tap)
+  constexpr int KS = (CK / 2) * T;            // MFMA k-steps per step: (channel pair, tap)
   // Staging work of one step = XJ input items + WV weight items.  In a HOT step each item (write
   // last step's registers to LDS, then reload them for the step after next) is issued between
   // two k-steps of the MFMA stream, one item every STRIDE k-steps, so that no MFMA waits behind
@@ -291,18 +292,18 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   auto run_step = [&](int t, auto hot_tag) {
     constexpr bool HOT = decltype(hot_tag)::value;
     const int buf = t & 1;
-    const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * 9 * LDM;
+    const float* wsm = Ws + buf * WB + wm * Cfg::TM + l32 + half * T * LDM;
     const float* xs = Xs + buf * XB;
     float* xs_next = Xs + (buf ^ 1) * XB;
     float* ws_next = Ws + (buf ^ 1) * WB;
     const int nxt = min(t + 2, steps - 1), nxt_abs = s_begin + nxt;
-    const uint32_t x_soff = MULTI ? 0u : 4u * (uint32_t)((int64_t)nxt_abs * CK * p.xs[1]), w_soff = 36u * (uint32_t)(nxt_abs * CK);
+    const uint32_t x_soff = MULTI ? 0u : 4u * (uint32_t)((int64_t)nxt_abs * CK * p.xs[1]), w_soff = 4u * T * (uint32_t)(nxt_abs * CK);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
-      const int cp = s / 9, tap = s % 9, kh = tap / 3, kw = tap % 3;
+      const int cp = s / T, tap = s % T, kh = tap / KW, kw = tap % KW;
 #pragma unroll
-      for (int i = 0; i < FM; ++i) av[i] = wsm[(cp * 18 + tap) * LDM + i * 32];
+      for (int i = 0; i < FM; ++i) av[i] = wsm[(cp * 2 * T + tap) * LDM + i * 32];
 #pragma unroll
       for (int j = 0; j < FN; ++j) bv[j] = xs[cp * 2 * PL + pos_l[j] + kh * LDW + kw];
     };
@@ -411,29 +412,29 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_segment_sum_kernel(const 
 }
 
 // input region in one buffer
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED, int KH = 3, int KW = 3>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, false, BALANCED>(p, nullptr);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, false, BALANCED, KH, KW>(p, nullptr);
 }
 
 // input region read from the blocks that hold it
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED, int KH = 3, int KW = 3>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_multi_kernel(const ConvArgs p, const ConvSources srcs) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, true, BALANCED>(p, &srcs);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, true, BALANCED, KH, KW>(p, &srcs);
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;   // dynamic LDS a launch may ask for without raising the kernel's limit; the plans stay below it
 
-// Most floats per channel any tile of BN consecutive positions stages (rows touched + halo rows).
-static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN) {
+// Most floats per channel any tile of BN consecutive positions stages (rows touched + window rows).
+static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN, int64_t KH = 3, int64_t KW = 3) {
   int64_t max_slots = 0;
   for (int64_t pb = 0; pb < P; pb += BN) {
     const int64_t pe = pb + BN < P ? pb + BN : P;
     const int64_t ra = pb / BW, rb = (pe - 1) / BW;
-    const int64_t slots = ((rb / BH) * (BH + 2) + rb % BH + 2) - ((ra / BH) * (BH + 2) + ra % BH) + 1;
+    const int64_t slots = ((rb / BH) * (BH + KH - 1) + rb % BH + KH - 1) - ((ra / BH) * (BH + KH - 1) + ra % BH) + 1;
     if (slots > max_slots) max_slots = slots;
   }
-  return max_slots * (BW + 2);
+  return max_slots * (BW + KW - 1);
 }
 
 constexpr int kConvSlots = 512;        // two resident workgroups on each of the 256 compute units
@@ -442,22 +443,29 @@ constexpr int kConvSlots = 512;        // two resident workgroups on each of the
 // the first `whole` tiles one workgroup each (full waves of kConvSlots), the remaining `rest`
 // tiles cut into (tile, channel step) units dealt evenly to `groups` workgroups.
 struct ConvPlan {
-  int variant;        // 0: 64 x 256 positions, 4 channels per step; 1: 64 x 128, 8 channels; 2: 64 x 128, 4 channels; -1: none fits
+  int variant;        // 3x3: 0: 64 x 256 positions, 4 channels per step; 1: 64 x 128, 8 channels; 2: 64 x 128, 4 channels;
+                      // 1x3: 10: 64 x 256 positions, 12 channels per step; 11: 64 x 128, 12 channels; -1: none fits
   int64_t E;          // staged floats per channel
   int64_t tiles, whole, rest;
   int groups, max_segments;
   int BN, CK;
 };
 
-static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false) {
+static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false, int KH = 3, int KW = 3) {
   ConvPlan pl;
   memset(&pl, 0, sizeof(pl));
-  const int64_t E256 = max_staged(P, BH, BW, 256), E128 = max_staged(P, BH, BW, 128);
+  const int64_t E256 = max_staged(P, BH, BW, 256, KH, KW), E128 = max_staged(P, BH, BW, 128, KH, KW);
   // 256 positions per workgroup (64 x 64 per wavefront) whenever its staged rows fit and the shard
   // has at least that many positions; else 128 positions, with fewer channels per step when the
   // staged rows are wide.
   (void)multi;   // both forms use the same shapes today; the plan is asked per form so that they may differ
-  if (P >= 256 && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
+  if (KH == 1 && KW == 3) {
+    // a row of three taps: 12 channels per step give the same 36-deep step as 4 channels of 3 x 3
+    if (P >= 256 && 12 * E256 <= 13 * 256) { pl.variant = 10; pl.E = E256; pl.BN = 256; pl.CK = 12; }
+    else if (12 * E128 <= 13 * 256) { pl.variant = 11; pl.E = E128; pl.BN = 128; pl.CK = 12; }
+    else { pl.variant = -1; pl.E = E128; return pl; }
+  } else if (KH != 3 || KW != 3) { pl.variant = -1; return pl; }
+  else if (P >= 256 && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
   else if (8 * E128 <= 10 * 256) { pl.variant = 1; pl.E = E128; pl.BN = 128; pl.CK = 8; }
   else if (4 * E128 <= 10 * 256) { pl.variant = 2; pl.E = E128; pl.BN = 128; pl.CK = 4; }
   else { pl.variant = -1; pl.E = E128; return pl; }
@@ -482,14 +490,14 @@ static size_t plan_bytes(const ConvPlan& pl) {
 }
 
 // enough for either entry point (one input buffer, or the region read from several blocks)
-size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI) {
-  const size_t a = plan_bytes(conv_plan(P, BH, BW, CO, CI, false)), b = plan_bytes(conv_plan(P, BH, BW, CO, CI, true));
+size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, int KH, int KW) {
+  const size_t a = plan_bytes(conv_plan(P, BH, BW, CO, CI, false, KH, KW)), b = plan_bytes(conv_plan(P, BH, BW, CO, CI, true, KH, KW));
   return a > b ? a : b;
 }
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, int KH = 3, int KW = 3>
 static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, hipStream_t stream) {
-  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ>;
+  using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ, KH, KW>;
   p.tiles_m = (p.CO + BM - 1) / BM;
   p.tiles_n = (p.P + BN - 1) / BN;
   p.E = (int)pl.E;
@@ -499,11 +507,13 @@ static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, 
   auto launch = [&](bool balanced, int wgs) {
     const dim3 grid((wgs + 7) / 8 * 8), block(Cfg::kThreads);
     if (srcs) {
-      if (balanced) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p, *srcs);
-      else hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p, *srcs);
+      if constexpr (KH == 3 && KW == 3) {   // the multi-block form exists for the 3 x 3 shapes only (the caller checked)
+        if (balanced) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p, *srcs);
+        else hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p, *srcs);
+      }
     } else {
-      if (balanced) hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p);
-      else hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p);
+      if (balanced) hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, true, KH, KW>), grid, block, lds_bytes, stream, p);
+      else hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, false, KH, KW>), grid, block, lds_bytes, stream, p);
     }
   };
   if (pl.whole > 0) {
@@ -537,6 +547,7 @@ struct ConvProblem {
   void* workspace;           // segment slots of a balanced launch (conv_workspace_bytes), may be NULL when none are needed
   size_t workspace_bytes;
   bool accumulate;           // add to the output box instead of overwriting it
+  int KH = 3, KW = 3;        // filter rows / columns: 3 x 3 or 1 x 3
 };
 
 static int conv_core(const ConvProblem& q, hipStream_t stream) {
@@ -551,7 +562,7 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   for (int d = 0; d < 4; ++d) { p.xs[d] = q.xs[d]; p.ws[d] = q.ws[d]; p.ys[d] = q.ys[d]; }
   // lanes address the filters (and a single input buffer) with 32-bit byte offsets from the boxes' low corners
   int64_t x_span = 1, w_span = 1;
-  const int64_t w_ext[4] = {CO, CI, 3, 3};
+  const int64_t w_ext[4] = {CO, CI, q.KH, q.KW};
   for (int d = 0; d < 4; ++d) {
     if (q.xs[d] < 0 || q.ws[d] < 0) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: negative strides are not supported");
     x_span += (q.in_box.hi[d] - q.in_box.lo[d] - 1) * q.xs[d];
@@ -565,10 +576,11 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   p.IH = (int)(q.in_box.hi[2] - q.in_box.lo[2]);
   p.IW = (int)(q.in_box.hi[3] - q.in_box.lo[3]);
   p.plh = (int)q.pad_lo[0]; p.plw = (int)q.pad_lo[1];
-  p.LDW = (int)BW + 2;
-  p.w_fast = q.ws[3] == 1 && q.ws[2] == 3 && q.ws[1] == 9 && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
+  p.LDW = (int)BW + q.KW - 1;
+  p.w_fast = q.ws[3] == 1 && (q.KH == 1 || q.ws[2] == q.KW) && q.ws[1] == q.KH * q.KW && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
 
-  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI, q.srcs != nullptr);
+  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI, q.srcs != nullptr, q.KH, q.KW);
+  if (q.srcs && (q.KH != 3 || q.KW != 3)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: only 3 x 3 filters read their region from several blocks");
   if (pl.variant < 0)
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)pl.E);
   const size_t need = plan_bytes(pl);
@@ -578,6 +590,8 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
     if (reinterpret_cast<uintptr_t>(q.workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   }
   p.slots = static_cast<float*>(q.workspace);
+  if (pl.variant == 10) return launch_conv<64, 256, 12, 1, 4, 13, 1, 3>(p, q.srcs, pl, stream);
+  if (pl.variant == 11) return launch_conv<64, 128, 12, 1, 4, 13, 1, 3>(p, q.srcs, pl, stream);
   if (pl.variant == 0) return launch_conv<64, 256, 4, 1, 4, 8>(p, q.srcs, pl, stream);
   if (pl.variant == 1) return launch_conv<64, 128, 8, 1, 4, 10>(p, q.srcs, pl, stream);
   return launch_conv<64, 128, 4, 1, 4, 10>(p, q.srcs, pl, stream);
@@ -672,7 +686,119 @@ __global__ void __launch_bounds__(256) flip_filters_kernel(float* __restrict__ o
   }
 }
 
+// out[(m * K + k) * T + t] = w[m * s_m + k * s_k + t * s_t]: filters brought to the dense
+// [m][k][taps] order the convolution kernel loads as vectors (conv1d keeps its filters as
+// [ci][co][dx], Fig. 1).  A workgroup moves 32 x 32 (m, k) pairs through LDS: it reads runs along
+// (m, t) for one k -- contiguous in such a source -- and writes runs along (k, t) for one m.
+template <int T>
+__global__ void __launch_bounds__(256) repack_filters_kernel(float* __restrict__ out, const float* __restrict__ w, int64_t s_m, int64_t s_k,
+                                                             int64_t s_t, int M, int K) {
+  __shared__ float tile[32][32 * T + 1];   // [k][m * T + t]
+  const int m0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  for (int i = threadIdx.x; i < 32 * 32 * T; i += 256) {
+    const int k = i / (32 * T), r = i - k * (32 * T), m = r / T, t = r - m * T;
+    float v = 0.f;
+    if (m0 + m < M && k0 + k < K) v = w[(int64_t)(m0 + m) * s_m + (int64_t)(k0 + k) * s_k + t * s_t];
+    tile[k][r] = v;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 32 * 32 * T; i += 256) {
+    const int m = i / (32 * T), r = i - m * (32 * T), k = r / T, t = r - k * T;
+    if (m0 + m < M && k0 + k < K) out[((int64_t)(m0 + m) * K + k0 + k) * T + t] = tile[k][m * T + t];
+  }
+}
+
+int64_t conv1d_chunk(int64_t bw) {
+  // rows of d columns: a tile of 256 consecutive positions stages every row it touches, d + 2 floats each
+  int64_t best = 1, best_score = -1;
+  for (int64_t d = 1; d <= bw && d <= 272; ++d) {
+    if (bw % d) continue;
+    const int64_t rows = 256 % d == 0 ? 256 / d : 255 / d + 2;
+    const int64_t score = rows * (d + 2);
+    if (best_score < 0 || score <= best_score) { best = d; best_score = score; }
+  }
+  return best;
+}
+
+static int shard_conv1d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* data,
+                        const tofu_tensor_t* filters, const tofu_tensor_t* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                        bool accumulate) {
+  if (!op || op->kind != TOFU_OP_CONV1D) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a conv1d");
+  tofu_region_t out_box, in_boxes[2];
+  int32_t partial = 0;
+  int rc = tofu_op_regions(op, splits, nsplits, &out_box, in_boxes, nullptr, nullptr, &partial);
+  if (rc) return rc;
+  if (op->KW != 3) return fail(TOFU_ERR_UNSUPPORTED, "conv1d kernels implement a window of 3");
+  if ((rc = check_tensor("data", data, 3, &in_boxes[0]))) return rc;
+  if ((rc = check_tensor("filters", filters, 3, &in_boxes[1]))) return rc;
+  if ((rc = check_tensor("out", out, 3, &out_box))) return rc;
+  if (volume(&out_box) == 0) return TOFU_OK;
+  const int64_t NB = out_box.hi[0] - out_box.lo[0], CO = out_box.hi[1] - out_box.lo[1], BW = out_box.hi[2] - out_box.lo[2];
+  const int64_t CI = in_boxes[0].hi[1] - in_boxes[0].lo[1];
+  if (CO >= (1 << 30) || CI >= (1 << 30)) return fail(TOFU_ERR_UNSUPPORTED, "conv1d shard extent exceeds 2^30");
+  int64_t ds[3], fs[3], os[3];
+  effective_strides(data, ds);
+  effective_strides(filters, fs);
+  effective_strides(out, os);
+
+  // An output row of BW columns is handed to the convolution kernel as BW / CW rows of CW columns:
+  // row r reads data columns [r * CW, r * CW + CW + 2), so consecutive rows overlap by the window.
+  const int64_t CW = conv1d_chunk(BW), rows = BW / CW;
+  ConvProblem q;
+  q.KH = 1; q.KW = 3;
+  q.pad_lo[0] = q.pad_lo[1] = 0;
+  const int64_t olo[4] = {0, 0, 0, 0}, ohi[4] = {NB, CO, rows, CW}, ihi[4] = {NB, CI, rows, CW + 2};
+  memset(&q.out_box, 0, sizeof(q.out_box));
+  memset(&q.in_box, 0, sizeof(q.in_box));
+  q.out_box.ndim = q.in_box.ndim = 4;
+  for (int d = 0; d < 4; ++d) { q.out_box.lo[d] = q.in_box.lo[d] = olo[d]; q.out_box.hi[d] = ohi[d]; q.in_box.hi[d] = ihi[d]; }
+  q.x = element_ptr(data, ds, in_boxes[0].lo);
+  q.xs[0] = ds[0]; q.xs[1] = ds[1]; q.xs[2] = CW * ds[2]; q.xs[3] = ds[2];
+  q.srcs = nullptr;
+  q.y = const_cast<float*>(element_ptr(out, os, out_box.lo));
+  q.ys[0] = os[0]; q.ys[1] = os[1]; q.ys[2] = CW * os[2]; q.ys[3] = os[2];
+  q.accumulate = accumulate;
+
+  // filters[ci][co][dx] seen as (co, ci, -, dx); a buffer that is physically [co][ci][dx] is used in place
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const float* f = element_ptr(filters, fs, in_boxes[1].lo);
+  const bool in_place = fs[2] == 1 && fs[0] == 3 && fs[1] % 4 == 0 && fs[1] >= 3 * CI && (reinterpret_cast<uintptr_t>(f) & 15) == 0;
+  const size_t repack_bytes = in_place ? 0 : ((size_t)CO * (size_t)CI * 3 * sizeof(float) + 255) / 256 * 256;
+  const size_t need = repack_bytes + conv_workspace_bytes(NB * BW, rows, CW, CO, CI, 1, 3);
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need)
+      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv1d shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  }
+  if (in_place) {
+    q.w = f;
+    q.ws[0] = fs[1]; q.ws[1] = fs[0]; q.ws[2] = 0; q.ws[3] = fs[2];
+  } else {
+    hipLaunchKernelGGL(repack_filters_kernel<3>, dim3((unsigned)((CO + 31) / 32), (unsigned)((CI + 31) / 32)), dim3(256), 0, stream,
+                       static_cast<float*>(workspace), f, fs[1], fs[0], fs[2], (int)CO, (int)CI);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv1d filter launch failed: %s", hipGetErrorString(e));
+    q.w = static_cast<const float*>(workspace);
+    q.ws[0] = CI * 3; q.ws[1] = 3; q.ws[2] = 0; q.ws[3] = 1;
+  }
+  q.workspace = workspace ? static_cast<char*>(workspace) + repack_bytes : nullptr;
+  q.workspace_bytes = workspace ? workspace_bytes - repack_bytes : 0;
+  return conv_core(q, stream);
+}
+
 }  // namespace tofu
+
+extern "C" int tofu_shard_conv1d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                 const tofu_tensor_t* data, const tofu_tensor_t* filters, const tofu_tensor_t* out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_conv1d(op, splits, nsplits, data, filters, out, workspace, workspace_bytes, hip_stream, false);
+}
+
+extern "C" int tofu_shard_conv1d_accumulate(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                            const tofu_tensor_t* data, const tofu_tensor_t* filters, const tofu_tensor_t* out,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return tofu::shard_conv1d(op, splits, nsplits, data, filters, out, workspace, workspace_bytes, hip_stream, true);
+}
 
 extern "C" int tofu_shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
                                  const tofu_tensor_t* x, const tofu_tensor_t* w, const tofu_tensor_t* y, void* workspace,

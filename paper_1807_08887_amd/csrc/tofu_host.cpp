@@ -26,6 +26,7 @@ int iter_ndim(int32_t kind) {
     case TOFU_OP_CONV2D_WGRAD: return 3;
     case TOFU_OP_CONV2D_DGRAD: return 5;
     case TOFU_OP_LSTM_CELL: return 2;
+    case TOFU_OP_CONV1D: return 4;
     default: return 0;
   }
 }
@@ -55,6 +56,12 @@ int check_op(const tofu_op_desc_t* op) {
       return fail(TOFU_ERR_INVALID_ARG, "conv output would be empty");
     return TOFU_OK;
   }
+  if (op->kind == TOFU_OP_CONV1D) {
+    if (op->batch < 1 || op->c_in < 1 || op->c_out < 1 || op->W < 1 || op->KW < 1)
+      return fail(TOFU_ERR_INVALID_ARG, "conv1d needs positive batch, c_in, c_out, W and KW");
+    if (op->W < op->KW) return fail(TOFU_ERR_INVALID_ARG, "conv1d output would be empty");
+    return TOFU_OK;
+  }
   return fail(TOFU_ERR_INVALID_ARG, "unknown operator kind %d", (int)op->kind);
 }
 
@@ -75,6 +82,11 @@ static void iter_extents(const tofu_op_desc_t* op, int64_t* ext, int* first_redu
     case TOFU_OP_LSTM_CELL:
       ext[TOFU_LSTM_DIM_B] = op->M; ext[TOFU_LSTM_DIM_H] = op->N;
       *first_reduce = 2;          // no reduction dimension
+      break;
+    case TOFU_OP_CONV1D:
+      ext[TOFU_CONV1D_DIM_B] = op->batch; ext[TOFU_CONV1D_DIM_CO] = op->c_out;
+      ext[TOFU_CONV1D_DIM_X] = op->W - op->KW + 1; ext[TOFU_CONV1D_DIM_CI] = op->c_in;
+      *first_reduce = TOFU_CONV1D_DIM_CI;
       break;
     case TOFU_OP_CONV2D_DGRAD:
       ext[TOFU_DGRAD_DIM_N] = op->batch; ext[TOFU_DGRAD_DIM_CI] = op->c_in;
@@ -280,6 +292,15 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
     lo[0] = r.lo[CO]; hi[0] = r.hi[CO]; lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
     lo[2] = 0; hi[2] = op->KH; lo[3] = 0; hi[3] = op->KW;
     set_box(&ib[1], 4, lo, hi);
+  } else if (op->kind == TOFU_OP_CONV1D) {
+    const int B = TOFU_CONV1D_DIM_B, CO = TOFU_CONV1D_DIM_CO, X = TOFU_CONV1D_DIM_X, CI = TOFU_CONV1D_DIM_CI;
+    int64_t lo[3] = {r.lo[B], r.lo[CO], r.lo[X]}, hi[3] = {r.hi[B], r.hi[CO], r.hi[X]};
+    set_box(&ob, 3, lo, hi);
+    lo[1] = r.lo[CI]; hi[1] = r.hi[CI];
+    hi[2] = r.hi[X] + op->KW - 1;               // data[x + dx]: the output range widened by the window, always inside the tensor
+    set_box(&ib[0], 3, lo, hi);
+    lo[0] = r.lo[CI]; hi[0] = r.hi[CI]; lo[1] = r.lo[CO]; hi[1] = r.hi[CO]; lo[2] = 0; hi[2] = op->KW;
+    set_box(&ib[1], 3, lo, hi);
   } else if (op->kind == TOFU_OP_LSTM_CELL) {   // element-wise: inputs are read where the output is written
     int64_t lo[3] = {r.lo[0], r.lo[1], 0}, hi[3] = {r.hi[0], r.hi[1], 4};
     set_box(&ob, 2, lo, hi);
@@ -338,6 +359,14 @@ size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits
     if (op->KH != 3 || op->KW != 3 || op->stride != 1 || op->pad > 1) return 0;
     return conv_workspace_bytes((r.hi[TOFU_CONV_DIM_N] - r.lo[TOFU_CONV_DIM_N]) * bh * bw, bh, bw,
                                 r.hi[TOFU_CONV_DIM_CO] - r.lo[TOFU_CONV_DIM_CO], r.hi[TOFU_CONV_DIM_CI] - r.lo[TOFU_CONV_DIM_CI]);
+  }
+  if (op->kind == TOFU_OP_CONV1D) {         // the shard's filters re-ordered to [co][ci][dx], then the slots
+    const int64_t nb = r.hi[TOFU_CONV1D_DIM_B] - r.lo[TOFU_CONV1D_DIM_B], bw = r.hi[TOFU_CONV1D_DIM_X] - r.lo[TOFU_CONV1D_DIM_X];
+    const int64_t co = r.hi[TOFU_CONV1D_DIM_CO] - r.lo[TOFU_CONV1D_DIM_CO], ci = r.hi[TOFU_CONV1D_DIM_CI] - r.lo[TOFU_CONV1D_DIM_CI];
+    const size_t repack = ((size_t)ci * (size_t)co * (size_t)op->KW * sizeof(float) + 255) / 256 * 256;
+    if (op->KW != 3) return repack;
+    const int64_t cw = conv1d_chunk(bw);
+    return repack + conv_workspace_bytes(nb * bw, bw / cw, cw, co, ci, 1, 3);
   }
   if (op->kind == TOFU_OP_CONV2D_DGRAD) {   // the shard's filters, taps reversed and channels exchanged, then the slots
     const int64_t ci = r.hi[TOFU_DGRAD_DIM_CI] - r.lo[TOFU_DGRAD_DIM_CI], co = r.hi[TOFU_DGRAD_DIM_CO] - r.lo[TOFU_DGRAD_DIM_CO];

@@ -55,7 +55,11 @@ size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb);
 
 // Workspace the convolution kernels need for a shard of P positions in BH x BW output boxes with
 // co output and ci input channels (the segment slots of its balanced last wave, possibly 0).
-size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t co, int64_t ci);
+size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t co, int64_t ci, int KH = 3, int KW = 3);
+
+// Columns per chunk the conv1d shard cuts an output row of `bw` columns into (a divisor of bw):
+// the convolution kernel then sees bw / chunk rows of `chunk` columns whose windows overlap.
+int64_t conv1d_chunk(int64_t bw);
 
 // Enqueue dst[i] = sum_j parts[j][i] (fixed order j = 0..k-1); used by the public reduce and
 // by the kernels that split their own reduction.  Pointers are device pointers.

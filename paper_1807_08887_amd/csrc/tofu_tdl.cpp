@@ -76,6 +76,17 @@ extern "C" int tofu_tdl_from_op(const tofu_op_desc_t* op, tofu_tdl_op_t* out) {
     dim(c, 0, op->M).coef[0] = 1; dim(c, 1, op->N).coef[1] = 1;
     return TOFU_OK;
   }
+  if (op->kind == TOFU_OP_CONV1D) {                      // vars: b, co, x | ci, dx  (Fig. 3)
+    out->n_vars = 5; out->n_out = 3; out->n_inputs = 2;
+    const int64_t ext[5] = {op->batch, op->c_out, op->W - op->KW + 1, op->c_in, op->KW};
+    memcpy(out->extent, ext, sizeof(ext));
+    tofu_tdl_access_t &d = out->input[0], &f = out->input[1];
+    d.ndim = f.ndim = 3;
+    dim(d, 0, op->batch).coef[0] = 1; dim(d, 1, op->c_in).coef[3] = 1;
+    tofu_tdl_index_t& dx = dim(d, 2, op->W); dx.coef[2] = 1; dx.coef[4] = 1;
+    dim(f, 0, op->c_in).coef[3] = 1; dim(f, 1, op->c_out).coef[1] = 1; dim(f, 2, op->KW).coef[4] = 1;
+    return TOFU_OK;
+  }
   if (op->kind == TOFU_OP_MATMUL) {                      // vars: m, n | k
     out->n_vars = 3; out->n_out = 2; out->n_inputs = 2;
     out->extent[0] = op->M; out->extent[1] = op->N; out->extent[2] = op->K;

@@ -869,3 +869,84 @@ def test_wgrad_accumulate_through_workspace_segments():
     assert torch.equal(out, want)
     val, absum = oracle.wgrad_box(x, dy, 3, 3, pad=1)
     assert_close(out.cpu().numpy(), val, absum, "accumulated wgrad")
+
+
+# ----------------------------------------------------------------------------- conv1d (the paper's running example)
+CONV1D_DIMS = {"B": tofu.CONV1D_DIM_B, "CO": tofu.CONV1D_DIM_CO, "X": tofu.CONV1D_DIM_X, "CI": tofu.CONV1D_DIM_CI}
+
+
+def run_conv1d(opd, splits, d_data, d_filt, data_lo=None, call=None, out=None):
+    op = tofu.conv1d_desc(opd["batch"], opd["c_in"], opd["c_out"], opd["W"])
+    sp = [(CONV1D_DIMS[d], k, s) for d, k, s in splits]
+    if out is None:
+        out = torch.full((opd["batch"], opd["c_out"], opd["W"] - 2), float("nan"), dtype=torch.float32, device=DEV)
+    (call or tofu.shard_conv1d)(op, sp, tofu.tensor(d_data, data_lo), tofu.tensor(d_filt), tofu.tensor(out), workspace(op, sp))
+    return out
+
+
+@pytest.mark.parametrize("B,CI,CO,X", [(3, 16, 70, 64), (2, 5, 33, 37), (4, 24, 64, 256), (2, 12, 10, 1024), (1, 4, 3, 1), (2, 8, 130, 2048),
+                                       (5, 7, 9, 100)])
+def test_conv1d_shapes_unpartitioned(B, CI, CO, X):
+    data = synth.uniform(130, 0, (B, CI, X + 2), -1, 1)
+    filt = synth.uniform(130, 1, (CI, CO, 3), -1, 1)
+    opd = dict(kind="conv1d", batch=B, c_in=CI, c_out=CO, W=X + 2, KW=3)
+    got = run_conv1d(opd, [], dev(data), dev(filt)).cpu().numpy()
+    val, absum = oracle.conv1d_box(data, filt)
+    assert_close(got, val, absum, f"conv1d {B}x{CI}x{CO}x{X}")
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_conv1d_pnr_invariant_bit_exact(k):
+    B, CI, CO, X = 4, 36, 72, 96
+    data = synth.small_int(131, 0, (B, CI, X + 2), -3, 3)
+    filt = synth.small_int(131, 1, (CI, CO, 3), -3, 3)
+    d_data, d_filt = dev(data), dev(filt)
+    opd = dict(kind="conv1d", batch=B, c_in=CI, c_out=CO, W=X + 2, KW=3)
+    want = oracle.conv1d_box(data, filt)[0]
+    for dim in ["B", "CO", "X", "CI"]:
+        got = assemble(opd, dim, k, lambda sp: run_conv1d(opd, sp, d_data, d_filt))
+        assert np.array_equal(got.astype(np.float64), want), dim
+
+
+def test_conv1d_filter_layouts_halo_block_and_accumulate():
+    B, CI, CO, X = 3, 40, 64, 128
+    data = synth.normal(132, 0, (B, CI, X + 2), 1.0)
+    filt = synth.normal(132, 1, (CI, CO, 3), 0.2)
+    opd = dict(kind="conv1d", batch=B, c_in=CI, c_out=CO, W=X + 2, KW=3)
+    d_data, d_filt = dev(data), dev(filt)
+    val, absum = oracle.conv1d_box(data, filt)
+    base = run_conv1d(opd, [], d_data, d_filt)
+    assert_close(base.cpu().numpy(), val, absum, "conv1d dense [ci][co][dx] filters")
+    # the same filters held as [co][ci][dx] and passed as a permuted view are read in place: same bits
+    phys = d_filt.permute(1, 0, 2).contiguous()
+    view = phys.permute(1, 0, 2)
+    assert view.shape == d_filt.shape and view.stride() == (3, 3 * CI, 1)
+    assert torch.equal(run_conv1d(opd, [], d_data, view), base)
+    # an X shard computed from a block that holds exactly its window-widened range
+    sp = [("X", 4, 2)]
+    reg = R.op_regions(opd, sp)
+    (x0, x1) = reg["in_boxes"][0][2]
+    block = d_data[:, :, x0:x1].contiguous()
+    got = run_conv1d(opd, sp, block, d_filt, data_lo=[0, 0, x0])
+    (o0, o1) = reg["out_box"][2]
+    assert torch.equal(got[:, :, o0:o1], base[:, :, o0:o1])
+    assert torch.isnan(got[:, :, :o0]).all() and torch.isnan(got[:, :, o1:]).all()
+    # CI shards added into one buffer == partial buffers + reduce
+    k = 4
+    parts = [run_conv1d(opd, [("CI", k, s)], d_data, d_filt) for s in range(k)]
+    want = torch.empty_like(parts[0])
+    tofu.partition_reduce(want, parts)
+    out = torch.full_like(want, float("nan"))
+    for s in range(k):
+        run_conv1d(opd, [("CI", k, s)], d_data, d_filt, call=tofu.shard_conv1d if s == 0 else tofu.shard_conv1d_accumulate, out=out)
+    assert torch.equal(out, want)
+    assert_close(out.cpu().numpy(), val, absum, "conv1d accumulated CI split")
+
+
+def test_conv1d_length_without_a_suitable_divisor_is_reported():
+    B, CI, CO, X = 1, 4, 4, 521          # a prime: rows of one column would stage 256 rows per tile
+    opd = dict(kind="conv1d", batch=B, c_in=CI, c_out=CO, W=X + 2, KW=3)
+    d_data = torch.zeros(B, CI, X + 2, device=DEV); d_filt = torch.zeros(CI, CO, 3, device=DEV)
+    with pytest.raises(tofu.TofuError) as e:
+        run_conv1d(opd, [], d_data, d_filt)
+    assert e.value.status == -6

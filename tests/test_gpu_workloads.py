@@ -45,7 +45,7 @@ def _check_reduce(leg):
 
 @pytest.mark.parametrize("group", [("gemm_nsplit",), ("gemm_dx_nsplit", "gemm_dw_nsplit"), ("gemm_ksplit", "reduce_gates"),
                                    ("conv_cout", "fetch_halo", "conv_cout_h", "conv_cout_h_fused"), ("wgrad_batch", "reduce_dw"), ("dgrad_cout",), ("lstm_cell_nsplit",),
-                                   ("gemm_ksplit_accumulate",), ("wgrad_batch_accumulate",)])
+                                   ("gemm_ksplit_accumulate",), ("wgrad_batch_accumulate",), ("conv1d_cout",)])
 def test_full_size_legs(group):
     print(f"building {group}", flush=True)
     legs = tofu_workloads.build("cuda:0", group)
@@ -77,6 +77,13 @@ def test_full_size_legs(group):
             if leg.name == "conv_cout_h_fused":   # reading the blocks directly changes no bit of the result
                 fetched = next(l for l in legs if l.name == "conv_cout_h")
                 assert torch.equal(leg.out, fetched.out)
+        elif h["kind"] == "conv1d":
+            y = leg.out.cpu().numpy()
+            pts = _points(75, 4096, y.shape)
+            # the oracle evaluates a box; sample rows of outputs instead of single points: 8 (b, co) rows, all x
+            for b, co, _ in pts[:8]:
+                val, absum = oracle.conv1d_box(h["data"][b:b + 1], np.ascontiguousarray(h["filters"][:, co:co + 1]))
+                _close(y[b, co], val[0, 0], absum[0, 0], leg.name)
         elif h["kind"] == "lstm":
             cn, hn, sc = oracle.lstm_cell(h["gates"], h["c"])
             _close(leg.out.cpu().numpy().ravel(), cn.ravel(), sc.ravel(), leg.name + " c")

@@ -536,3 +536,82 @@ def test_lstm_cell_against_torch_fp64_and_closed_forms():
             sl = R.box_slices(reg["out_box"])
             out[sl] = oracle.lstm_cell(g[sl], c[sl])[0]
         assert np.array_equal(out, cn)
+
+
+# ----------------------------------------------------------------------------- conv1d (Fig. 1 / Fig. 3)
+def test_conv1d_against_its_loop_nest_the_2d_convolution_and_closed_forms():
+    B, CI, CO, X, DX = 2, 3, 4, 7, 3
+    data = synth.uniform(120, 0, (B, CI, X + DX - 1), -1, 1)
+    filt = synth.uniform(120, 1, (CI, CO, DX), -1, 1)
+    val, absum = oracle.conv1d_box(data, filt)
+    # the loop nest of Fig. 1, written out
+    want = np.zeros((B, CO, X)); wabs = np.zeros((B, CO, X))
+    for b in range(B):
+        for co in range(CO):
+            for x in range(X):
+                for ci in range(CI):
+                    for dx in range(DX):
+                        p = float(data[b, ci, x + dx]) * float(filt[ci, co, dx])
+                        want[b, co, x] += p
+                        wabs[b, co, x] += abs(p)
+    assert np.allclose(val, want, rtol=0, atol=1e-15) and np.allclose(absum, wabs, rtol=0, atol=1e-15)
+    # a 2-D convolution with one row, no padding and the filters' first two indices exchanged
+    v2, _ = oracle.conv2d_box(data[:, :, None, :], np.ascontiguousarray(filt.transpose(1, 0, 2))[:, :, None, :], pad=0)
+    assert np.allclose(val, v2[:, :, 0, :], rtol=0, atol=1e-14)
+    # torch's conv1d in fp64
+    import torch
+    ref = torch.nn.functional.conv1d(torch.from_numpy(data).double(), torch.from_numpy(filt).double().permute(1, 0, 2)).numpy()
+    assert np.allclose(val, ref, rtol=0, atol=1e-14)
+    # closed forms: all ones -> CI * DX; a one-tap filter shifts the data
+    ones = oracle.conv1d_box(np.ones((B, CI, X + DX - 1), np.float32), np.ones((CI, CO, DX), np.float32))[0]
+    assert (ones == CI * DX).all()
+    shift = np.zeros((CI, CI, DX), np.float32)
+    for c in range(CI):
+        shift[c, c, 2] = 1.0
+    assert np.array_equal(oracle.conv1d_box(data, shift)[0], data[:, :, 2:2 + X].astype(np.float64))
+    # the ci range restricts the sum: two halves add up
+    a = oracle.conv1d_box(data, filt, cirange=(0, 1))[0] + oracle.conv1d_box(data, filt, cirange=(1, CI))[0]
+    assert np.allclose(a, val, rtol=0, atol=1e-15)
+
+
+def test_conv1d_regions_follow_the_papers_strategies_and_touched_coordinates():
+    """The dedicated conv1d regions reproduce the table of strategies (Fig. 2 / Sec. 4.2) and the bounding
+    boxes of what the loop nest touches, for every one-step plan."""
+    X, DX = 12, 3
+    op = dict(kind="conv1d", batch=4, c_in=6, c_out=8, W=X + DX - 1, KW=DX)
+    name = {"b": "B", "ci": "CI", "co": "CO", "x": "X"}
+    for split, d_b, d_ci, d_x, f_ci, f_co, f_dx, combine in _rows("conv1d_strategies.txt"):
+        regs = [R.op_regions(op, [(name[split], 2, s)]) for s in range(2)]
+        assert all(r["is_partial"] == (combine == "sum") for r in regs)
+        full = [(0, 4), (0, 6), (0, X + DX - 1)]
+        for dimidx, which in enumerate((d_b, d_ci, d_x)):
+            parts = [r["in_boxes"][0][dimidx] for r in regs]
+            lo, hi = full[dimidx]
+            want = {"all": [(lo, hi)] * 2, "half": [(lo, hi // 2), (hi // 2, hi)], "halo": [(0, X // 2 + DX - 1), (X // 2, X + DX - 1)]}[which]
+            assert parts == want, (split, dimidx)
+        fullf = [(0, 6), (0, 8), (0, DX)]
+        for dimidx, which in enumerate((f_ci, f_co, f_dx)):
+            parts = [r["in_boxes"][1][dimidx] for r in regs]
+            lo, hi = fullf[dimidx]
+            assert parts == ([(lo, hi)] * 2 if which == "all" else [(lo, hi // 2), (hi // 2, hi)]), (split, dimidx)
+    from oracle import tdl as O
+    desc = O.conv1d(4, 6, 8, X, DX)
+    var = {"B": "b", "CO": "co", "X": "x", "CI": "ci"}
+    for dim in var:
+        for k in (2, 3, 4):
+            for s in range(k):
+                reg = R.op_regions(op, [(dim, k, s)])
+                masks = O.touched(desc, [(var[dim], k, s)])
+                assert [tuple(b) for b in reg["in_boxes"][0]] == O.bbox(masks[0])
+                assert [tuple(b) for b in reg["in_boxes"][1]] == O.bbox(masks[1])
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_conv1d_pnr_invariant_on_the_oracle(k):
+    data = synth.small_int(121, 0, (4, 8, 14), -3, 3)
+    filt = synth.small_int(121, 1, (8, 8, 3), -3, 3)
+    op = dict(kind="conv1d", batch=4, c_in=8, c_out=8, W=14, KW=3)
+    full = oracle.conv1d_box(data, filt)[0]
+    for dim in ["B", "CO", "X", "CI"]:
+        got = _assemble(op, dim, k, lambda reg: oracle.conv1d_box(data, filt, box=reg["out_box"], cirange=reg["ranges"]["CI"])[0])
+        assert np.array_equal(got, full), dim

@@ -146,6 +146,9 @@ CONFIGS = {
     "wresnet_conv_wgrad": dict(kind="conv2d_wgrad", seed=505, batch=128, c_in=1280, c_out=1280, H=28, W=28,
                                KH=3, KW=3, stride=1, pad=1, k=8, shard=3,
                                x=("normal", 1.0), dy=("normal", 1.0), partial_std=math.sqrt(16.0 * 784.0)),
+    # the paper's running example at a large size: conv1d, 2048 channels, window 3, 512 outputs per row; 8-way C_out split
+    "conv1d_large": dict(kind="conv1d", seed=606, batch=64, c_in=2048, c_out=2048, W=514, KW=3, k=8, shard=3,
+                         x=("normal", 1.0), w=("normal", math.sqrt(2.0 / (2048 * 3)))),
 }
 
 

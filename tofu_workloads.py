@@ -16,6 +16,7 @@ Builds, from the seeded generator, the device buffers of the four large workload
   gemm_dw_nsplit     (extra) backward of the N-split gate GEMM: dW_s = X^T . dY_s, X read transposed in place
   gemm_ksplit_accumulate, wgrad_batch_accumulate  (extra) the two Case-2 shards adding into a resident full-size buffer
                      instead of writing a partial (out = out + shard; the buffer starts at zero)
+  conv1d_cout        (extra) the paper's conv1d (Fig. 1) with 2048 channels, 512 outputs per row, batch 64: shard 3 of an 8-way C_out split
   wgrad_batch   3x3 conv weight gradient 1280->1280 @28x28: shard 3 of an 8-way batch split -> partial dW
   reduce_dw     that partial + 7 remote partials -> dW                           (partition-n-reduce)
 
@@ -66,7 +67,7 @@ def _ws(op, splits, dev):
 STEP_LEGS = ("gemm_nsplit", "gemm_ksplit", "reduce_gates", "conv_cout", "fetch_halo", "conv_cout_h", "wgrad_batch", "reduce_dw")
 # variants and backward operators outside the step, built only when named
 EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_cout", "lstm_cell_nsplit", "gemm_ksplit_accumulate",
-              "wgrad_batch_accumulate")
+              "wgrad_batch_accumulate", "conv1d_cout")
 
 
 def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
@@ -241,6 +242,22 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
                               tofu.tensor(part_dx), wsd), part_dx,
                         dict(kind="dgrad", dy=dy_s, w=w_s, H=H, W=W, keep=(d_dy, d_w, wsd)) if keep_host else dict(keep=(d_dy, d_w, wsd)),
                         conventional_flop=2.0 * NB * C * (co1 - co0) * 9 * H * W))
+
+    if extra("conv1d_cout"):
+        cfg = synth.CONFIGS["conv1d_large"]
+        NB, C, L, k, s = cfg["batch"], cfg["c_in"], cfg["W"], cfg["k"], cfg["shard"]
+        op1 = tofu.conv1d_desc(NB, C, C, L)
+        sp1 = [(tofu.CONV1D_DIM_CO, k, s)]
+        reg1 = tofu.op_regions(op1, sp1)
+        (co0, co1) = reg1["out_box"][1]
+        data = synth.draw(cfg["x"], cfg["seed"], 0, (NB, C, L))
+        f_s = synth.draw(cfg["w"], cfg["seed"], 1, (C, co1 - co0, 3))     # the worker's own filters, [ci][co][dx] as in Fig. 1
+        d_data, d_f = up(data), up(f_s)
+        out1 = torch.zeros(NB, co1 - co0, L - 2, dtype=torch.float32, device=dev)
+        ws1 = _ws(op1, sp1, dev)
+        legs.append(Leg("conv1d_cout", "mfma", 2.0 * NB * (co1 - co0) * (L - 2) * C * 3,
+                        _call(tofu.shard_conv1d, op1, sp1, tofu.tensor(d_data), tofu.tensor(d_f, [0, co0, 0]), tofu.tensor(out1, [0, co0, 0]), ws1), out1,
+                        dict(kind="conv1d", data=data, filters=f_s, keep=(d_data, d_f, ws1)) if keep_host else dict(keep=(d_data, d_f, ws1))))
 
     # ------------------------------------------------------------------ Wide-ResNet conv weight gradient
     if want("wgrad_batch", "reduce_dw") or extra("wgrad_batch_accumulate"):
