@@ -128,8 +128,8 @@ def cpu_model():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--legs", type=str, default="", help="comma-separated subset of legs (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -186,14 +186,17 @@ def main():
     wall = time.perf_counter() - t0
 
     ms_per_step = wall * 1e3 / args.steps
-    leg_ms = [sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps for i in range(len(legs))]
+    per_step = [[ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)] for i in range(len(legs))]
+    leg_ms = [sum(t) / len(t) for t in per_step]
     leg_out = []
-    for leg, ms in zip(legs, leg_ms):
+    for leg, ms, samples in zip(legs, leg_ms, per_step):
         peak, unit = PEAK[leg.bound]
         scale = 1e-9 if leg.bound == "mfma" else 1e-6           # FLOP/ms -> TFLOP/s, B/ms -> GB/s
         achieved = leg.work / ms * scale
-        entry = {"leg": leg.name, "bound": leg.bound, "ms": round(ms, 4), "achieved": round(achieved, 2), "unit": unit,
-                 "frac": round(achieved / peak, 4)}
+        # ms = mean over the timed steps (what `value` is made of); median and min over the same launches.
+        # Inside a step every leg finds its operands evicted by the other legs (a step moves about 3 GB): cache-cold.
+        entry = {"leg": leg.name, "bound": leg.bound, "ms": round(ms, 4), "median_ms": round(sorted(samples)[len(samples) // 2], 4),
+                 "min_ms": round(min(samples), 4), "achieved": round(achieved, 2), "unit": unit, "frac": round(achieved / peak, 4)}
         if leg.conventional_flop:
             entry["conventional_tflops"] = round(leg.conventional_flop / ms * 1e-9, 2)
         leg_out.append(entry)
@@ -233,6 +236,22 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         out["graph_replay_ms_per_step"] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
+    # the streaming legs again, launched back to back: their operands are then partly resident in the
+    # last-level cache (the gate reduce's 151 MB fit it, the dW reduce's 531 MB do not) -- the cache-warm figure
+    for leg, entry in zip(legs, leg_out):
+        if leg.bound != "hbm":
+            continue
+        for _ in range(3):
+            leg.run()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+        for i in range(20):
+            e[i].record()
+            leg.run()
+        e[20].record()
+        torch.cuda.synchronize()
+        warm = sorted(e[i].elapsed_time(e[i + 1]) for i in range(20))[10]
+        entry["back_to_back_ms"] = round(warm, 4)
+        entry["back_to_back_gbs"] = round(leg.work / warm * 1e-6, 1)
     if extra_legs:
         # outside the step: the fused-fetch convolution and the backward GEMMs, timed right after
         # the steps (warm clocks)

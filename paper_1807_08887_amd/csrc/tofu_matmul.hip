@@ -286,7 +286,7 @@ constexpr int kMaxSplit = 16;        // the reduce kernel sums at most 16 inputs
 
 int matmul_split_k(int64_t m, int64_t n, int64_t k) {
   int64_t tiles = ((m + kBM - 1) / kBM) * ((n + kBN - 1) / kBN);
-  if (tiles >= kTargetGroups / 2 || k < 1024) return 1;
+  if (tiles >= kTargetGroups || k < 1024) return 1;
   int64_t s = kTargetGroups / tiles;
   if (s > kMaxSplit) s = kMaxSplit;
   while (s > 1 && k / s < 512) --s;   // keep every slice long enough to amortise its prologue
