@@ -437,7 +437,8 @@ static int64_t max_staged(int64_t P, int64_t BH, int64_t BW, int64_t BN, int64_t
   return max_slots * (BW + KW - 1);
 }
 
-constexpr int kConvSlots = 512;        // two resident workgroups on each of the 256 compute units
+constexpr int kConvSlots = 512;        // two resident workgroups on each of the 256 compute units (a third one per unit
+                                       // fits only with register spills and measured no faster)
 
 // Which kernel shape a shard of P positions in BH x BW boxes uses, and how its tiles are launched:
 // the first `whole` tiles one workgroup each (full waves of kConvSlots), the remaining `rest`

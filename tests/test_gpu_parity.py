@@ -950,3 +950,42 @@ def test_conv1d_length_without_a_suitable_divisor_is_reported():
     with pytest.raises(tofu.TofuError) as e:
         run_conv1d(opd, [], d_data, d_filt)
     assert e.value.status == -6
+
+
+def test_matmul_reads_an_operand_held_in_row_blocks_without_assembling_it():
+    """The paper's example of a matrix product cut twice (Sec. 5.2): a worker that computes rows of C needs
+    all of B, which is held as k row blocks (its own and the fetched ones).  One call per block, the later
+    ones accumulating, reads every block in place -- no assembled copy of B -- and equals the K-split
+    partials reduced left to right bit for bit."""
+    M, N, K, k = 96, 200, 512, 4
+    A = synth.normal(140, 0, (M, K), 1.0); B = synth.normal(140, 1, (K, N), 1.0)
+    dA = dev(A)
+    op = tofu.matmul_desc(M, N, K)
+    rows = [R.shard_range(K, k, j) for j in range(k)]
+    blocks = [dev(B[lo:hi]) for lo, hi in rows]                      # k separate buffers, never concatenated
+    m_split = (tofu.MM_DIM_M, 2, 1)                                  # this worker's rows of C
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    for j, (lo, hi) in enumerate(rows):
+        sp = [m_split, (tofu.MM_DIM_K, k, j)]
+        call = tofu.shard_matmul if j == 0 else tofu.shard_matmul_accumulate
+        call(op, sp, tofu.tensor(dA), tofu.tensor(blocks[j], [lo, 0]), tofu.tensor(C), workspace(op, sp))
+    got = C.cpu().numpy()
+    m0, m1 = R.shard_range(M, 2, 1)
+    assert np.isnan(got[:m0]).all() and not np.isnan(got[m0:m1]).any()
+    val, absum = oracle.matmul_box(A, B, box=[(m0, m1), (0, N)])
+    assert_close(got[m0:m1], val, absum, "matmul over row blocks of B")
+    # the same through k partial buffers and the reduce
+    dB = dev(B)
+    parts = []
+    for j in range(k):
+        P = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        sp = [m_split, (tofu.MM_DIM_K, k, j)]
+        tofu.shard_matmul(op, sp, tofu.tensor(dA), tofu.tensor(dB), tofu.tensor(P), workspace(op, sp))
+        parts.append(P)
+    want = torch.empty_like(parts[0])
+    tofu.partition_reduce(want, parts)
+    assert torch.equal(C[m0:m1], want[m0:m1])
+    # a block that does not hold the rows of its step is refused, never read as zeros
+    with pytest.raises(tofu.TofuError) as e:
+        tofu.shard_matmul(op, [m_split, (tofu.MM_DIM_K, k, 1)], tofu.tensor(dA), tofu.tensor(blocks[0], [0, 0]), tofu.tensor(C))
+    assert e.value.status == -2
