@@ -989,3 +989,76 @@ def test_matmul_reads_an_operand_held_in_row_blocks_without_assembling_it():
     with pytest.raises(tofu.TofuError) as e:
         tofu.shard_matmul(op, [m_split, (tofu.MM_DIM_K, k, 1)], tofu.tensor(dA), tofu.tensor(blocks[0], [0, 0]), tofu.tensor(C))
     assert e.value.status == -2
+
+
+# ----------------------------------------------------------------------------- from a searched plan to executed shards
+def _nested_box(shape, cuts):
+    """Box of a tensor held after the nested cuts [(dim, k, part), ...] (each cuts the range left by the earlier ones)."""
+    box = [(0, e) for e in shape]
+    for d, k, part in cuts:
+        lo, hi = box[d]
+        a, b = R.shard_range(hi - lo, k, part)
+        box[d] = (lo + a, lo + b)
+    return box
+
+
+@pytest.mark.parametrize("kind", ["matmul", "conv1d"])
+def test_searched_plan_drives_fetch_shard_and_reduce(kind):
+    """The whole path for four workers: search a recursive plan (2 x 2), hold every tensor cut as the plan says,
+    and for each worker fetch its input regions from the owners' blocks, run its shard, then sum the partials of
+    workers that share an output box and place the result -- the unpartitioned operator comes out."""
+    from paper_1807_08887_amd import plan as L, tdl as T
+    ks = [2, 2]
+    if kind == "matmul":
+        M, N, K = 64, 96, 160
+        op = tofu.matmul_desc(M, N, K)
+        ins = [synth.small_int(150, 0, (M, K), -3, 3), synth.small_int(150, 1, (K, N), -3, 3)]
+        want = oracle.matmul_box(*ins)[0]
+        run = tofu.shard_matmul
+    else:
+        B, CI, CO, X = 4, 24, 64, 64
+        op = tofu.conv1d_desc(B, CI, CO, X + 2)
+        ins = [synth.small_int(151, 0, (B, CI, X + 2), -3, 3), synth.small_int(151, 1, (CI, CO, 3), -3, 3)]
+        want = oracle.conv1d_box(*ins)[0]
+        run = tofu.shard_conv1d
+    desc = T.from_op(op)
+    g = L.graph(3, [(desc, [0, 1], 2, 0)])
+    res = L.recursive(g, ks)
+    n_workers = ks[0] * ks[1]
+    digits = [(w // ks[1], w % ks[1]) for w in range(n_workers)]
+    # every worker's block of each input, as separate device buffers
+    held = []
+    for t in range(2):
+        blocks = []
+        for w in range(n_workers):
+            box = _nested_box(ins[t].shape, [(res["tensor_dim"][s][t], ks[s], digits[w][s]) for s in range(2)])
+            blocks.append((box, dev(ins[t][R.box_slices(box)])))
+        held.append(blocks)
+    out = torch.full(want.shape, float("nan"), dtype=torch.float32, device=DEV)
+    partials = {}
+    for w in range(n_workers):
+        sp = L.worker_splits(res["op_var"], ks, 0, w)
+        assert all(v < desc.n_vars - (1 if kind == "conv1d" else 0) for v, _, _ in sp)      # a variable the shard calls can cut
+        reg = tofu.op_regions(op, sp)
+        fetched = []
+        for t in range(2):
+            box = reg["in_boxes"][t]
+            dst = torch.empty([hi - lo for lo, hi in box], dtype=torch.float32, device=DEV)
+            tofu.region_fetch(tofu.tensor(dst, [lo for lo, _ in box]), [tofu.tensor(b, [lo for lo, _ in bx]) for bx, b in held[t]])
+            fetched.append(tofu.tensor(dst, [lo for lo, _ in box]))
+            fetched.append(dst)                                                          # keep the buffer alive
+        part = torch.zeros(want.shape, dtype=torch.float32, device=DEV)
+        run(op, sp, fetched[0], fetched[2], tofu.tensor(part), workspace(op, sp))
+        partials.setdefault(tuple(map(tuple, reg["out_box"])), []).append(part)
+    assert sum(len(v) for v in partials.values()) == n_workers
+    for box, parts in partials.items():
+        sl = R.box_slices(list(box))
+        if len(parts) == 1:
+            out[sl] = parts[0][sl]
+        else:                      # Case-2 somewhere in the plan: the workers that share this box hold partial sums
+            total = torch.empty_like(parts[0])
+            tofu.partition_reduce(total, parts)
+            out[sl] = total[sl]
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), want)
+    # what the plan says it costs is what the fetches moved in its first step: elements read from other groups' blocks
+    assert res["total"] == sum(res["step_elements"]) and res["step_elements"][0] <= res["step_elements"][1]
