@@ -22,15 +22,15 @@ PEAK = {"mfma": (157.3, "TFLOP/s"), "hbm": (8000.0, "GB/s")}   # MI355X: fp32 ma
 # hardware-counter runs summarised in profiles/all_legs_hbm_traffic.txt: (FETCH_SIZE, WRITE_SIZE)
 # per dispatch, each scaled by the factor that makes the same counter match the 256 MiB
 # calibration copy of that run (2.0 for reads, 1.0 for writes).
-TRAFFIC_KIB = {"conv_cout": (532281.0 + 32050.0, 64000.0 + 35699.1),        # conv2d_kernel + conv2d_segment_sum_kernel
-               "conv_cout_h": (792903.0 + 24241.7, 48384.0 + 19107.9),
-               "wgrad_batch": (1089900.0 + 63396.5, 126720.0 + 57763.5),    # wgrad_kernel + wgrad_segment_sum_kernel
-               "gemm_ksplit": (149577.0, 16384.0),
-               "gemm_nsplit": (149577.0 + 8210.5, 16384.0 + 2048.0)}        # matmul_kernel + slice_sum_kernel
+TRAFFIC_KIB = {"conv_cout": (533973.0 + 32054.9, 64000.0 + 35703.7),        # conv2d_kernel + conv2d_segment_sum_kernel
+               "conv_cout_h": (792886.0 + 24247.0, 48384.0 + 19040.2),
+               "wgrad_batch": (1088130.0 + 63398.1, 126720.0 + 57727.8),    # wgrad_kernel + wgrad_segment_sum_kernel
+               "gemm_ksplit": (149581.0, 16384.0),
+               "gemm_nsplit": (149581.0 + 8211.0, 16384.0 + 2048.0)}        # matmul_kernel + slice_sum_kernel
 TRAFFIC_SCALE = (2.0, 1.0)
-LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced> + conv2d_segment_sum_kernel",
-               "conv_cout_h": "conv2d_kernel<64,256,4,1,4,8,balanced> + conv2d_segment_sum_kernel",
-               "wgrad_batch": "wgrad_kernel<128,32,fast,balanced,14> + wgrad_segment_sum_kernel",
+LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced,3,3> + conv2d_segment_sum_kernel",
+               "conv_cout_h": "conv2d_kernel<64,256,4,1,4,8,balanced,3,3> + conv2d_segment_sum_kernel",
+               "wgrad_batch": "wgrad_kernel<128,32,fast,balanced,14,1,4> + wgrad_segment_sum_kernel",
                "gemm_ksplit": "matmul_kernel<128,64,32,2,2>", "gemm_nsplit": "matmul_kernel<128,64,32,2,2> + slice_sum_kernel"}
 EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
                "gemm_ksplit_accumulate": "gemm_ksplit adding into a resident [128,32768] buffer (reduction fused into the epilogue)",
