@@ -26,7 +26,9 @@
  *   - Layouts: matmul A[M,K], B[K,N], C[M,N] row-major.  conv2d x[N,C_in,H,W],
  *     w[C_out,C_in,KH,KW] (output channel outermost), y[N,C_out,H_out,W_out].
  *     The convolution is a cross-correlation (index x+dx, no filter flip) as in
- *     the paper's conv1d loop nest (Fig. 1), with zero padding `pad`.
+ *     the paper's conv1d loop nest (Fig. 1), with zero padding `pad`.  conv1d
+ *     itself keeps the figure's shapes: data[B,C_in,W], filters[C_in,C_out,KW],
+ *     out[B,C_out,W-KW+1], no padding.
  */
 #ifndef TOFU_H_
 #define TOFU_H_
@@ -126,8 +128,9 @@ int tofu_shard_range(int64_t extent, int32_t k, int32_t shard, int64_t* lo, int6
  * operator's iteration space and returns
  *   out_box      the box of the output tensor this shard writes (the whole
  *                output when only reduction dimensions were split),
- *   in_boxes[0]  the box of the first input it reads  (A | x | x  | dy | gates),
- *   in_boxes[1]  the box of the second input it reads (B | w | dy | w  | c_prev),
+ *   in_boxes[0]  the box of the first input it reads  (A | x | x  | dy | gates  | data),
+ *   in_boxes[1]  the box of the second input it reads (B | w | dy | w  | c_prev | filters),
+ *                in the order matmul | conv2d | wgrad | dgrad | lstm cell | conv1d,
  *   pad_lo/hi[2] conv only: rows/columns (index 0 = H, 1 = W) of the needed
  *                window that fall outside the global input on the low/high
  *                side and are therefore zeros; in_boxes[0] is already clipped,
@@ -147,7 +150,8 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
  * their own reductions to fill the GPU -- K slices of a tall-skinny matmul,
  * (tile, channel step) or (tile, image) segments of the convolutions -- and the
  * workspace holds those partial tiles until a second kernel sums them in a
- * fixed order; the data gradient also keeps its reversed filters there.  The
+ * fixed order; the data gradient also keeps its reversed filters there and the
+ * conv1d its re-ordered filters.  The
  * content is scratch: nothing is carried from one call to the next, and calls
  * that run concurrently need separate workspaces. */
 size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits);
