@@ -172,3 +172,30 @@ def test_large_rnn_like_chain_for_eight_workers():
         reg = T.regions(desc, L.worker_splits(res["op_var"], [2, 2, 2], 0, w))
         seen.add(tuple(map(tuple, reg["out_box"])) + tuple(map(tuple, reg["in_boxes"][0])))
     assert len(seen) == 8
+
+
+def test_resnet_like_chain_moves_filters_low_and_activations_high():
+    """A chain of 3x3 convolutions shaped like a widened ResNet trunk (feature map halves, channels double;
+    Sec. 7.4: lower layers have large feature maps and small filters, higher layers the opposite): searched
+    for 8 workers in three recursive steps, the lowest layers keep cutting the batch (filters are what
+    moves) and the highest layer ends up cutting channels (activations move), total cost below that of
+    cutting the batch everywhere, per-step costs non-decreasing."""
+    batch = 32
+    layers = [(160, 160, 56, 1), (160, 320, 56, 2), (320, 320, 28, 1), (320, 640, 28, 2), (640, 640, 14, 1), (640, 1280, 14, 2),
+              (1280, 1280, 7, 1)]
+    ops = []
+    for l, (ci, co, hw, stride) in enumerate(layers):
+        desc = T.from_op(tofu.conv2d_desc(batch, ci, co, hw, hw, stride=stride))
+        ops.append((desc, [2 * l, 2 * l + 1], 2 * l + 2, l))        # activations 0, 2, 4, ...; filters 1, 3, 5, ...
+    g = L.graph(2 * len(layers) + 1, ops)
+    res = L.recursive(g, [2, 2, 2])
+    assert all(a <= b for a, b in zip(res["step_elements"], res["step_elements"][1:]))
+    cuts = [[res["op_var"][s][l] for s in range(3)] for l in range(len(layers))]
+    assert cuts[0] == [0, 0, 0] and cuts[1] == [0, 0, 0]              # batch, batch, batch
+    assert any(v in (1, 4) for v in cuts[-1])                         # output or input channels somewhere in the last layer
+    # data parallelism: every worker gathers every filter tensor once per step level -> (k - 1) * sum of filter sizes
+    dp = 7 * sum(ci * co * 9 for ci, co, _, _ in layers)
+    assert res["total"] < dp
+    # a single 8-way step may only cut one dimension per tensor: never cheaper than the recursion's grid
+    one = L.basic(g, 8)
+    assert one["elements"] >= res["total"]
