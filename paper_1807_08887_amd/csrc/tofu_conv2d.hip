@@ -460,13 +460,15 @@ static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t
   // has at least that many positions; else 128 positions, with fewer channels per step when the
   // staged rows are wide.
   (void)multi;   // both forms use the same shapes today; the plan is asked per form so that they may differ
+  // a shard of few positions: 128-position tiles when they leave at least a tenth less of the last tile empty
+  const bool small_tiles = ((P + 127) / 128 * 128) * 10 <= ((P + 255) / 256 * 256) * 9;
   if (KH == 1 && KW == 3) {
     // a row of three taps: 12 channels per step give the same 36-deep step as 4 channels of 3 x 3
-    if (P >= 256 && 12 * E256 <= 13 * 256) { pl.variant = 10; pl.E = E256; pl.BN = 256; pl.CK = 12; }
+    if (P >= 256 && !small_tiles && 12 * E256 <= 13 * 256) { pl.variant = 10; pl.E = E256; pl.BN = 256; pl.CK = 12; }
     else if (12 * E128 <= 13 * 256) { pl.variant = 11; pl.E = E128; pl.BN = 128; pl.CK = 12; }
     else { pl.variant = -1; pl.E = E128; return pl; }
   } else if (KH != 3 || KW != 3) { pl.variant = -1; return pl; }
-  else if (P >= 256 && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
+  else if (P >= 256 && !small_tiles && 4 * E256 <= 8 * 256) { pl.variant = 0; pl.E = E256; pl.BN = 256; pl.CK = 4; }
   else if (8 * E128 <= 10 * 256) { pl.variant = 1; pl.E = E128; pl.BN = 128; pl.CK = 8; }
   else if (4 * E128 <= 10 * 256) { pl.variant = 2; pl.E = E128; pl.BN = 128; pl.CK = 4; }
   else { pl.variant = -1; pl.E = E128; return pl; }
