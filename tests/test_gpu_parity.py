@@ -1062,3 +1062,69 @@ def test_searched_plan_drives_fetch_shard_and_reduce(kind):
     assert np.array_equal(out.cpu().numpy().astype(np.float64), want)
     # what the plan says it costs is what the fetches moved in its first step: elements read from other groups' blocks
     assert res["total"] == sum(res["step_elements"]) and res["step_elements"][0] <= res["step_elements"][1]
+
+
+def test_searched_plan_for_a_training_layer_forward_and_backward():
+    """One fully-connected layer with its two backward products as ONE operator group (Sec. 5.1): the search may
+    cut forward and backward tensors differently.  Four workers execute all three products of their shards from
+    blocks held as the plan says (the backward products read W and X through transposed views of the fetched
+    regions); Y, dX and dW all come out bit-exact."""
+    from paper_1807_08887_amd import plan as L, tdl as T
+    Bt, D0, D1, ks = 48, 96, 160, [2, 2]
+    X = synth.small_int(160, 0, (Bt, D0), -3, 3); W = synth.small_int(160, 1, (D0, D1), -3, 3); dY = synth.small_int(160, 2, (Bt, D1), -3, 3)
+    iX, iW, iY, idY, idX, idW = range(6)
+    host = {iX: X, iW: W, idY: dY}
+    shapes = {iX: (Bt, D0), iW: (D0, D1), iY: (Bt, D1), idY: (Bt, D1), idX: (Bt, D0), idW: (D0, D1)}
+    one = lambda v: {v: 1}
+    # (description, inputs, output, matmul extents (M, N, K), which inputs are read transposed)
+    ops = [
+        (T.describe([Bt, D1, D0], 2, [((Bt, D0), [one(0), one(2)]), ((D0, D1), [one(2), one(1)])]), [iX, iW], iY, (Bt, D1, D0), (False, False)),
+        (T.describe([Bt, D0, D1], 2, [((Bt, D1), [one(0), one(2)]), ((D0, D1), [one(1), one(2)])]), [idY, iW], idX, (Bt, D0, D1), (False, True)),
+        (T.describe([D0, D1, Bt], 2, [((Bt, D0), [one(2), one(0)]), ((Bt, D1), [one(2), one(1)])]), [iX, idY], idW, (D0, D1, Bt), (True, False)),
+    ]
+    g = L.graph(6, [(d, ins, out, 0) for d, ins, out, _, _ in ops])
+    res = L.recursive(g, ks)
+    n_workers = ks[0] * ks[1]
+    digits = [(w // ks[1], w % ks[1]) for w in range(n_workers)]
+    held = {}
+    for t, arr in host.items():
+        held[t] = []
+        for w in range(n_workers):
+            box = _nested_box(arr.shape, [(res["tensor_dim"][s][t], ks[s], digits[w][s]) for s in range(2)])
+            held[t].append((box, dev(arr[R.box_slices(box)])))
+    results = {}
+    for o, (desc, ins, out_t, (M, N, K), transposed) in enumerate(ops):
+        mm = tofu.matmul_desc(M, N, K)
+        partials = {}
+        for w in range(n_workers):
+            sp = L.worker_splits(res["op_var"], ks, o, w)          # variables (0, 1, 2) are the product's (M, N, K)
+            need = T.regions(desc, sp)                              # boxes in the tensors' own coordinates
+            mreg = tofu.op_regions(mm, sp)
+            operands, keep = [], []
+            for i, t in enumerate(ins):
+                box = need["in_boxes"][i]
+                dst = torch.empty([hi - lo for lo, hi in box], dtype=torch.float32, device=DEV)
+                tofu.region_fetch(tofu.tensor(dst, [lo for lo, _ in box]), [tofu.tensor(b, [lo for lo, _ in bx]) for bx, b in held[t]])
+                keep.append(dst)
+                lo = [lo for lo, _ in box]
+                operands.append(tofu.tensor(dst.t(), lo[::-1]) if transposed[i] else tofu.tensor(dst, lo))
+            # the fetched regions are exactly what the product's shard reads, seen through the views
+            for i in range(2):
+                want_box = [tuple(b) for b in (need["in_boxes"][i][::-1] if transposed[i] else need["in_boxes"][i])]
+                assert [tuple(b) for b in mreg["in_boxes"][i]] == want_box
+            part = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+            tofu.shard_matmul(mm, sp, operands[0], operands[1], tofu.tensor(part), workspace(mm, sp))
+            partials.setdefault(tuple(map(tuple, mreg["out_box"])), []).append(part)
+        out = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        for box, parts in partials.items():
+            sl = R.box_slices(list(box))
+            total = parts[0]
+            if len(parts) > 1:
+                total = torch.empty_like(parts[0])
+                tofu.partition_reduce(total, parts)
+            out[sl] = total[sl]
+        results[out_t] = out.cpu().numpy().astype(np.float64)
+    assert np.array_equal(results[iY], oracle.matmul_box(X, W)[0])
+    assert np.array_equal(results[idX], oracle.matmul_box(dY, np.ascontiguousarray(W.T))[0])
+    assert np.array_equal(results[idW], oracle.matmul_box(np.ascontiguousarray(X.T), dY)[0])
+    assert res["step_elements"][0] <= res["step_elements"][1]
