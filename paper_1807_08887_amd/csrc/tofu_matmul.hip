@@ -9,10 +9,13 @@
 // columns (B) are contiguous along the other index.
 //
 // Kernel: a BM x BN output tile per workgroup, K walked in steps of BK.  Each step stages
-// A[BM x BK] (as k-major As[k][m]) and B[BK x BN] (as Bs[k][n]) in LDS through registers, double-buffered so
-// that the global loads of step t+1 are in flight while the matrix cores work on step t; one
-// barrier per step.  WM x WN wavefronts each own a (BM/WM) x (BN/WN) block of 32x32 MFMA tiles
-// and read their operands from LDS with conflict-free 32-lane rows.  Tall-skinny shards (the
+// A[BM x BK] and B[BK x BN] in LDS through registers, double-buffered so that the global loads
+// of step t+1 are in flight while the matrix cores work on step t; one barrier per step.
+// WM x WN wavefronts each own a (BM/WM) x (BN/WN) block of 32x32 MFMA tiles.  An operand whose
+// global vectors run along k is kept row-major with the step's k values permuted so that the
+// values a lane feeds to four successive MFMAs are one 16-byte LDS read (two 8-byte writes per
+// global vector); an operand whose vectors run along the other index is kept k-major, written
+// whole and read one float per MFMA.  Tall-skinny shards (the
 // M = 128 LSTM gate GEMM) do not have enough output tiles to fill 256 CUs, so the kernel cuts
 // its own K range into slices -- a partition-n-reduce inside the worker -- writes the slices to
 // the caller's workspace and sums them in fixed order with the reduce kernel.
@@ -46,27 +49,35 @@ struct MatmulCfg {
   static constexpr int kThreads = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN;   // wavefront tile
   static constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wavefront
-  // k-major A tile As[k][m].  Vectors along k are transposed on the LDS write: the pitch makes
-  // the writes of a half-wavefront (BK/4 column groups x 128/BK rows) hit 32 different banks.
-  // Vectors along m are written whole and need a pitch of whole vectors.
-  static constexpr int LDA = TA ? BM + 4 : BM + 32 / BK;
-  // Bs[k][n]: whole vectors along n, or (TB) transposing writes with an odd pitch
-  static constexpr int LDB = TB ? BN + 1 : BN + 4;
-  static constexpr int kLdsFloats = 2 * BK * (LDA + LDB);
+  // A tile.  TA (vectors along m): k-major As[k][m], written whole, read one float per MFMA.
+  // Otherwise (vectors along k): m-major As[m][slot] with the step's k values permuted so that
+  // the BK/2 values one lane feeds to successive MFMAs -- k = half, half + 2, half + 4, ... --
+  // are consecutive: slot(k) = (k % 2) * BK/2 + k / 2.  A global vector k0..k0+3 is then two
+  // 8-byte writes, and one 16-byte read serves four MFMA steps.  The pitch of BK + 4 floats
+  // keeps rows 16-byte aligned and sends the eight lanes of a 128-byte read phase to
+  // different banks.
+  static constexpr int LDA = TA ? BM + 4 : BK + 4;
+  static constexpr int kAStage = TA ? BK * LDA : BM * LDA;     // floats of one A buffer
+  // B tile.  Vectors along n: k-major Bs[k][n], written whole.  TB (vectors along k): n-major
+  // Bs[n][slot] with the same permuted k slots as A.
+  static constexpr int LDB = TB ? BK + 4 : BN + 4;
+  static constexpr int kBStage = TB ? BN * LDB : BK * LDB;     // floats of one B buffer
+  static constexpr int kLdsFloats = 2 * (kAStage + kBStage);
   static constexpr int AV = BM * BK / 4 / kThreads;  // 16-byte vectors of A per thread per step
   static constexpr int BV = BK * BN / 4 / kThreads;
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wavefront tile must be made of 32x32 blocks");
   static_assert(AV >= 1 && BV >= 1 && BM * BK / 4 % kThreads == 0 && BK * BN / 4 % kThreads == 0, "staging must divide evenly");
-  static_assert(BK % 4 == 0, "BK must hold whole vectors");
+  static_assert(BK % 8 == 0, "BK must hold whole vectors and whole groups of four MFMA steps per half");
 };
 
 template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB>
 __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p) {
   using Cfg = MatmulCfg<BM, BN, BK, WM, WN, TA, TB>;
   constexpr int NT = Cfg::kThreads, LDA = Cfg::LDA, LDB = Cfg::LDB, FM = Cfg::FM, FN = Cfg::FN;
-  __shared__ float lds[Cfg::kLdsFloats];
-  float* As = lds;                      // [2][BK][LDA]
-  float* Bs = lds + 2 * BK * LDA;       // [2][BK][LDB]
+  __shared__ __attribute__((aligned(16))) float lds[Cfg::kLdsFloats];
+  constexpr int AST = Cfg::kAStage, BST = Cfg::kBStage;
+  float* As = lds;                      // [2][AST]: [BK][LDA] (TA) or [BM][LDA]
+  float* Bs = lds + 2 * AST;            // [2][BST]: [BK][LDB] or (TB) [BN][LDB]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -143,27 +154,31 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
     const int idx = tid + i * NT;
     if (TA) {
       *reinterpret_cast<v4f32*>(as + (idx / (BM / 4)) * LDA + 4 * (idx % (BM / 4))) = ra[i];
-    } else {
+    } else {   // k = 4q, 4q+2 -> slots 2q, 2q+1 of the even half; k = 4q+1, 4q+3 -> the same slots of the odd half
       const int row = idx / (BK / 4), q = idx % (BK / 4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) as[(4 * q + j) * LDA + row] = ra[i][j];
+      typedef float v2f32 __attribute__((ext_vector_type(2)));
+      v2f32 even = {ra[i][0], ra[i][2]}, odd = {ra[i][1], ra[i][3]};
+      *reinterpret_cast<v2f32*>(as + row * LDA + 2 * q) = even;
+      *reinterpret_cast<v2f32*>(as + row * LDA + BK / 2 + 2 * q) = odd;
     }
   };
   auto store_b = [&](float* bs, int i) {
     const int idx = tid + i * NT;
     if (TB) {
       const int col = idx / (BK / 4), q = idx % (BK / 4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bs[(4 * q + j) * LDB + col] = rb[i][j];
+      typedef float v2f32 __attribute__((ext_vector_type(2)));
+      v2f32 even = {rb[i][0], rb[i][2]}, odd = {rb[i][1], rb[i][3]};
+      *reinterpret_cast<v2f32*>(bs + col * LDB + 2 * q) = even;
+      *reinterpret_cast<v2f32*>(bs + col * LDB + BK / 2 + 2 * q) = odd;
     } else {
       *reinterpret_cast<v4f32*>(bs + (idx / (BN / 4)) * LDB + 4 * (idx % (BN / 4))) = rb[i];
     }
   };
   auto store_lds = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < Cfg::AV; ++i) store_a(As + buf * BK * LDA, i);
+    for (int i = 0; i < Cfg::AV; ++i) store_a(As + buf * AST, i);
 #pragma unroll
-    for (int i = 0; i < Cfg::BV; ++i) store_b(Bs + buf * BK * LDB, i);
+    for (int i = 0; i < Cfg::BV; ++i) store_b(Bs + buf * BST, i);
   };
 
   acc16 acc[FM][FN];
@@ -194,19 +209,32 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
   auto run_step = [&](int t, auto hot_tag) {
     constexpr bool HOT = decltype(hot_tag)::value;
     const int buf = t & 1;
-    const float* as = As + buf * BK * LDA + wm * Cfg::TM + l32 + half * LDA;
-    const float* bs = Bs + buf * BK * LDB + wn * Cfg::TN + l32 + half * LDB;
-    float* as_next = As + (buf ^ 1) * BK * LDA;
-    float* bs_next = Bs + (buf ^ 1) * BK * LDB;
+    const float* as = TA ? As + buf * AST + wm * Cfg::TM + l32 + half * LDA
+                         : As + buf * AST + (wm * Cfg::TM + l32) * LDA + half * (BK / 2);
+    const float* bs = TB ? Bs + buf * BST + (wn * Cfg::TN + l32) * LDB + half * (BK / 2)
+                         : Bs + buf * BST + wn * Cfg::TN + l32 + half * LDB;
+    float* as_next = As + (buf ^ 1) * AST;
+    float* bs_next = Bs + (buf ^ 1) * BST;
     const int nxt = min(t + 2, steps - 1), k0 = k_begin + nxt * BK;
     const uint32_t a_soff = 4u * (uint32_t)((int64_t)k0 * p.a_cs), b_soff = 4u * (uint32_t)((int64_t)k0 * p.b_rs);
     // operands of k-step s+1 are fetched before the MFMAs of k-step s are issued
     float a[2][FM], b[2][FN];
+    v4f32 ag[2][FM], bg[2][FN];                // vectors along k: the values of four MFMA steps per 16-byte read
     auto fetch = [&](int s, float (&av)[FM], float (&bv)[FN]) {
+      if constexpr (TA) {
 #pragma unroll
-      for (int i = 0; i < FM; ++i) av[i] = as[2 * s * LDA + i * 32];
+        for (int i = 0; i < FM; ++i) av[i] = as[2 * s * LDA + i * 32];
+      } else if (s % 4 == 0) {
 #pragma unroll
-      for (int j = 0; j < FN; ++j) bv[j] = bs[2 * s * LDB + j * 32];
+        for (int i = 0; i < FM; ++i) ag[(s / 4) & 1][i] = *reinterpret_cast<const v4f32*>(as + i * 32 * LDA + s);
+      }
+      if constexpr (!TB) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bv[j] = bs[2 * s * LDB + j * 32];
+      } else if (s % 4 == 0) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bg[(s / 4) & 1][j] = *reinterpret_cast<const v4f32*>(bs + j * 32 * LDB + s);
+      }
     };
     fetch(0, a[0], b[0]);
 #pragma unroll
@@ -232,7 +260,7 @@ __global__ void __launch_bounds__(64 * WM * WN) matmul_kernel(const MatmulArgs p
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(a[s & 1][i], b[s & 1][j], acc[i][j]);
+        for (int j = 0; j < FN; ++j) acc[i][j] = mfma_32x32x2(TA ? a[s & 1][i] : ag[(s / 4) & 1][i][s % 4], TB ? bg[(s / 4) & 1][j][s % 4] : b[s & 1][j], acc[i][j]);
     }
     __syncthreads();
   };
