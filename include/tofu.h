@@ -325,6 +325,22 @@ int tofu_shard_conv2d_dgrad_accumulate(const tofu_op_desc_t* op, const tofu_spli
                                        const tofu_tensor_t* dy, const tofu_tensor_t* w, const tofu_tensor_t* dx,
                                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* tofu_shard_matmul for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * checks, kernels and results (bit for bit) as tofu_shard_matmul, but the K slices of a
+ * tall-skinny shard go to an array of TOFU_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's device image; each GPU the library runs on holds its copy until the process ends.
+ * The call allocates and frees nothing and synchronises nothing.  A shard whose K slices need
+ * more (tofu_workspace_bytes tells) -> WORKSPACE_TOO_SMALL, nothing launched.  The array's device
+ * address is looked up on the first call on each device (make that call outside stream capture);
+ * `hip_stream` must belong to the current device.  Every call on a GPU shares that GPU's array:
+ * nothing in it has to be cleared (every slice element read was written by the same call), but
+ * calls that overlap in time on one GPU race -- order them on one stream. */
+#define TOFU_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int tofu_shard_matmul_noalloc(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                              const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C,
+                              void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ import os
 from typing import Optional, Sequence
 
 TOFU_MAX_DIMS = 6
+STATIC_SCRATCH_BYTES = 32 << 20      # TOFU_STATIC_SCRATCH_BYTES of include/tofu.h
 OP_MATMUL, OP_CONV2D, OP_CONV2D_WGRAD, OP_CONV2D_DGRAD, OP_LSTM_CELL, OP_CONV1D = 0, 1, 2, 3, 4, 5
 LSTM_DIM_B, LSTM_DIM_H = 0, 1
 CONV1D_DIM_B, CONV1D_DIM_CO, CONV1D_DIM_X, CONV1D_DIM_CI = 0, 1, 2, 3
@@ -89,6 +90,8 @@ def load():
     accumulate_calls = tuple(n + "_accumulate" for n in shard_calls)
     for name in shard_calls + accumulate_calls:
         getattr(lib, name).argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp, sz, vp]
+    lib.tofu_shard_matmul_noalloc.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), vp]
+    lib.tofu_shard_matmul_noalloc.restype = ctypes.c_int
     lib.tofu_shard_conv2d_fused.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), i32, P(Tensor), P(Tensor), vp, sz, vp]
     lib.tofu_partition_reduce.argtypes = [vp, P(vp), i32, i64, vp]
     lib.tofu_shard_lstm_cell.argtypes = [P(OpDesc), P(Split), i32, P(Tensor), P(Tensor), P(Tensor), P(Tensor), vp]
@@ -207,6 +210,12 @@ def _shard(fn, op, splits, a, b, c, workspace, stream):
 
 def shard_matmul(op, splits, A: Tensor, B: Tensor, C: Tensor, workspace=None, stream=None) -> None:
     _shard(load().tofu_shard_matmul, op, splits, A, B, C, workspace, stream)
+
+
+def shard_matmul_noalloc(op, splits, A: Tensor, B: Tensor, C: Tensor, stream=None) -> None:
+    """tofu_shard_matmul_noalloc: the K slices go to the library's built-in device array."""
+    arr, n = _splits(splits)
+    _check(load().tofu_shard_matmul_noalloc(ctypes.byref(op), arr, n, ctypes.byref(A), ctypes.byref(B), ctypes.byref(C), _stream(stream)))
 
 
 def shard_conv2d(op, splits, x: Tensor, w: Tensor, y: Tensor, workspace=None, stream=None) -> None:

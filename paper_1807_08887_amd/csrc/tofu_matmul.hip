@@ -21,6 +21,7 @@
 // the caller's workspace and sums them in fixed order with the reduce kernel.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "tofu_internal.h"
@@ -410,4 +411,53 @@ extern "C" int tofu_shard_matmul_accumulate(const tofu_op_desc_t* op, const tofu
                                             const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* workspace,
                                             size_t workspace_bytes, void* hip_stream) {
   return tofu::shard_matmul(op, splits, nsplits, A, B, C, workspace, workspace_bytes, hip_stream, true);
+}
+
+// ---- the same shard for callers that cannot allocate -------------------------------------
+// The K slices go to a fixed array in device memory instead of a caller-owned workspace.  In host
+// code the array's name is only a handle: its device address is looked up once per device with
+// hipGetSymbolAddress and kept; every launch takes that address, never the name.
+namespace tofu {
+
+constexpr size_t kStaticScratchBytes = TOFU_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_addr[kMaxDevices];   // device address of `scratch` on each device, 0 until looked up
+static std::mutex g_scratch_mutex;
+
+// Address of this device's copy of `scratch` (each GPU holds its own copy at its own address).
+static int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(TOFU_ERR_UNSUPPORTED, "device index %d outside [0,%d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail(TOFU_ERR_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_addr[dev] = ptr;
+  }
+  *out = g_scratch_addr[dev];
+  return TOFU_OK;
+}
+
+}  // namespace tofu
+
+extern "C" int tofu_shard_matmul_noalloc(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,
+                                         const tofu_tensor_t* A, const tofu_tensor_t* B, const tofu_tensor_t* C, void* hip_stream) {
+  using namespace tofu;
+  if (!op || op->kind != TOFU_OP_MATMUL) return fail(TOFU_ERR_INVALID_ARG, "operator description is not a matmul");
+  // size check first, on the host, before anything touches the device (0 also for an invalid plan: the shard call reports that)
+  const size_t need = tofu_workspace_bytes(op, splits, nsplits);
+  if (need > kStaticScratchBytes)
+    return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "matmul shard needs %zu bytes for its K slices; the built-in scratch array holds %zu: use tofu_shard_matmul with a workspace",
+                need, kStaticScratchBytes);
+  void* ws = nullptr;
+  if (need > 0) {
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+  }
+  return shard_matmul(op, splits, nsplits, A, B, C, ws, need > 0 ? kStaticScratchBytes : 0, hip_stream, false);
 }
