@@ -5,7 +5,7 @@ in the HIP kernels of libtofu.so; Python only marshals arguments.  PyTorch is us
 memory and streams.
 """
 from .binding import (TOFU_MAX_DIMS, OpDesc, Region, Split, Tensor, TofuError, conv2d_desc, dgrad_desc, last_error, lstm_cell_desc, shard_lstm_cell, lib_path,  # noqa: F401
-                      load, matmul_desc, op_regions, partition_reduce, probe_copy, probe_mfma, region_fetch, shard_conv2d, shard_conv2d_dgrad, shard_conv2d_fused, shard_conv2d_wgrad,
+                      load, matmul_desc, op_regions, partition_reduce, probe_copy, probe_mfma, probe_read, probe_stream, region_fetch, shard_conv2d, shard_conv2d_dgrad, shard_conv2d_fused, shard_conv2d_wgrad,
                       shard_matmul, shard_range, tensor, wgrad_desc, workspace_bytes, partition_reduce_scatter, shard_matmul_accumulate,
                       shard_conv2d_accumulate, shard_conv2d_wgrad_accumulate, shard_conv2d_dgrad_accumulate, conv1d_desc, shard_conv1d,
                       shard_conv1d_accumulate, shard_matmul_noalloc, OP_CONV1D, CONV1D_DIM_B, CONV1D_DIM_CO, CONV1D_DIM_X, CONV1D_DIM_CI)

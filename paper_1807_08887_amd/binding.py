@@ -99,6 +99,9 @@ def load():
     lib.tofu_partition_reduce_scatter.argtypes = [vp, P(vp), i32, i64, i32, i32, i32, i32, vp]
     lib.tofu_probe_mfma.argtypes = [vp, i32, i32, vp]
     lib.tofu_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.tofu_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.tofu_probe_stream.argtypes = [vp, P(vp), i32, sz, vp]
+    lib.tofu_probe_read.restype = lib.tofu_probe_stream.restype = ctypes.c_int
     for name in ("tofu_shard_range", "tofu_op_regions", "tofu_region_fetch", "tofu_shard_matmul", "tofu_shard_conv2d",
                  "tofu_shard_conv2d_wgrad", "tofu_partition_reduce", "tofu_probe_mfma", "tofu_probe_copy", "tofu_shard_conv2d_fused", "tofu_shard_conv2d_dgrad", "tofu_partition_reduce_ex", "tofu_shard_lstm_cell",
                  "tofu_partition_reduce_scatter") + accumulate_calls:
@@ -323,3 +326,18 @@ def probe_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
     if nbytes is None:
         nbytes = src.numel() * src.element_size()
     _check(load().tofu_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes, _stream(stream)))
+
+
+def probe_read(src, sink, nbytes: Optional[int] = None, stream=None) -> None:
+    """include/tofu_probe.h: read-only nontemporal stream over a device tensor."""
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    _check(load().tofu_probe_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def probe_stream(dst, srcs: Sequence, nbytes: Optional[int] = None, stream=None) -> None:
+    """include/tofu_probe.h: k:1 read:write stream, dst = sum of the k sources (k in 1, 2, 4, 8)."""
+    if nbytes is None:
+        nbytes = dst.numel() * dst.element_size()
+    ptrs = (ctypes.c_void_p * max(1, len(srcs)))(*[t.data_ptr() for t in srcs])
+    _check(load().tofu_probe_stream(ctypes.c_void_p(dst.data_ptr()), ptrs, len(srcs), nbytes, _stream(stream)))

@@ -5,9 +5,14 @@
 // tree of workers (Sec. 5.2): fold(l, r) = fold(l, m) (+) fold(m, r), m = l + ceil((r - l) / 2).
 //
 // Pure streaming: k reads and one write per element, no reuse, so the kernel is bound by HBM
-// bandwidth.  Each lane owns 16-byte vectors, issues all k loads of a vector before the first
-// add (k independent requests in flight per lane), and never uses atomics, so the result does
-// not depend on the launch shape and is identical from run to run.
+// bandwidth, and what decides the rate is the ORDER in which the requests reach the memory: a
+// workgroup is one wavefront that owns a contiguous chunk of 64 * VPL 16-byte vectors (8 KB per
+// input for VPL = 8) and reads it input by input -- the whole 8 KB run of input 0, then of input
+// 1, ... -- folding as it goes.  Reading the same bytes vector by vector across the k inputs
+// (1 KB from each in turn) measured 15 - 20 % slower (27.5 against 23.3 us for the 151 MB gate
+// reduction, 96 against 84 us for the 531 MB one), and so did a grid-wide stride between a
+// lane's vectors.  No atomics: the result does not depend on the launch shape and is identical
+// from run to run.
 #include <hip/hip_runtime.h>
 
 #include "tofu_internal.h"
@@ -21,14 +26,10 @@ struct ReducePtrs {
   const float* p[kMaxReduceK];
 };
 
-constexpr int kReduceThreads = 512;
-constexpr int kReduceMaxBlocks = 16384;
-// Inputs are read with the streaming (nontemporal) hint: measured cold (inside the whole-step
-// benchmark) it is the faster choice for both the 151 MB and the 531 MB reduction.
-template <bool NT>
-__device__ __forceinline__ v4f ld_vec(const v4f* p) {
-  return NT ? __builtin_nontemporal_load(p) : *p;
-}
+constexpr int kReduceThreads = 64;       // one wavefront per workgroup
+// Inputs and output carry the streaming (nontemporal) hint: measured cold it is the faster
+// choice for both the 151 MB and the 531 MB reduction.
+__device__ __forceinline__ v4f ld_vec(const v4f* p) { return __builtin_nontemporal_load(p); }
 
 // MODE: 0 sum left to right, 1 sum pairwise, 2 product left to right, 3 product pairwise, 4 max, 5 min
 template <int MODE, typename T>
@@ -57,35 +58,62 @@ __device__ __forceinline__ T fold(const T* v) {
   }
 }
 
-template <int K, int UNROLL, bool NT, int MODE>
-__global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restrict__ dst_all, ReducePtrs src_all, int64_t n_vec, int64_t count, int head) {
+// INPLACE: dst is the first input (in-place aggregation); every element is read and then written
+// by the same lane, and the pointers carry no __restrict__.  Otherwise dst overlaps no input and
+// says so, which lets the stores of finished vectors go out between the loads of later ones.
+template <bool INPLACE> struct DstPtr { typedef float* __restrict__ type; };
+template <> struct DstPtr<true> { typedef float* type; };
+
+template <int K, int VPL, int MODE, bool INPLACE>
+__global__ void __launch_bounds__(kReduceThreads) reduce_kernel(typename DstPtr<INPLACE>::type dst_all, ReducePtrs src_all, int64_t n_vec, int64_t count, int head) {
   // elements [head, head + 4 * n_vec) are whole aligned vectors; the `head` elements before them and the rest after are scalar work
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  float* dst = dst_all + head;
-  ReducePtrs src;
+  constexpr int CHUNK = kReduceThreads * VPL;
+  constexpr bool PAIRWISE = MODE == 1 || MODE == 3;
+  const int64_t base = (int64_t)blockIdx.x * CHUNK;
+  if (base + CHUNK <= n_vec) {            // a whole chunk, input by input; the scheduling barriers keep that order
+    v4f* d = reinterpret_cast<v4f*>(dst_all + head) + base + threadIdx.x;
+    if constexpr (!PAIRWISE) {            // left to right (any order for max / min): fold as the inputs arrive
+      v4f acc[VPL];
+      {
+        const v4f* p = reinterpret_cast<const v4f*>(src_all.p[0] + head) + base + threadIdx.x;
 #pragma unroll
-  for (int j = 0; j < K; ++j) src.p[j] = src_all.p[j] + head;
-  // main part: UNROLL vectors per trip, all loads first
-  for (; i + (UNROLL - 1) * stride < n_vec; i += UNROLL * stride) {
-    v4f v[UNROLL][K];
+        for (int u = 0; u < VPL; ++u) acc[u] = ld_vec(p + u * kReduceThreads);
+      }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
+      for (int j = 1; j < K; ++j) {
+        const v4f* p = reinterpret_cast<const v4f*>(src_all.p[j] + head) + base + threadIdx.x;
+        v4f t[VPL];
 #pragma unroll
-      for (int j = 0; j < K; ++j) v[u][j] = ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[j]) + i + u * stride);
+        for (int u = 0; u < VPL; ++u) t[u] = ld_vec(p + u * kReduceThreads);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
-      __builtin_nontemporal_store(fold<MODE, K>(v[u]), reinterpret_cast<v4f*>(dst) + i + u * stride);
-  }
-  for (; i < n_vec; i += stride) {
-    v4f v[K];
+        for (int u = 0; u < VPL; ++u) acc[u] = combine<MODE>(acc[u], t[u]);
+      }
 #pragma unroll
-    for (int j = 0; j < K; ++j) v[j] = ld_vec<NT>(reinterpret_cast<const v4f*>(src.p[j]) + i);
-    __builtin_nontemporal_store(fold<MODE, K>(v), reinterpret_cast<v4f*>(dst) + i);
+      for (int u = 0; u < VPL; ++u) __builtin_nontemporal_store(acc[u], d + u * kReduceThreads);
+    } else {                              // pairwise: every input's value is kept until the tree is folded
+      v4f v[VPL][K];
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        const v4f* p = reinterpret_cast<const v4f*>(src_all.p[j] + head) + base + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < VPL; ++u) v[u][j] = ld_vec(p + u * kReduceThreads);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int u = 0; u < VPL; ++u) __builtin_nontemporal_store(fold<MODE, K>(v[u]), d + u * kReduceThreads);
+    }
+  } else {                                // the ragged last chunk, one vector at a time
+    for (int64_t i = base + threadIdx.x; i < n_vec; i += kReduceThreads) {
+      v4f v[K];
+#pragma unroll
+      for (int j = 0; j < K; ++j) v[j] = ld_vec(reinterpret_cast<const v4f*>(src_all.p[j] + head) + i);
+      __builtin_nontemporal_store(fold<MODE, K>(v), reinterpret_cast<v4f*>(dst_all + head) + i);
+    }
   }
   // scalar work: the head, the tail, or the whole array when the pointers do not share one 16-byte phase
-  const int64_t left = count - n_vec * 4;
-  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < left; r += stride) {
+  const int64_t left = count - n_vec * 4, stride = (int64_t)gridDim.x * kReduceThreads;
+  for (int64_t r = (int64_t)blockIdx.x * kReduceThreads + threadIdx.x; r < left; r += stride) {
     const int64_t e = r < head ? r : r + n_vec * 4;
     float v[K];
 #pragma unroll
@@ -94,16 +122,25 @@ __global__ void __launch_bounds__(kReduceThreads) reduce_kernel(float* __restric
   }
 }
 
+// Vectors per lane: 8 (an 8 KB run per input and wavefront); the pairwise orders keep all k * VPL
+// values in registers and take 4 when k > 8.
+template <int K, int MODE> struct ReduceVpl { static constexpr int value = ((MODE == 1 || MODE == 3) && K > 8) ? 4 : 8; };
+
 template <int K, int MODE>
-static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, int blocks, hipStream_t s) {
-  constexpr int U = K <= 4 ? 4 : K <= 8 ? 2 : 1;
-  hipLaunchKernelGGL((reduce_kernel<K, U, true, MODE>), dim3(blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count, head);
+static void launch_k(float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, hipStream_t s) {
+  constexpr int VPL = ReduceVpl<K, MODE>::value;
+  constexpr int64_t chunk = (int64_t)kReduceThreads * VPL;
+  // one workgroup per chunk of vectors; without a vector part (pointers out of phase) a grid-stride loop over elements
+  int64_t blocks = n_vec > 0 ? (n_vec + chunk - 1) / chunk : (count + 4 * kReduceThreads - 1) / (4 * kReduceThreads);
+  if (n_vec == 0 && blocks > 16384) blocks = 16384;
+  if (dst == src.p[0]) hipLaunchKernelGGL((reduce_kernel<K, VPL, MODE, true>), dim3((unsigned)blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count, head);
+  else hipLaunchKernelGGL((reduce_kernel<K, VPL, MODE, false>), dim3((unsigned)blocks), dim3(kReduceThreads), 0, s, dst, src, n_vec, count, head);
 }
 
 template <int MODE>
-static bool launch_mode(int k, float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, int blocks, hipStream_t s) {
+static bool launch_mode(int k, float* dst, const ReducePtrs& src, int64_t n_vec, int64_t count, int head, hipStream_t s) {
   switch (k) {
-#define TOFU_CASE(K) case K: launch_k<K, MODE>(dst, src, n_vec, count, head, blocks, s); return true;
+#define TOFU_CASE(K) case K: launch_k<K, MODE>(dst, src, n_vec, count, head, s); return true;
     TOFU_CASE(1) TOFU_CASE(2) TOFU_CASE(3) TOFU_CASE(4) TOFU_CASE(5) TOFU_CASE(6) TOFU_CASE(7) TOFU_CASE(8)
     TOFU_CASE(9) TOFU_CASE(10) TOFU_CASE(11) TOFU_CASE(12) TOFU_CASE(13) TOFU_CASE(14) TOFU_CASE(15) TOFU_CASE(16)
 #undef TOFU_CASE
@@ -129,19 +166,16 @@ int launch_reduce_mode(float* dst, const float* const* parts, int k, int64_t cou
   int head = aligned ? (int)((16 - phase) % 16 / 4) : 0;
   if (head > count) head = (int)count;
   const int64_t n_vec = aligned ? (count - head) / 4 : 0;
-  // Enough resident lanes to cover HBM latency, few enough that every lane streams several vectors.
-  int64_t work = n_vec > 0 ? n_vec : count;
-  int64_t want = (work + kReduceThreads - 1) / kReduceThreads;
-  int blocks = (int)(want < kReduceMaxBlocks ? (want < 1 ? 1 : want) : kReduceMaxBlocks);
+  if (n_vec >= ((int64_t)1 << 31) * 64) return fail(TOFU_ERR_UNSUPPORTED, "reduce: more than 2^37 vectors in one call; split it");
   hipStream_t s = static_cast<hipStream_t>(stream);
   bool ok = false;
   switch (mode) {
-    case 0: ok = launch_mode<0>(k, dst, src, n_vec, count, head, blocks, s); break;
-    case 1: ok = launch_mode<1>(k, dst, src, n_vec, count, head, blocks, s); break;
-    case 2: ok = launch_mode<2>(k, dst, src, n_vec, count, head, blocks, s); break;
-    case 3: ok = launch_mode<3>(k, dst, src, n_vec, count, head, blocks, s); break;
-    case 4: ok = launch_mode<4>(k, dst, src, n_vec, count, head, blocks, s); break;
-    case 5: ok = launch_mode<5>(k, dst, src, n_vec, count, head, blocks, s); break;
+    case 0: ok = launch_mode<0>(k, dst, src, n_vec, count, head, s); break;
+    case 1: ok = launch_mode<1>(k, dst, src, n_vec, count, head, s); break;
+    case 2: ok = launch_mode<2>(k, dst, src, n_vec, count, head, s); break;
+    case 3: ok = launch_mode<3>(k, dst, src, n_vec, count, head, s); break;
+    case 4: ok = launch_mode<4>(k, dst, src, n_vec, count, head, s); break;
+    case 5: ok = launch_mode<5>(k, dst, src, n_vec, count, head, s); break;
     default: break;
   }
   if (!ok) return fail(TOFU_ERR_INVALID_ARG, "k = %d outside [1,%d] or unknown reduction mode %d", k, kMaxReduceK, mode);

@@ -717,8 +717,15 @@ def test_probes_copy_exactly_and_leave_the_sink_alone():
     assert torch.equal(dst, src)
     sink = torch.full((64,), 3.0, dtype=torch.float32, device=DEV)
     tofu.probe_mfma(sink, 16, 8)
+    tofu.probe_read(src, sink)
     torch.cuda.synchronize()
     assert (sink == 3.0).all()
+    # the k:1 stream: small integers, so the sum is exact; a ragged count exercises the last chunk
+    for k in (1, 2, 4, 8):
+        parts = [dev(synth.small_int(78, j, (4 * 70001,), -8, 8)) for j in range(k)]
+        out = torch.zeros_like(parts[0])
+        tofu.probe_stream(out, parts)
+        assert torch.equal(out, torch.stack(parts).sum(0))
 
 
 # ----------------------------------------------------------------------------- reduce-scatter share, fused accumulation

@@ -316,6 +316,14 @@ def test_probe_error_paths_are_checked_on_the_host():
     assert lib.tofu_probe_copy(vp(FAKE + 4), vp(FAKE + 4096), 16, None) == -1  # misaligned
     assert lib.tofu_probe_copy(vp(FAKE), vp(FAKE + 4096), 0, None) == 0        # nothing to do, nothing launched
     assert "copy probe" in tofu.last_error() or tofu.last_error() is not None
+    assert lib.tofu_probe_read(vp(0), 16, vp(FAKE), None) == -1
+    assert lib.tofu_probe_read(vp(FAKE), 24, vp(FAKE), None) == -1
+    assert lib.tofu_probe_read(vp(FAKE), 0, vp(FAKE), None) == 0
+    srcs = (vp * 8)(*[FAKE + 4096 * (j + 1) for j in range(8)])
+    assert lib.tofu_probe_stream(vp(FAKE), srcs, 3, 16, None) == -1             # k must be 1, 2, 4 or 8
+    assert lib.tofu_probe_stream(vp(FAKE), srcs, 8, 20, None) == -1
+    assert lib.tofu_probe_stream(vp(0), srcs, 8, 16, None) == -1
+    assert lib.tofu_probe_stream(vp(FAKE), srcs, 8, 0, None) == 0
 
 
 def test_size_limits_are_reported_not_overflowed():

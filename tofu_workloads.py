@@ -45,6 +45,7 @@ class Leg:
     out: torch.Tensor          # device tensor the leg writes (full buffer)
     host: Dict[str, object] = field(default_factory=dict)   # host arrays / parameters for checking
     conventional_flop: float = 0.0                            # dense 9-tap count, for reference
+    cold: List[Callable[[], None]] = field(default_factory=list)   # the same call on rotating copies of the operands (streaming legs)
 
 
 def _conv_valid_taps(h_lo, h_hi, w_lo, w_hi, H, W, pad=1):
@@ -70,7 +71,18 @@ EXTRA_LEGS = ("conv_cout_h_fused", "gemm_dx_nsplit", "gemm_dw_nsplit", "dgrad_co
               "wgrad_batch_accumulate", "conv1d_cout")
 
 
-def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
+def _rotations(make_call, operands, copies):
+    """The leg's call on `copies` fresh copies of its operand tensors: launched in turn, every launch finds its
+    operands evicted from the 256 MB last-level cache by the launches before it."""
+    runs, keep = [], []
+    for _ in range(copies):
+        clone = [[t.clone() for t in o] if isinstance(o, (list, tuple)) else o.clone() for o in operands]
+        keep.append(clone)
+        runs.append(make_call(*clone))
+    return runs, keep
+
+
+def build(dev: str = "cuda:0", which=None, keep_host: bool = True, cold_copies: bool = False) -> List[Leg]:
     which = set(which) if which else None
     want = lambda *names: which is None or any(n in which for n in names)
     legs: List[Leg] = []
@@ -167,6 +179,8 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
             legs.append(Leg("reduce_gates", "hbm", 4.0 * M * N * (k + 1),
                             _call(tofu.partition_reduce, gates, order), gates,
                             dict(kind="reduce", remote=remote, own_index=s, own=part, keep=order) if keep_host else dict(keep=order)))
+            if cold_copies:      # 4 x 151 MB
+                legs[-1].cold, legs[-1].host["cold_keep"] = _rotations(lambda o, p: _call(tofu.partition_reduce, o, p), [gates, order], 4)
 
     # ------------------------------------------------------------------ Wide-ResNet conv forward
     if want("conv_cout", "fetch_halo", "conv_cout_h") or extra("conv_cout_h_fused"):
@@ -202,6 +216,11 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
         if want("fetch_halo"):
             legs.append(Leg("fetch_halo", "hbm", nbytes, _call(tofu.region_fetch, t_region, srcs), region,
                             dict(kind="fetch", x=x if keep_host else None, box=box, keep=(own, halo))))
+            if cold_copies:      # 3 x 294 MB
+                lo_box = [lo for lo, _ in box]
+                legs[-1].cold, legs[-1].host["cold_keep"] = _rotations(
+                    lambda r, o, h: _call(tofu.region_fetch, tofu.tensor(r, lo_box), [tofu.tensor(o, [0, 0, 0, 0]), tofu.tensor(h, [0, 0, h_cut, 0])]),
+                    [region, own, halo], 3)
         if want("conv_cout_h"):
             (h0, h1) = reg2["out_box"][2]
             y2 = torch.zeros(NB, co1 - co0, h1 - h0, W, dtype=torch.float32, device=dev)
@@ -292,4 +311,6 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True) -> List[Leg]:
             legs.append(Leg("reduce_dw", "hbm", 4.0 * C * C * 9 * (k + 1),
                             _call(tofu.partition_reduce, dw_full, order), dw_full,
                             dict(kind="reduce", remote=remote, own_index=s, own=part_w, keep=order) if keep_host else dict(keep=order)))
+            if cold_copies:      # 2 x 531 MB
+                legs[-1].cold, legs[-1].host["cold_keep"] = _rotations(lambda o, p: _call(tofu.partition_reduce, o, p), [dw_full, order], 2)
     return legs
