@@ -80,6 +80,25 @@ def apply_splits(op: dict, splits):
     return rng
 
 
+def worker_splits(dims_per_step, ks, worker: int):
+    """Split list of worker `worker` under a recursive plan (Appendix A.1: a plan is the sequence
+    of basic plans; Sec. 5.2: step i cuts every worker group of step i-1 into k_i groups).  The
+    k_1 * ... * k_m workers are numbered group by group: the step-1 group is the slowest-varying
+    part of the worker number.  dims_per_step[i] is the dimension the operator is cut along at
+    step i.  -> [(dim, k_i, which of the k_i parts), ...]."""
+    group_size = 1
+    for k in ks:
+        group_size *= k
+    if not 0 <= worker < group_size:
+        raise ValueError("worker outside the plan's worker count")
+    out = []
+    for dim, k in zip(dims_per_step, ks):
+        group_size //= k                      # workers in one group once this step has cut
+        out.append((dim, k, worker // group_size))
+        worker %= group_size
+    return out
+
+
 def _window(out_lo, out_hi, ksize, stride, pad, size):
     """Input coordinates touched by outputs [out_lo,out_hi) through index o*stride + d - pad,
     d in [0,ksize): the widened ("halo") range, its clipped part and the zero rows cut off."""

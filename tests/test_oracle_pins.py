@@ -615,3 +615,27 @@ def test_conv1d_pnr_invariant_on_the_oracle(k):
     for dim in ["B", "CO", "X", "CI"]:
         got = _assemble(op, dim, k, lambda reg: oracle.conv1d_box(data, filt, box=reg["out_box"], cirange=reg["ranges"]["CI"])[0])
         assert np.array_equal(got, full), dim
+
+
+# ----------------------------------------------------------------------------- workers of a recursive plan
+def test_worker_numbering_of_a_recursive_plan():
+    """Appendix A.1 / Sec. 5.2: pins of oracle.regions.worker_splits.  (1) Three 2-way steps on one
+    dimension give worker w the w-th eighth (the composition rule of readings 3), which fixes the
+    digit order; (2) the 2 x 2 grid of Sec. 5.2's figure numbers its quadrants row by row;
+    (3) for mixed step sizes over different dimensions the workers' shards tile the iteration
+    space exactly (every coordinate marked once)."""
+    op = dict(kind="matmul", M=16, N=12, K=24)
+    for w in range(8):
+        rng = R.apply_splits(op, R.worker_splits(["K", "K", "K"], [2, 2, 2], w))
+        assert rng["K"] == R.shard_range(24, 8, w)
+    quad = [R.apply_splits(op, R.worker_splits(["M", "N"], [2, 2], w)) for w in range(4)]
+    assert [(q["M"], q["N"]) for q in quad] == [((0, 8), (0, 6)), ((0, 8), (6, 12)), ((8, 16), (0, 6)), ((8, 16), (6, 12))]
+    for dims, ks in [(["M", "K", "N"], [2, 3, 2]), (["N", "N", "M"], [3, 2, 4]), (["K"], [5])]:
+        seen = np.zeros((16, 12, 24), dtype=np.int32)
+        total = int(np.prod(ks))
+        for w in range(total):
+            r = R.apply_splits(op, R.worker_splits(dims, ks, w))
+            seen[r["M"][0]:r["M"][1], r["N"][0]:r["N"][1], r["K"][0]:r["K"][1]] += 1
+        assert (seen == 1).all()
+    with pytest.raises(ValueError):
+        R.worker_splits(["M"], [2], 2)
