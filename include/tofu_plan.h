@@ -106,6 +106,20 @@ int tofu_plan_basic(const tofu_plan_graph_t* g, int32_t k, int32_t* tensor_dim, 
 int tofu_plan_recursive(const tofu_plan_graph_t* g, const int32_t* ks, int32_t steps,
                         int32_t* tensor_dim, int32_t* op_var, int64_t* step_elements, int64_t* total);
 
+/* Worker `worker`'s shard of operator `op` under a recursive plan (Appendix A.1: a plan is the
+ * sequence of basic plans <p_1, ..., p_m>; Sec. 5.2: step i cuts every group of step i-1 k_i
+ * ways).  The k = ks[0] * ... * ks[steps-1] workers are numbered so that the step-1 group is the
+ * most significant digit of the worker number in the mixed radix (ks[0], ..., ks[steps-1]):
+ * worker = ((d_0 * ks[1] + d_1) * ks[2] + d_2) ..., 0 <= d_s < ks[s].  Writes
+ *   splits[s] = (op_var[s * n_ops + op], ks[s], d_s),  s = 0 .. steps-1,
+ * the split list the shard calls of tofu.h and tofu_tdl_regions take (`splits` is a HOST array of
+ * `steps` entries; op_var as tofu_plan_recursive returns it).  The shards of all k workers tile
+ * the operator's iteration space exactly.
+ * Errors: INVALID_ARG for NULL arrays, steps outside [1, TOFU_PLAN_MAX_STEPS], a ks[s] < 2,
+ * op outside [0, n_ops), worker outside [0, k) or a negative variable. */
+int tofu_plan_worker_splits(const int32_t* op_var, int32_t n_ops, const int32_t* ks, int32_t steps,
+                            int32_t op, int64_t worker, tofu_split_t* splits);
+
 #ifdef __cplusplus
 }
 #endif

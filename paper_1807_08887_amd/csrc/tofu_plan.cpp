@@ -370,3 +370,28 @@ extern "C" int tofu_plan_recursive(const tofu_plan_graph_t* g, const int32_t* ks
   if (total) *total = sum;
   return TOFU_OK;
 }
+
+extern "C" int tofu_plan_worker_splits(const int32_t* op_var, int32_t n_ops, const int32_t* ks, int32_t steps, int32_t op,
+                                       int64_t worker, tofu_split_t* splits) {
+  if (!op_var || !ks || !splits) return fail(TOFU_ERR_INVALID_ARG, "op_var, ks or splits is NULL");
+  if (steps < 1 || steps > TOFU_PLAN_MAX_STEPS) return fail(TOFU_ERR_INVALID_ARG, "steps = %d outside [1,%d]", (int)steps, TOFU_PLAN_MAX_STEPS);
+  if (n_ops < 1 || op < 0 || op >= n_ops) return fail(TOFU_ERR_INVALID_ARG, "operator %d outside [0,%d)", (int)op, (int)n_ops);
+  int64_t k = 1;
+  for (int s = 0; s < steps; ++s) {
+    if (ks[s] < 2) return fail(TOFU_ERR_INVALID_ARG, "ks[%d] = %d: every step needs at least two workers", s, (int)ks[s]);
+    if (k > kInf / ks[s]) return fail(TOFU_ERR_UNSUPPORTED, "worker count overflows 64 bits");
+    k *= ks[s];
+  }
+  if (worker < 0 || worker >= k) return fail(TOFU_ERR_INVALID_ARG, "worker %lld outside [0,%lld)", (long long)worker, (long long)k);
+  // digits of the worker number, least significant (the last step) first
+  int64_t w = worker;
+  for (int s = steps - 1; s >= 0; --s) {
+    const int32_t var = op_var[(size_t)s * n_ops + op];
+    if (var < 0) return fail(TOFU_ERR_INVALID_ARG, "step %d has no variable for operator %d", s, (int)op);
+    splits[s].dim = var;
+    splits[s].k = ks[s];
+    splits[s].shard = (int32_t)(w % ks[s]);
+    w /= ks[s];
+  }
+  return TOFU_OK;
+}

@@ -30,7 +30,9 @@ def _lib():
         lib.tofu_plan_cost.argtypes = [P(PlanGraph), _i32, P(_i32), P(_i32), P(_i64)]
         lib.tofu_plan_basic.argtypes = [P(PlanGraph), _i32, P(_i32), P(_i32), P(_i64), P(_i64)]
         lib.tofu_plan_recursive.argtypes = [P(PlanGraph), P(_i32), _i32, P(_i32), P(_i32), P(_i64), P(_i64)]
-        for n in ("tofu_plan_strategy_cost", "tofu_plan_cost", "tofu_plan_basic", "tofu_plan_recursive"):
+        from .binding import Split
+        lib.tofu_plan_worker_splits.argtypes = [P(_i32), _i32, P(_i32), _i32, _i32, _i64, P(Split)]
+        for n in ("tofu_plan_strategy_cost", "tofu_plan_cost", "tofu_plan_basic", "tofu_plan_recursive", "tofu_plan_worker_splits"):
             getattr(lib, n).restype = ctypes.c_int
         _ready = True
     return lib
@@ -86,12 +88,10 @@ def recursive(g: PlanGraph, ks: Sequence[int]):
 
 
 def worker_splits(op_var_steps: Sequence[Sequence[int]], ks: Sequence[int], op: int, worker: int) -> List[Tuple[int, int, int]]:
-    """Split list of `worker`'s shard of operator `op` under a recursive plan: step s cuts variable
-    op_var_steps[s][op] k_s ways and the worker takes the digit of its number at that step
-    (most significant digit = first step)."""
-    digits, w = [], worker
-    for k in reversed(ks):
-        digits.append(w % k)
-        w //= k
-    digits.reverse()
-    return [(op_var_steps[s][op], ks[s], digits[s]) for s in range(len(ks))]
+    """tofu_plan_worker_splits: the split list of `worker`'s shard of operator `op` under a recursive plan."""
+    from .binding import Split
+    m, n_ops = len(ks), len(op_var_steps[0]) if op_var_steps else 0
+    flat = _ints([v for step in op_var_steps for v in step])
+    out = (Split * max(1, m))()
+    _check(_lib().tofu_plan_worker_splits(flat, n_ops, _ints(ks), m, op, worker, out))
+    return [(out[s].dim, out[s].k, out[s].shard) for s in range(m)]

@@ -199,3 +199,23 @@ def test_resnet_like_chain_moves_filters_low_and_activations_high():
     # a single 8-way step may only cut one dimension per tensor: never cheaper than the recursion's grid
     one = L.basic(g, 8)
     assert one["elements"] >= res["total"]
+
+
+def test_worker_splits_match_the_oracle_for_every_worker():
+    """tofu_plan_worker_splits against oracle.regions.worker_splits: every worker of several mixed-radix
+    plans, variables taken per step and operator from a (made-up) recursive plan; and its error paths."""
+    from oracle import regions as R
+    for ks, op_var in [([2, 2, 2], [[0, 2], [0, 1], [1, 1]]), ([2, 3, 2], [[2, 0], [1, 1], [0, 2]]), ([5], [[1, 0]]), ([4, 2], [[0, 0], [2, 1]])]:
+        total = 1
+        for k in ks:
+            total *= k
+        for op in range(2):
+            for w in range(total):
+                want = R.worker_splits([step[op] for step in op_var], ks, w)
+                assert L.worker_splits(op_var, ks, op, w) == [tuple(x) for x in want]
+    with pytest.raises(tofu.TofuError):
+        L.worker_splits([[0]], [2], 0, 2)            # worker outside [0, k)
+    with pytest.raises(tofu.TofuError):
+        L.worker_splits([[0]], [2], 1, 0)            # operator outside the plan
+    with pytest.raises(tofu.TofuError):
+        L.worker_splits([[0]], [1], 0, 0)            # a one-way step
