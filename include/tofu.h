@@ -153,7 +153,10 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
  * fixed order; the data gradient also keeps its reversed filters there and the
  * conv1d its re-ordered filters.  The
  * content is scratch: nothing is carried from one call to the next, and calls
- * that run concurrently need separate workspaces. */
+ * that run concurrently need separate workspaces.  An invalid operator or plan
+ * also returns 0; that case is told apart by tofu_last_error(), which is set
+ * then and only then (a valid call that needs no workspace leaves the text of
+ * this thread empty). */
 size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits);
 
 /* Thread-local text for the last non-zero status returned on this thread. */
@@ -256,8 +259,9 @@ int tofu_shard_conv1d_accumulate(const tofu_op_desc_t* op, const tofu_split_t* s
  *           4 * h + gate, so an N shard that is a multiple of 4 holds whole units),
  *   c_prev  [batch, hidden]     cell state before the step,
  *   c_new, h_new [batch, hidden] written over the shard's box only;
- *           c_new may be the same buffer as c_prev (each element is read before
- *           it is written by the same thread), no other aliasing.
+ *           c_new may be c_prev itself (the same address and strides: each element
+ *           is read before the same thread writes it); any other overlap in memory
+ *           between an output box and an input or the other output -> INVALID_ARG.
  * All four are addressed by global coordinate through their extents, like the
  * other shard calls; the innermost stride of gates must be 1.  No workspace. */
 int tofu_shard_lstm_cell(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits,

@@ -69,12 +69,13 @@ def lib_path() -> str:
 
 
 def load():
-    """Load libtofu.so (building it first only when no built library exists)."""
+    """Load libtofu.so, building it first when no built library exists or when the sources it was
+    built from are not the present ones (their hash is kept beside the library)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from .build import build
+    from .build import build, is_current
+    if not is_current():
         build()
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -162,6 +163,9 @@ def tensor(t, lo: Optional[Sequence[int]] = None) -> Tensor:
     lo = list(lo) if lo is not None else [0] * t.dim()
     if len(lo) != t.dim() or t.dim() > TOFU_MAX_DIMS:
         raise ValueError("lo must give one coordinate per tensor dimension (at most 6)")
+    if t.numel() > 1 and all(t.stride(i) == 0 for i in range(t.dim()) if t.shape[i] > 1):
+        raise ValueError("a fully expanded (all strides zero) tensor cannot be described: all-zero strides mean dense row-major; "
+                         "materialise it first")
     d = Tensor()
     d.data = t.data_ptr()
     d.extent.ndim = t.dim()
@@ -196,8 +200,12 @@ def op_regions(op: OpDesc, splits: Sequence):
 
 
 def workspace_bytes(op: OpDesc, splits: Sequence) -> int:
+    """tofu_workspace_bytes; an invalid operator or plan (0 with an error text) raises."""
     arr, n = _splits(splits)
-    return int(load().tofu_workspace_bytes(ctypes.byref(op), arr, n))
+    need = int(load().tofu_workspace_bytes(ctypes.byref(op), arr, n))
+    if need == 0 and last_error():
+        raise TofuError(-1, last_error())
+    return need
 
 
 def region_fetch(dst: Tensor, srcs: Sequence[Tensor], stream=None) -> None:

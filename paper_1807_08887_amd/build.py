@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import subprocess
 
@@ -9,6 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 LIB = os.path.join(PKG, "libtofu.so")
+STAMP = os.path.join(PKG, "libtofu.srchash")      # hash of the sources the present library was built from
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 VALU forms are not to be generated.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-value",
@@ -17,6 +19,24 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
+
+
+def source_hash() -> str:
+    """Hash of everything the library is compiled from: csrc/*.{hip,cpp,h}, include/*.h and the flags."""
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for path in sources() + sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(INCLUDE, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True when a built library exists and was built from the present sources."""
+    try:
+        return os.path.exists(LIB) and open(STAMP).read().strip() == source_hash()
+    except OSError:
+        return False
 
 
 def build(verbose: bool = False) -> str:
@@ -33,6 +53,8 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err)
+    with open(STAMP, "w") as f:
+        f.write(source_hash() + "\n")
     return LIB
 
 

@@ -162,14 +162,7 @@ __global__ void __launch_bounds__(256) fetch_kernel(const FetchPlan t) {
 
 // Lowest and one-past-highest byte address a tensor's extent can touch.
 static void byte_span(const tofu_tensor_t* t, const int64_t* stride, const char** lo, const char** hi) {
-  int64_t min_off = 0, max_off = 0;
-  for (int d = 0; d < t->extent.ndim; ++d) {
-    int64_t e = t->extent.hi[d] - t->extent.lo[d] - 1;
-    if (e < 0) e = 0;
-    if (stride[d] >= 0) max_off += e * stride[d]; else min_off += e * stride[d];
-  }
-  *lo = static_cast<const char*>(t->data) + min_off * (int64_t)sizeof(float);
-  *hi = static_cast<const char*>(t->data) + (max_off + 1) * (int64_t)sizeof(float);
+  box_byte_span(t, stride, &t->extent, lo, hi);
 }
 
 }  // namespace tofu

@@ -252,6 +252,20 @@ const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const in
   return p;
 }
 
+void box_byte_span(const tofu_tensor_t* t, const int64_t* stride, const tofu_region_t* box, const char** lo, const char** hi) {
+  int64_t min_off = 0, max_off = 0;
+  for (int d = 0; d < box->ndim; ++d) {
+    const int64_t first = box->lo[d] - t->extent.lo[d];
+    int64_t last = box->hi[d] - 1 - t->extent.lo[d];
+    if (last < first) last = first;               // an empty range touches nothing; keep the span well formed
+    const int64_t a = first * stride[d], b = last * stride[d];
+    min_off += a < b ? a : b;
+    max_off += a < b ? b : a;
+  }
+  *lo = static_cast<const char*>(t->data) + min_off * (int64_t)sizeof(float);
+  *hi = static_cast<const char*>(t->data) + (max_off + 1) * (int64_t)sizeof(float);
+}
+
 }  // namespace tofu
 
 using namespace tofu;
@@ -343,6 +357,7 @@ int tofu_op_regions(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_
 }
 
 size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits) {
+  g_error[0] = 0;                      // a 0 with an empty error text means "no workspace needed", with a text "invalid"
   IterRanges r;
   int32_t partial = 0;
   if (apply_splits(op, splits, nsplits, &r, &partial)) return 0;

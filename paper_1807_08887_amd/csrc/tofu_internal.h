@@ -47,6 +47,10 @@ int check_tiling(const char* name, const tofu_region_t* want, const tofu_tensor_
 // Pointer to the element at global coordinate `coord` (which must lie inside the extent).
 const float* element_ptr(const tofu_tensor_t* t, const int64_t* stride, const int64_t* coord);
 
+// Lowest and one-past-highest byte address touched when the box `box` of tensor `t` (which must
+// lie inside t's extent) is read or written through the element strides `stride`.
+void box_byte_span(const tofu_tensor_t* t, const int64_t* stride, const tofu_region_t* box, const char** lo, const char** hi);
+
 // ---- launch plans (shared by tofu_workspace_bytes and the entry points) ----
 // Number of K slices the matmul kernel cuts its own reduction into for an m x n x k shard.
 int matmul_split_k(int64_t m, int64_t n, int64_t k);

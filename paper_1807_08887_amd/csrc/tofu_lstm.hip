@@ -72,8 +72,22 @@ extern "C" int tofu_shard_lstm_cell(const tofu_op_desc_t* op, const tofu_split_t
   p.c_prev = element_ptr(c_prev, ps, in_boxes[1].lo);
   p.c_new = const_cast<float*>(element_ptr(c_new, ns, out_box.lo));
   p.h_new = const_cast<float*>(element_ptr(h_new, hs, out_box.lo));
-  if (static_cast<const void*>(p.h_new) == static_cast<const void*>(p.c_new) || static_cast<const void*>(p.h_new) == static_cast<const void*>(p.c_prev))
-    return fail(TOFU_ERR_INVALID_ARG, "h_new must not share its buffer with c_new or c_prev");
+  // Aliasing, by the bytes the shard's boxes span: the outputs overlap no input and not each other, except that
+  // c_new may be c_prev itself (same address and strides: every element is read before the same lane writes it).
+  {
+    const char *g0, *g1, *p0, *p1, *n0, *n1, *h0, *h1;
+    box_byte_span(gates, gs, &in_boxes[0], &g0, &g1);
+    box_byte_span(c_prev, ps, &in_boxes[1], &p0, &p1);
+    box_byte_span(c_new, ns, &out_box, &n0, &n1);
+    box_byte_span(h_new, hs, &out_box, &h0, &h1);
+    auto overlap = [](const char* a0, const char* a1, const char* b0, const char* b1) { return a0 < b1 && b0 < a1; };
+    if (overlap(h0, h1, n0, n1) || overlap(h0, h1, p0, p1) || overlap(h0, h1, g0, g1))
+      return fail(TOFU_ERR_INVALID_ARG, "h_new must not overlap c_new, c_prev or gates in memory");
+    if (overlap(n0, n1, g0, g1)) return fail(TOFU_ERR_INVALID_ARG, "c_new must not overlap gates in memory");
+    const bool in_place = static_cast<const void*>(p.c_new) == static_cast<const void*>(p.c_prev) && ns[0] == ps[0] && ns[1] == ps[1];
+    if (overlap(n0, n1, p0, p1) && !in_place)
+      return fail(TOFU_ERR_INVALID_ARG, "c_new overlaps c_prev without being the same view (same address and strides)");
+  }
   p.g_rs = gs[0]; p.g_hs = gs[1];
   p.cp_rs = ps[0]; p.cp_hs = ps[1]; p.cn_rs = ns[0]; p.cn_hs = ns[1]; p.hn_rs = hs[0]; p.hn_hs = hs[1];
   p.rows = (int)rows; p.cols = (int)cols;

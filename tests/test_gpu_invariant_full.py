@@ -117,13 +117,20 @@ def test_wresnet_conv_all_shards_cout_and_cout_x_h():
     _close(y2.cpu().numpy()[idx], val, absum, "conv, 16 <C_out, H> shards concatenated")
 
 
+@pytest.mark.timeout(600)
 def test_wresnet_wgrad_all_batch_shards_summed():
     cfg = synth.CONFIGS["wresnet_conv_wgrad"]
     C, H, W, k, seed = cfg["c_in"], cfg["H"], cfg["W"], cfg["k"], cfg["seed"]
-    NB = 32                                                   # 4 images per shard
+    NB = cfg["batch"]                                         # the full batch of 128: 16 images per shard
     op = tofu.wgrad_desc(NB, C, C, H, W)
-    x = synth.draw(cfg["x"], seed, 30, (NB, C, H, W))
-    dy = synth.draw(cfg["dy"], seed, 31, (NB, C, H, W))
+    # every shard's images are drawn as tensors of their own (ids 40 + s, 60 + s), eight at a time on host threads
+    from concurrent.futures import ThreadPoolExecutor
+    per = NB // k
+    with ThreadPoolExecutor(8) as pool:
+        xs = list(pool.map(lambda s: synth.draw(cfg["x"], seed, 40 + s, (per, C, H, W)), range(k)))
+        dys = list(pool.map(lambda s: synth.draw(cfg["dy"], seed, 60 + s, (per, C, H, W)), range(k)))
+    x, dy = np.concatenate(xs), np.concatenate(dys)
+    del xs, dys
     dx, ddy = torch.from_numpy(x).to(DEV), torch.from_numpy(dy).to(DEV)
     parts = []
     for s in range(k):

@@ -1,6 +1,12 @@
 """GPU parity at the full workload sizes, in the launch configuration bench.py times: every
 leg of tofu_workloads.build() is run once and checked against the oracle on seeded samples
-of output coordinates (plus the corners of the output box); the copy is checked in full."""
+of output coordinates; the copy is checked in full.  The samples of a contraction are
+  * seeded uniform points and the corners of the output box,
+  * points on every face of the output box, and
+  * one point in every 32 x 32 block of the kernel's matrix view of the output ([m] x [n];
+    [c_out] x [positions in n-major order over the box]; [c_out] x [c_in] per filter tap), the
+    size of one matrix-core accumulator block: whatever tiles a launch cuts that matrix into,
+    every accumulator block of every tile is hit, for the weight gradient at every tap."""
 import itertools
 
 import numpy as np
@@ -19,6 +25,35 @@ TOL = 1e-5
 def _points(seed, n, shape):
     corners = list(itertools.product(*[(0, e - 1) for e in shape]))
     return np.concatenate([np.array(corners, dtype=np.int64), synth.coords(seed, 0, n, shape)])
+
+
+def _faces(seed, per_face, shape):
+    """Seeded points on each of the 2 * ndim faces of a box of `shape`."""
+    out = []
+    for d, e in enumerate(shape):
+        for side, v in enumerate((0, e - 1)):
+            p = synth.coords(seed, 10 + 2 * d + side, per_face, shape)
+            p[:, d] = v
+            out.append(p)
+    return np.concatenate(out)
+
+
+def _strata(seed, rows, cols, block=32):
+    """One seeded (row, col) inside every block x block cell of a rows x cols matrix (ragged last cells included)."""
+    br, bc = (rows + block - 1) // block, (cols + block - 1) // block
+    off = synth.coords(seed, 30, br * bc, (block, block))
+    r = np.minimum(np.repeat(np.arange(br), bc) * block + off[:, 0], rows - 1)
+    c = np.minimum(np.tile(np.arange(bc), br) * block + off[:, 1], cols - 1)
+    return r, c
+
+
+def _conv_points(seed, n, shape):
+    """Sample coordinates of a [batch, channels, h, w] output: uniform + corners + faces + one per 32 x 32 block of
+    the [channels] x [positions] matrix, positions numbered batch-major over the box."""
+    nb, ch, bh, bw = shape
+    r, c = _strata(seed, ch, nb * bh * bw)
+    strat = np.stack([c // (bh * bw), r, (c // bw) % bh, c % bw], axis=1).astype(np.int64)
+    return np.concatenate([_points(seed, n, shape), _faces(seed, 48, shape), strat])
 
 
 def _close(got, val, absum, what):
@@ -58,7 +93,8 @@ def test_full_size_legs(group):
         if h["kind"] == "matmul":
             box = h["box"]
             (m0, m1), (n0, n1) = box
-            pts = _points(71, 4096, (m1 - m0, n1 - n0))
+            r, c = _strata(71, m1 - m0, n1 - n0)
+            pts = np.concatenate([_points(71, 4096, (m1 - m0, n1 - n0)), _faces(71, 64, (m1 - m0, n1 - n0)), np.stack([r, c], axis=1).astype(np.int64)])
             k0, k1 = h["krange"]
             if "b_col0" in h:     # B holds the shard's columns only
                 val, absum = oracle.matmul_pts(h["A"], h["B"], pts)
@@ -68,7 +104,7 @@ def test_full_size_legs(group):
             _close(got, val, absum, leg.name)
         elif h["kind"] == "conv2d":
             y = leg.out.cpu().numpy()
-            pts = _points(72, 4096, y.shape)
+            pts = _conv_points(72, 4096, y.shape)
             h0 = h["box"][2][0]
             opts = pts.copy()
             opts[:, 2] += h0      # output row in global coordinates; channels stay local to the shard's filters
@@ -90,12 +126,16 @@ def test_full_size_legs(group):
             _close(h["h_out"].cpu().numpy().ravel(), hn.ravel(), np.ones(hn.size), leg.name + " h")
         elif h["kind"] == "dgrad":
             dxp = leg.out.cpu().numpy()
-            pts = _points(74, 4096, dxp.shape)
+            pts = _conv_points(74, 4096, dxp.shape)
             val, absum = oracle.dgrad_pts(h["dy"], h["w"], h["H"], h["W"], pts, stride=1, pad=1)   # the shard's output channels only
             _close(dxp[tuple(pts.T)], val, absum, leg.name)
         elif h["kind"] == "wgrad":
             dw = leg.out.cpu().numpy()
-            pts = _points(73, 2048, dw.shape)
+            # one point per (32 output channels, 32 input channels, tap) block, plus faces, corners and uniform points
+            co_n, ci_n = dw.shape[0], dw.shape[1]
+            r, c = _strata(73, co_n, ci_n)
+            strat = np.concatenate([np.stack([r, c, np.full_like(r, t // 3), np.full_like(r, t % 3)], axis=1) for t in range(9)]).astype(np.int64)
+            pts = np.concatenate([_points(73, 2048, dw.shape), _faces(73, 48, dw.shape), strat])
             val, absum = oracle.wgrad_pts(h["x"], h["dy"], 3, 3, pts, stride=1, pad=1)   # the shard's images only
             _close(dw[tuple(pts.T)], val, absum, leg.name)
         elif h["kind"] == "fetch":

@@ -229,6 +229,19 @@ def test_lstm_cell_error_paths_are_checked_on_the_host():
     with pytest.raises(tofu.TofuError) as e:
         tofu.shard_lstm_cell(tofu.matmul_desc(4, 8, 2), [], g, c, cn, hn, stream=0)
     assert e.value.status == -1
+    # aliasing is judged by the bytes the boxes span, not by base pointers: partial overlaps are refused
+    for bad in [(g, c, cn, _t([(0, 4), (0, 8)], FAKE + (2 << 20) + 16)),        # h_new starts inside c_new
+                (g, c, cn, _t([(0, 4), (0, 8)], FAKE + (1 << 20) + 64)),        # h_new starts inside c_prev
+                (g, c, cn, _t([(0, 4), (0, 8)], FAKE + 256)),                   # h_new inside gates
+                (g, c, _t([(0, 4), (0, 8)], FAKE + 128), hn),                   # c_new inside gates
+                (g, c, _t([(0, 4), (0, 8)], FAKE + (1 << 20) + 4), hn),         # c_new shifted by one element against c_prev
+                (g, c, _t([(0, 4), (0, 8)], FAKE + (1 << 20), stride=[16, 1]), hn)]:   # same address as c_prev, other strides
+        with pytest.raises(tofu.TofuError) as e:
+            tofu.shard_lstm_cell(op, [], *bad, stream=0)
+        assert e.value.status == -1 and "overlap" in str(e.value)
+    # an invalid plan makes workspace_bytes raise instead of returning a 0 that looks like "none needed"
+    with pytest.raises(tofu.TofuError):
+        tofu.workspace_bytes(op, [(tofu.LSTM_DIM_H, 16, 1)])
     assert tofu.workspace_bytes(op, [(tofu.LSTM_DIM_H, 2, 1)]) == 0
     r = tofu.op_regions(op, [(tofu.LSTM_DIM_H, 2, 1)])
     assert r["in_boxes"] == [[(0, 4), (4, 8), (0, 4)], [(0, 4), (4, 8)]] and not r["is_partial"]
