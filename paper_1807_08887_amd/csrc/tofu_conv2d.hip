@@ -449,10 +449,10 @@ struct ConvPlan {
   int64_t E;          // staged floats per channel
   int64_t tiles, whole, rest;
   int groups, max_segments;
-  int BN, CK;
+  int BM, BN, CK;
 };
 
-static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false, int KH = 3, int KW = 3) {
+static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false, int KH = 3, int KW = 3, int BM = 64) {
   ConvPlan pl;
   memset(&pl, 0, sizeof(pl));
   const int64_t E256 = max_staged(P, BH, BW, 256, KH, KW), E128 = max_staged(P, BH, BW, 128, KH, KW);
@@ -472,7 +472,8 @@ static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t
   else if (8 * E128 <= 10 * 256) { pl.variant = 1; pl.E = E128; pl.BN = 128; pl.CK = 8; }
   else if (4 * E128 <= 10 * 256) { pl.variant = 2; pl.E = E128; pl.BN = 128; pl.CK = 4; }
   else { pl.variant = -1; pl.E = E128; return pl; }
-  pl.tiles = ((CO + 63) / 64) * ((P + pl.BN - 1) / pl.BN);
+  pl.BM = BM;
+  pl.tiles = ((CO + BM - 1) / BM) * ((P + pl.BN - 1) / pl.BN);
   const int64_t steps = (CI + pl.CK - 1) / pl.CK;
   pl.rest = pl.tiles % kConvSlots;
   // a last wave that is nearly full, or a reduction too short to cut, is launched as whole tiles
@@ -489,13 +490,32 @@ static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t
 
 static size_t plan_bytes(const ConvPlan& pl) {
   if (pl.variant < 0 || pl.rest == 0) return 0;
-  return (size_t)pl.groups * pl.max_segments * 64 * pl.BN * sizeof(float);
+  return (size_t)pl.groups * pl.max_segments * pl.BM * pl.BN * sizeof(float);
 }
 
-// enough for either entry point (one input buffer, or the region read from several blocks)
+// A shard's output channels are computed in tile rows of 64.  When the last row would hold at most 32
+// channels it is computed by a launch of its own with 32-row tiles (one MFMA block per wavefront instead of
+// two), so that a shard of 160 channels costs 160 rows of work and not 192.  -> channels of the 64-row part
+// (a multiple of 64, possibly 0); the rest, if any, is the 32-row part.
+static int64_t conv_main_channels(int64_t CO) {
+  const int64_t tail = CO % 64;
+  return (tail == 0 || tail > 32) ? CO : CO - tail;
+}
+
+// enough for either entry point (one input buffer, or the region read from several blocks) and for both channel parts,
+// which run one after the other on the stream and use the slots in turn
 size_t conv_workspace_bytes(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, int KH, int KW) {
-  const size_t a = plan_bytes(conv_plan(P, BH, BW, CO, CI, false, KH, KW)), b = plan_bytes(conv_plan(P, BH, BW, CO, CI, true, KH, KW));
-  return a > b ? a : b;
+  const int64_t co_main = conv_main_channels(CO);
+  size_t need = 0;
+  for (int part = 0; part < 2; ++part) {
+    const int64_t co = part == 0 ? co_main : CO - co_main;
+    if (co == 0) continue;
+    for (int multi = 0; multi < 2; ++multi) {
+      const size_t n = plan_bytes(conv_plan(P, BH, BW, co, CI, multi != 0, KH, KW, part == 0 ? 64 : 32));
+      if (n > need) need = n;
+    }
+  }
+  return need;
 }
 
 template <int BM, int BN, int CK, int WM, int WN, int XJ, int KH = 3, int KW = 3>
@@ -582,22 +602,48 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   p.LDW = (int)BW + q.KW - 1;
   p.w_fast = q.ws[3] == 1 && (q.KH == 1 || q.ws[2] == q.KW) && q.ws[1] == q.KH * q.KW && q.ws[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(p.w) & 15) == 0;
 
-  const ConvPlan pl = conv_plan(P, BH, BW, CO, CI, q.srcs != nullptr, q.KH, q.KW);
   if (q.srcs && (q.KH != 3 || q.KW != 3)) return fail(TOFU_ERR_UNSUPPORTED, "conv2d: only 3 x 3 filters read their region from several blocks");
-  if (pl.variant < 0)
-    return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)pl.E);
-  const size_t need = plan_bytes(pl);
-  if (need > 0) {
-    if (!q.workspace || q.workspace_bytes < need)
-      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d shard needs %zu workspace bytes, got %zu", need, q.workspace ? q.workspace_bytes : (size_t)0);
-    if (reinterpret_cast<uintptr_t>(q.workspace) & 15) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
-  }
+  if (q.workspace && (reinterpret_cast<uintptr_t>(q.workspace) & 15)) return fail(TOFU_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
   p.slots = static_cast<float*>(q.workspace);
-  if (pl.variant == 10) return launch_conv<64, 256, 12, 1, 4, 13, 1, 3>(p, q.srcs, pl, stream);
-  if (pl.variant == 11) return launch_conv<64, 128, 12, 1, 4, 13, 1, 3>(p, q.srcs, pl, stream);
-  if (pl.variant == 0) return launch_conv<64, 256, 4, 1, 4, 8>(p, q.srcs, pl, stream);
-  if (pl.variant == 1) return launch_conv<64, 128, 8, 1, 4, 10>(p, q.srcs, pl, stream);
-  return launch_conv<64, 128, 4, 1, 4, 10>(p, q.srcs, pl, stream);
+  // the 64-row part of the output channels, then the 32-row part (see conv_main_channels)
+  const int64_t co_main = conv_main_channels(CO);
+  ConvPlan plans[2];
+  for (int part = 0; part < 2; ++part) {
+    const int64_t co = part == 0 ? co_main : CO - co_main;
+    if (co == 0) continue;
+    plans[part] = conv_plan(P, BH, BW, co, CI, q.srcs != nullptr, q.KH, q.KW, part == 0 ? 64 : 32);
+    if (plans[part].variant < 0)
+      return fail(TOFU_ERR_UNSUPPORTED, "conv2d: output box is too wide for the staging buffers (%lld staged floats per channel)", (long long)plans[part].E);
+    const size_t need = plan_bytes(plans[part]);
+    if (need > 0 && (!q.workspace || q.workspace_bytes < need))
+      return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d shard needs %zu workspace bytes, got %zu", need, q.workspace ? q.workspace_bytes : (size_t)0);
+  }
+  for (int part = 0; part < 2; ++part) {
+    const int64_t co0 = part == 0 ? 0 : co_main, co = part == 0 ? co_main : CO - co_main;
+    if (co == 0) continue;
+    ConvArgs pp = p;
+    pp.w = p.w + co0 * q.ws[0];
+    pp.y = p.y + co0 * q.ys[1];
+    pp.CO = (int)co;
+    pp.w_bytes = (uint32_t)(4 * (w_span - (CO - co) * q.ws[0]));
+    const ConvPlan& pl = plans[part];
+    int rc;
+    if (part == 0) {
+      rc = pl.variant == 10  ? launch_conv<64, 256, 12, 1, 4, 13, 1, 3>(pp, q.srcs, pl, stream)
+           : pl.variant == 11 ? launch_conv<64, 128, 12, 1, 4, 13, 1, 3>(pp, q.srcs, pl, stream)
+           : pl.variant == 0  ? launch_conv<64, 256, 4, 1, 4, 8>(pp, q.srcs, pl, stream)
+           : pl.variant == 1  ? launch_conv<64, 128, 8, 1, 4, 10>(pp, q.srcs, pl, stream)
+                              : launch_conv<64, 128, 4, 1, 4, 10>(pp, q.srcs, pl, stream);
+    } else {
+      rc = pl.variant == 10  ? launch_conv<32, 256, 12, 1, 4, 13, 1, 3>(pp, q.srcs, pl, stream)
+           : pl.variant == 11 ? launch_conv<32, 128, 12, 1, 4, 13, 1, 3>(pp, q.srcs, pl, stream)
+           : pl.variant == 0  ? launch_conv<32, 256, 4, 1, 4, 8>(pp, q.srcs, pl, stream)
+           : pl.variant == 1  ? launch_conv<32, 128, 8, 1, 4, 10>(pp, q.srcs, pl, stream)
+                              : launch_conv<32, 128, 4, 1, 4, 10>(pp, q.srcs, pl, stream);
+    }
+    if (rc) return rc;
+  }
+  return TOFU_OK;
 }
 
 // Shared by the two forward entry points: `x` is the single buffer that holds the input region,

@@ -58,7 +58,7 @@ def check_box(out, reg, val, absum, what):
     close(got[sl], val, absum, what)
 
 
-CH = [1, 3, 31, 32, 33, 63, 64, 65, 96, 127, 129]
+CH = [1, 3, 31, 32, 33, 63, 64, 65, 80, 96, 127, 129, 160]
 SP = [1, 2, 3, 4, 7, 13, 14, 15, 16, 27, 28, 31, 32, 33]
 
 
@@ -114,6 +114,34 @@ def test_random_conv_family(seed):
             tofu.shard_conv2d_dgrad(op, lsp, tofu.tensor(ddy), tofu.tensor(dw_), tofu.tensor(gx), ws(op, lsp))
             val, absum = oracle.dgrad_box(dy, w, H, W, pad=pad, box=reg["out_box"], corange=reg["ranges"]["CO"])
             check_box(gx, reg, val, absum, tag + " dgrad " + str(sp))
+
+
+@pytest.mark.parametrize("c_out,batch,hw", [(160, 40, 14), (80, 24, 14), (96, 3, 28), (32, 40, 14), (200, 9, 7)])
+def test_conv_output_channels_with_a_short_last_tile_row(c_out, batch, hw):
+    """Output channels that end in a tile row of at most 32 (160 = 2 x 64 + 32, 80 = 64 + 16, ...) take the
+    32-row kernel for that row -- as whole tiles and, with many positions, as balanced segments; forward on
+    the whole box and under a C_out split, and the data gradient (whose tile rows are the input channels)."""
+    c_in = 24
+    x = synth.normal(700 + c_out, 0, (batch, c_in, hw, hw), 1.0)
+    w = synth.normal(700 + c_out, 1, (c_out, c_in, 3, 3), 0.3)
+    dx_, dw_ = dev(x), dev(w)
+    op = tofu.conv2d_desc(batch, c_in, c_out, hw, hw)
+    opd = dict(kind="conv2d", batch=batch, c_in=c_in, c_out=c_out, H=hw, W=hw, KH=3, KW=3, stride=1, pad=1)
+    for sp, lsp in [([], []), ([("CO", 2, 1)], [(tofu.CONV_DIM_CO, 2, 1)])]:
+        reg = R.op_regions(opd, sp)
+        y = torch.full((batch, c_out, hw, hw), float("nan"), dtype=torch.float32, device=DEV)
+        tofu.shard_conv2d(op, lsp, tofu.tensor(dx_), tofu.tensor(dw_), tofu.tensor(y), ws(op, lsp))
+        val, absum = oracle.conv2d_box(x, w, pad=1, box=reg["out_box"])
+        check_box(y, reg, val, absum, f"conv2d co{c_out} {sp}")
+    # data gradient of a convolution with c_out INPUT channels: dx has c_out channels, the kernel's tile rows
+    dy = synth.normal(700 + c_out, 2, (batch, c_in, hw, hw), 1.0)
+    wd = synth.normal(700 + c_out, 3, (c_in, c_out, 3, 3), 0.3)
+    opg = tofu.dgrad_desc(batch, c_out, c_in, hw, hw)
+    gx = torch.full((batch, c_out, hw, hw), float("nan"), dtype=torch.float32, device=DEV)
+    d_dy, d_wd = dev(dy), dev(wd)          # kept alive: a descriptor holds only the address
+    tofu.shard_conv2d_dgrad(opg, [], tofu.tensor(d_dy), tofu.tensor(d_wd), tofu.tensor(gx), ws(opg, []))
+    val, absum = oracle.dgrad_box(dy, wd, hw, hw, pad=1)
+    close(gx.cpu().numpy(), val, absum, f"dgrad ci{c_out}")
 
 
 @pytest.mark.parametrize("seed", range(8))
