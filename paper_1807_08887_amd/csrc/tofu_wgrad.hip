@@ -13,9 +13,11 @@
 //     touch, x[n, ci tile, h-pad .. h+R-1-pad+2, :], are staged with their zero border, so the
 //     nine taps are nine shifted reads of the same staged rows.  One MFMA contracts two
 //     adjacent output columns (lanes 0-31: w, lanes 32-63: w+1).
-//   * Load balance: the work is T tiles x NB images ("units", tile-major).  400 tiles cannot fill
+//   * Load balance: the work is T tiles x (NB images x their K steps' row groups) ("units", tile-major:
+//     one unit is one output row, or the group of rows one step takes).  400 tiles cannot fill
 //     512 workgroup slots evenly, so workgroup g takes the units [g*N/G, (g+1)*N/G) -- the same
-//     even split as a shard range.  A run of units inside one tile is a segment; every segment
+//     even split as a shard range; with rows as units every workgroup gets the same number of steps
+//     to within one (with whole images as units some had 13 images where others had 12).  A run of units inside one tile is a segment; every segment
 //     goes tap-major to a workspace slot and a second kernel sums each tile's segments in
 //     workgroup order (fixed, no atomics) and restores the [co][ci][kh][kw] layout.  Each
 //     workgroup writes at most a few slots, so the workspace is about 2.5x the output instead
@@ -93,8 +95,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int per_xcd = (p.groups + 7) / 8;
   const int g = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (g >= p.groups) return;
-  const int64_t n_units = (int64_t)p.tiles_m * p.tiles_n * p.NB;
-  const int u_begin = (int)(g * n_units / p.groups), u_end = (int)((g + 1) * n_units / p.groups);
+  const int HG = (p.HO + R - 1) / R;             // row groups (= units) per image: groups of R output rows
+  const int UPT = p.NB * HG;                     // units per tile
+  const int64_t n_units = (int64_t)p.tiles_m * p.tiles_n * UPT;
+  const int64_t u_begin = g * n_units / p.groups, u_end = (g + 1) * n_units / p.groups;
   const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
   const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
   // the x buffer starts plh rows and plw columns before the box, so that staged element (r, c) of a
@@ -109,16 +113,16 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   // low image numbers and its first the high ones; walking them in this order makes every
   // workgroup sweep the images upwards, and the workgroups of a moment share image planes in L2.
   if (u_begin >= u_end) return;
-  const int first_tile = u_begin / p.NB, last_tile = (u_end - 1) / p.NB;
+  const int first_tile = (int)(u_begin / UPT), last_tile = (int)((u_end - 1) / UPT);
   for (int segment = last_tile - first_tile; segment >= 0; --segment) {
-  // ---- one segment: images [n_begin, n_end) of one tile ----
+  // ---- one segment: row groups [r_begin, r_end) of one tile, numbered image-major (image n, group h -> n * HG + h) ----
   const int tile = first_tile + segment;
-  const int n_begin = max(u_begin, tile * p.NB) - tile * p.NB;
-  const int n_end = min(u_end, (tile + 1) * p.NB) - tile * p.NB;
+  const int64_t t0 = (int64_t)tile * UPT;
+  const int r_begin = (int)(max(u_begin, t0) - t0);
+  const int r_end = (int)(min(u_end, t0 + UPT) - t0);
   const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
   const int m0 = tile_m * BM, c0 = tile_n * BCI;
-  const int HG = (p.HO + R - 1) / R;             // steps per image: groups of R output rows
-  const int steps = (n_end - n_begin) * HG * p.chunks;
+  const int steps = (r_end - r_begin) * p.chunks;
 
   // ---- fast-path staging maps ----
   // dy: thread -> (row = tid/8 + 32*j, columns 4*(tid%8) .. +3); x: thread -> (channel tid/TPC, elements tid%TPC + TPC*j)
@@ -172,8 +176,9 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     rx[j] = buf_load(x_rsrc, ok ? x_voff[j] : kNoOffset, x_soff);
   };
   auto load_global = [&](int step) {
-    const int row_id = step / p.chunks, chunk = step - row_id * p.chunks;
-    const int n = n_begin + row_id / HG, oh = (row_id - (row_id / HG) * HG) * R;   // first output row of the step
+    const int sr = step / p.chunks, chunk = step - sr * p.chunks;
+    const int row_id = r_begin + sr;
+    const int n = row_id / HG, oh = (row_id - n * HG) * R;   // image and first output row of the step
     if (FAST) {
       const int cw0 = chunk * p.CW;
       const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2] + cw0);
@@ -248,8 +253,9 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
     for (int t = 0; t < steps; ++t) {
       const int buf = t & 1;
       const int nxt = min(t + 2, steps - 1);
-      const int row_id = nxt / p.chunks, cw0 = (nxt - row_id * p.chunks) * p.CW;
-      const int n = n_begin + row_id / HG, oh = (row_id - (row_id / HG) * HG) * R;
+      const int sr = nxt / p.chunks, cw0 = (nxt - sr * p.chunks) * p.CW;
+      const int row_id = r_begin + sr;
+      const int n = row_id / HG, oh = (row_id - n * HG) * R;
       const uint32_t d_soff = 4u * (uint32_t)((int64_t)n * p.ds[0] + (int64_t)oh * p.ds[2] + cw0);
       const uint32_t x_soff = 4u * (uint32_t)((int64_t)n * p.xs[0] + (int64_t)oh * p.xs[2] + (int64_t)cw0 * p.xs[3]);
       const float* dsm = &Ds[buf][half][wave * 32 + l32];
@@ -363,24 +369,24 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 // dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine reads per slot are coalesced
 // across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
 __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
-                                                                 const float* __restrict__ slots, int groups, int max_segments, int NB,
+                                                                 const float* __restrict__ slots, int groups, int max_segments, int UPT,
                                                                  int tiles_m, int tiles_n, int CO, int CI, int accumulate) {
   constexpr int BM = 128, BCI = 32;
-  const int64_t n_units = (int64_t)tiles_m * tiles_n * NB;
+  const int64_t n_units = (int64_t)tiles_m * tiles_n * UPT;   // UPT: units (row groups of all images) per tile
   const int64_t items = (int64_t)tiles_m * tiles_n * BM * BCI;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
     const int tile = (int)(i / (BM * BCI)), local = (int)(i % (BM * BCI)), co_l = local / BCI, ci_l = local % BCI;
     const int tile_n = tile / tiles_m, tile_m = tile % tiles_m;
     const int co = tile_m * BM + co_l, ci = tile_n * BCI + ci_l;
     // workgroups whose unit ranges meet this tile: g(u) = floor(((u + 1) * G - 1) / N)
-    const int64_t u0 = (int64_t)tile * NB, u1 = u0 + NB - 1;
+    const int64_t u0 = (int64_t)tile * UPT, u1 = u0 + UPT - 1;
     const int g_first = (int)(((u0 + 1) * groups - 1) / n_units), g_last = (int)(((u1 + 1) * groups - 1) / n_units);
     if (co >= CO || ci >= CI) continue;
     float acc[9];
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) acc[tap] = 0.f;
     for (int g = g_first; g <= g_last; ++g) {
-      const int first_tile = (int)((g * n_units / groups) / NB);   // tile of the workgroup's first unit = its segment 0
+      const int first_tile = (int)((g * n_units / groups) / UPT);   // tile of the workgroup's first unit = its segment 0
       const float* sl = slots + ((int64_t)g * max_segments + (tile - first_tile)) * kSlotFloats + co_l * BCI + ci_l;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
@@ -407,9 +413,10 @@ void wgrad_plan(int64_t co, int64_t ci, int64_t nb, int* groups, int* max_segmen
     return;
   }
   const int64_t g = units < kWgradSlots ? units : kWgradSlots;
-  const int64_t per = (units + g - 1) / g;                 // most units per workgroup
   *groups = (int)g;
-  *max_segments = (int)((per + nb - 2) / nb + 1);
+  // A workgroup's run of units is at most ceil(units / g) long, so it meets at most ceil(tiles / g) + 1 tiles --
+  // whatever the unit (images here; the kernels cut finer, into the row groups of their steps).
+  *max_segments = (int)((tiles + g - 1) / g + 1);
 }
 
 size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb) {
@@ -515,6 +522,7 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, false, 16>
                                  : wgrad_kernel<gBM, gBCI, true, false>;
   }
+  const int64_t rows_per_step = !fast ? 1 : (fast_2x14 || fast_2x16) ? 2 : fast_4x7 ? 4 : 1;   // the R of the kernel picked above
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);
   hipError_t e = hipGetLastError();
@@ -523,7 +531,8 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
     const int64_t items = (int64_t)p.tiles_m * p.tiles_n * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
     hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
-                       static_cast<const float*>(workspace), groups, max_segments, (int)NB, p.tiles_m, p.tiles_n, (int)CO, (int)CI, accumulate ? 1 : 0);
+                       static_cast<const float*>(workspace), groups, max_segments, (int)(NB * ((HO + rows_per_step - 1) / rows_per_step)), p.tiles_m, p.tiles_n,
+                       (int)CO, (int)CI, accumulate ? 1 : 0);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient segment sum launch failed: %s", hipGetErrorString(e));
   }
