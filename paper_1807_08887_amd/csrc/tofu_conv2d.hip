@@ -29,6 +29,7 @@
 
 #include <type_traits>
 
+#include "tofu_balance.h"
 #include "tofu_internal.h"
 #include "tofu_mfma.h"
 
@@ -51,11 +52,11 @@ struct ConvArgs {
   int PL;           // floats per staged channel plane
   int E;            // upper bound over all tiles of the staged floats per channel (<= PL)
   int w_fast;       // 1: weights dense over (ci,kh,kw) and 16-byte aligned -> vector loads
-  // Balanced launches: the tiles [tile0, tile0 + n_tiles) times their channel steps are cut into
-  // units and dealt evenly to `groups` workgroups; every run of units inside one tile (a segment)
-  // leaves its accumulators in slot (workgroup * max_segments + segment) of `slots`.
-  // Whole-tile launches cover the same tile range with one workgroup per tile.
-  int tile0, n_tiles, groups, max_segments;
+  // Balanced launches: the channel steps of the tiles [tile0, tile0 + n_tiles) are dealt to bal.groups
+  // workgroups as tofu_balance.h describes; every piece of a tile leaves its accumulators in a slot of
+  // `slots`.  Whole-tile launches cover the same tile range with one workgroup per tile.
+  int tile0, n_tiles;
+  Balance bal;
   float* slots;
 };
 
@@ -73,6 +74,21 @@ struct ConvSources {
 };
 // Lanes with nothing to read (zero border, idle staging slots) load from here in the multi-block kernels.
 __device__ float kZeroWords[64];
+
+// Tile number -> (position tile, channel tile row).  Tiles are numbered in panels of kPanelRows channel
+// tile rows; inside a panel the channel row runs fastest.  The 64 workgroups that run side by side on one
+// XCD are consecutive tiles, i.e. a block of 8 position tiles x 8 channel rows (or all rows, when the shard has
+// fewer): per step they share 8 input tiles and 8 filter rows through that XCD's L2, close to the least a
+// block of 64 can read.  (Channel row fastest over ALL rows made 64 tiles = 1.6 position tiles x 40 rows
+// for a shard of 2560 output channels, which re-read the filters once per 1.6 position tiles.)
+constexpr int kPanelRows = 8;
+__device__ __forceinline__ void decode_tile(int tile, int tiles_m, int tiles_n, int& tile_n, int& tile_m) {
+  const int panel_tiles = kPanelRows * tiles_n;
+  const int panel = tile / panel_tiles, rem = tile - panel * panel_tiles;
+  const int rows = min(kPanelRows, tiles_m - panel * kPanelRows);
+  tile_n = rem / rows;
+  tile_m = panel * kPanelRows + (rem - tile_n * rows);
+}
 
 template <int BM, int BN, int CK, int WM, int WN, int XJ, int KH = 3, int KW = 3>
 struct ConvCfg {
@@ -103,22 +119,18 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 
   // Compute units are handed workgroups round-robin over the 8 XCDs; renumber so that
   // consecutive logical workgroups (which share staged input rows) land on the same XCD's L2.
-  const int total = BALANCED ? p.groups : p.n_tiles;
+  const int total = BALANCED ? p.bal.groups : p.n_tiles;
   const int per_xcd = (total + 7) / 8;
   const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (lid >= total) return;                   // grid is padded to a multiple of 8
   const int steps_all = (p.CI + CK - 1) / CK;
-  // balanced: this workgroup's run of units [u, u_end) of (tile, channel step) pairs
-  const int64_t n_units = (int64_t)p.n_tiles * steps_all;
-  const int64_t u_begin = BALANCED ? lid * n_units / p.groups : 0;
-  const int64_t u_end = BALANCED ? (lid + 1) * n_units / p.groups : 0;
-  if (BALANCED && u_begin >= u_end) return;
-  // Segments are numbered in unit order but processed last to first: a workgroup's run of units
-  // is at most a little longer than one tile's reduction, so its last segment covers the low
-  // channel steps and its first the high ones; in this order every workgroup sweeps the channels
-  // upwards and the workgroups of a moment read the same channels of the input (shared through L2).
-  const int first_rel = BALANCED ? (int)(u_begin / steps_all) : 0, last_rel = BALANCED ? (int)((u_end - 1) / steps_all) : 0;
-  int segment = last_rel - first_rel;
+  // balanced: this workgroup's segments (pieces of tiles)
+  BalanceWalk walk;
+  if (BALANCED) {
+    walk = balance_walk(p.bal, steps_all, lid);
+    if (walk.count == 0) return;
+  }
+  int seg_i = 0;
   do {
   // The per-lane staging lists below are rebuilt for every segment.  The thread index is made
   // opaque once per segment so that the parts of them that do not depend on the tile are not
@@ -128,19 +140,13 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int wm = wave / WN, wn = wave % WN;
-  int tile, s_begin, s_end;
+  int tile = p.tile0 + lid, s_begin = 0, s_end = steps_all, slot = 0;
   if (BALANCED) {
-    const int t_rel = first_rel + segment;
-    const int64_t t0 = (int64_t)t_rel * steps_all;
-    tile = p.tile0 + t_rel;
-    s_begin = (int)(max(u_begin, t0) - t0);
-    s_end = (int)(min(u_end, t0 + steps_all) - t0);
-  } else {
-    tile = p.tile0 + lid;
-    s_begin = 0;
-    s_end = steps_all;
+    const BalanceSegment seg = balance_segment(walk, seg_i);
+    tile = p.tile0 + seg.tile; s_begin = seg.begin; s_end = seg.end; slot = seg.slot;
   }
-  const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
+  int tile_n, tile_m;
+  decode_tile(tile, p.tiles_m, p.tiles_n, tile_n, tile_m);
   const int m0 = tile_m * BM;
   const int p_begin = tile_n * BN;
   const int p_end = min(p.P, p_begin + BN);
@@ -342,7 +348,7 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 
   if constexpr (BALANCED) {
     // slot [(i, j, v)][thread]: every store instruction of the workgroup writes NT consecutive floats
-    float* o = p.slots + ((int64_t)lid * p.max_segments + segment) * (BM * BN) + tid;
+    float* o = p.slots + (int64_t)slot * (BM * BN) + tid;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -350,7 +356,6 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[((i * FN + j) * 16 + v) * NT] = acc[i][j][v];
     __syncthreads();   // the next segment's prologue overwrites LDS buffer 0
-    --segment;
   } else {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -367,11 +372,12 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
         }
       }
   }
-  } while (BALANCED && segment >= 0);
+  ++seg_i;
+  } while (BALANCED && seg_i < walk.count);
 }
 
-// Sums the slots of every balanced tile in workgroup order and writes the output box (or adds
-// the sum to it).  One
+// Sums the slots of every balanced tile in the order of its channel steps and writes the output
+// box (or adds the sum to it).  One
 // workgroup per (tile, 32x32 accumulator block): thread and accumulator index map to (channel,
 // position) exactly as in the convolution kernel, so reads are NT consecutive floats and writes
 // follow the output rows.
@@ -381,25 +387,22 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_segment_sum_kernel(const 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
   const int wm = wave / WN, wn = wave % WN;
   const int t_rel = blockIdx.x, blk = blockIdx.y, i = blk / FN, j = blk % FN;
-  const int tile = p.tile0 + t_rel, tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
-  const int64_t n_units = (int64_t)p.n_tiles * steps_all;
-  // workgroups whose unit ranges meet this tile: g(u) = floor(((u + 1) * G - 1) / N)
-  const int64_t u0 = (int64_t)t_rel * steps_all, u1 = u0 + steps_all - 1;
-  const int g_first = (int)(((u0 + 1) * p.groups - 1) / n_units), g_last = (int)(((u1 + 1) * p.groups - 1) / n_units);
+  const int tile = p.tile0 + t_rel;
+  int tile_n, tile_m;
+  decode_tile(tile, p.tiles_m, p.tiles_n, tile_n, tile_m);
+  const int plane = p.BH * p.BW;
   const int pp = tile_n * BN + wn * TN + j * 32 + l32;
   const bool pos_ok = pp < p.P;
-  const int plane = p.BH * p.BW;
   const int img = pp / plane, q = pp - img * plane, oh = q / p.BW, ow = q - oh * p.BW;
   const int64_t y_off = (int64_t)img * p.ys[0] + (int64_t)oh * p.ys[2] + (int64_t)ow * p.ys[3];
   float acc[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-  for (int g = g_first; g <= g_last; ++g) {
-    const int first_tile = (int)((g * n_units / p.groups) / steps_all);   // tile of the workgroup's first unit = its segment 0
-    const float* sl = p.slots + ((int64_t)g * p.max_segments + (t_rel - first_tile)) * (BM * BN) + (i * FN + j) * 16 * NT + tid;
+  balance_for_each_slot(p.bal, steps_all, t_rel, [&](int slot) {
+    const float* sl = p.slots + (int64_t)slot * (BM * BN) + (i * FN + j) * 16 * NT + tid;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] += sl[v * NT];
-  }
+  });
   if (!pos_ok) return;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
@@ -441,16 +444,20 @@ constexpr int kConvSlots = 512;        // two resident workgroups on each of the
                                        // fits only with register spills and measured no faster)
 
 // Which kernel shape a shard of P positions in BH x BW boxes uses, and how its tiles are launched:
-// the first `whole` tiles one workgroup each (full waves of kConvSlots), the remaining `rest`
-// tiles cut into (tile, channel step) units dealt evenly to `groups` workgroups.
+// the first `whole` tiles one workgroup each (full waves of kConvSlots), the channel steps of the
+// remaining `rest` tiles dealt to kConvSlots workgroups (`bal`, see tofu_balance.h).
 struct ConvPlan {
   int variant;        // 3x3: 0: 64 x 256 positions, 4 channels per step; 1: 64 x 128, 8 channels; 2: 64 x 128, 4 channels;
                       // 1x3: 10: 64 x 256 positions, 12 channels per step; 11: 64 x 128, 12 channels; -1: none fits
   int64_t E;          // staged floats per channel
   int64_t tiles, whole, rest;
-  int groups, max_segments;
+  Balance bal;        // of the `rest` tiles
+  int64_t slots;      // accumulator slots the balanced launch writes
   int BM, BN, CK;
 };
+
+// Channel steps a workgroup loses per segment (list set-up, filling the pipeline, writing the slot).
+constexpr int kSegmentCost = 2;
 
 static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t CI, bool multi = false, int KH = 3, int KW = 3, int BM = 64) {
   ConvPlan pl;
@@ -480,17 +487,15 @@ static ConvPlan conv_plan(int64_t P, int64_t BH, int64_t BW, int64_t CO, int64_t
   if (pl.rest * 32 >= kConvSlots * 31 || steps < 4) pl.rest = 0;
   pl.whole = pl.tiles - pl.rest;
   if (pl.rest > 0) {
-    const int64_t units = pl.rest * steps;
-    pl.groups = (int)(units < kConvSlots ? units : kConvSlots);
-    const int64_t per = (units + pl.groups - 1) / pl.groups;           // most units per workgroup
-    pl.max_segments = (int)((per + steps - 2) / steps + 1);
+    pl.bal = balance_plan(pl.rest, steps, kConvSlots, kSegmentCost);
+    pl.slots = balance_slots(pl.bal, (int)steps);
   }
   return pl;
 }
 
 static size_t plan_bytes(const ConvPlan& pl) {
   if (pl.variant < 0 || pl.rest == 0) return 0;
-  return (size_t)pl.groups * pl.max_segments * pl.BM * pl.BN * sizeof(float);
+  return (size_t)pl.slots * pl.BM * pl.BN * sizeof(float);
 }
 
 // A shard's output channels are computed in tile rows of 64.  When the last row would hold at most 32
@@ -540,12 +545,12 @@ static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, 
     }
   };
   if (pl.whole > 0) {
-    p.tile0 = 0; p.n_tiles = (int)pl.whole; p.groups = 0; p.max_segments = 0;
+    p.tile0 = 0; p.n_tiles = (int)pl.whole; memset(&p.bal, 0, sizeof(p.bal));
     launch(false, (int)pl.whole);
   }
   if (pl.rest > 0) {
-    p.tile0 = (int)pl.whole; p.n_tiles = (int)pl.rest; p.groups = pl.groups; p.max_segments = pl.max_segments;
-    launch(true, pl.groups);
+    p.tile0 = (int)pl.whole; p.n_tiles = (int)pl.rest; p.bal = pl.bal;
+    launch(true, pl.bal.groups);
     hipLaunchKernelGGL((conv2d_segment_sum_kernel<BM, BN, WM, WN>), dim3((unsigned)pl.rest, Cfg::FM * Cfg::FN), dim3(Cfg::kThreads), 0, stream,
                        p, (p.CI + CK - 1) / CK);
   }

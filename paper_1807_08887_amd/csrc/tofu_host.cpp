@@ -367,7 +367,8 @@ size_t tofu_workspace_bytes(const tofu_op_desc_t* op, const tofu_split_t* splits
     return s > 1 ? (size_t)s * (size_t)m * (size_t)n * sizeof(float) : 0;
   }
   if (op->kind == TOFU_OP_CONV2D_WGRAD) {
-    return wgrad_workspace_bytes(r.hi[0] - r.lo[0], r.hi[1] - r.lo[1], r.hi[2] - r.lo[2]);
+    return wgrad_workspace_bytes(r.hi[0] - r.lo[0], r.hi[1] - r.lo[1], r.hi[2] - r.lo[2], conv_out_extent(op->H, op->KH, op->stride, op->pad),
+                                 conv_out_extent(op->W, op->KW, op->stride, op->pad));
   }
   if (op->kind == TOFU_OP_CONV2D) {         // segment slots of the balanced last wave
     const int64_t bh = r.hi[TOFU_CONV_DIM_H] - r.lo[TOFU_CONV_DIM_H], bw = r.hi[TOFU_CONV_DIM_W] - r.lo[TOFU_CONV_DIM_W];

@@ -54,8 +54,8 @@ void box_byte_span(const tofu_tensor_t* t, const int64_t* stride, const tofu_reg
 // ---- launch plans (shared by tofu_workspace_bytes and the entry points) ----
 // Number of K slices the matmul kernel cuts its own reduction into for an m x n x k shard.
 int matmul_split_k(int64_t m, int64_t n, int64_t k);
-// Workspace the weight-gradient kernel needs for a shard of co x ci output channels and nb images.
-size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb);
+// Workspace the weight-gradient kernel needs for a shard of co x ci output channels and nb images of ho x wo outputs.
+size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb, int64_t ho, int64_t wo);
 
 // Workspace the convolution kernels need for a shard of P positions in BH x BW output boxes with
 // co output and ci input channels (the segment slots of its balanced last wave, possibly 0).

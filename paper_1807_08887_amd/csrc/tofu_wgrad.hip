@@ -13,18 +13,21 @@
 //     touch, x[n, ci tile, h-pad .. h+R-1-pad+2, :], are staged with their zero border, so the
 //     nine taps are nine shifted reads of the same staged rows.  One MFMA contracts two
 //     adjacent output columns (lanes 0-31: w, lanes 32-63: w+1).
-//   * Load balance: the work is T tiles x (NB images x their K steps' row groups) ("units", tile-major:
-//     one unit is one output row, or the group of rows one step takes).  400 tiles cannot fill
-//     512 workgroup slots evenly, so workgroup g takes the units [g*N/G, (g+1)*N/G) -- the same
-//     even split as a shard range; with rows as units every workgroup gets the same number of steps
-//     to within one (with whole images as units some had 13 images where others had 12).  A run of units inside one tile is a segment; every segment
-//     goes tap-major to a workspace slot and a second kernel sums each tile's segments in
-//     workgroup order (fixed, no atomics) and restores the [co][ci][kh][kw] layout.  Each
-//     workgroup writes at most a few slots, so the workspace is about 2.5x the output instead
-//     of one full copy per image.  Shards with very many tiles, tiles that divide 512, or a
-//     single image run one workgroup per tile and write dw directly.
+//   * Load balance: the work is T tiles x (NB images x their row groups) units, one unit being the
+//     output rows one step takes (or the chunks of one wide row).  400 tiles cannot fill 512 workgroup
+//     slots evenly, so the units are dealt to 512 workgroups as tofu_balance.h describes: a
+//     workgroup of its own for the first part of every tile, the tails shared out among the rest,
+//     every workgroup the same number of steps to within a few, and the workgroups that run side
+//     by side at the same (image, row) at the same time.  Every piece goes tap-major to a workspace
+//     slot and a second kernel sums each tile's slots in the order of the units (fixed, no atomics)
+//     and restores the [co][ci][kh][kw] layout.  Shards with very many tiles, tiles that divide
+//     512, or a single image run one workgroup per tile and write dw directly.
+//   * Tile order: channel tile rows are numbered in panels of kWgradPanel, output channel tile fastest
+//     inside a panel, so that the 64 workgroups of one XCD are 4 output x 16 input channel tiles,
+//     which share 4 dy rows and 16 x rows per step through that XCD's L2.
 #include <hip/hip_runtime.h>
 
+#include "tofu_balance.h"
 #include "tofu_internal.h"
 #include "tofu_mfma.h"
 
@@ -35,7 +38,7 @@ struct WgradArgs {
   const float* dy;   // element (n_lo, co_lo, 0, 0)
   float* out;        // dw element (co_lo, ci_lo, 0, 0)
   int accumulate;    // 1: the shard's sum is added to what the output box holds
-  float* slots;      // workspace: [groups * max_segments] partial tiles of kSlotFloats floats
+  float* slots;      // workspace: partial tiles of kSlotFloats floats (slot numbering: tofu_balance.h)
   int64_t xs[4], ds[4], os[4];   // element strides: x (n,c,h,w), dy (n,co,h,w), out (co,ci,kh,kw)
   uint32_t x_bytes, dy_bytes;    // bytes spanned by the two input boxes (buffer bounds, fast path)
   int NB, CO, CI;    // images, output channels, input channels of the shard
@@ -43,8 +46,7 @@ struct WgradArgs {
   int IH, IW;        // rows / columns of the clipped input box
   int plh, plw;      // zero rows / columns in front of the input box
   int tiles_m, tiles_n;
-  int groups;        // workgroups that share the tiles x images units
-  int max_segments;  // most tile segments one workgroup can produce
+  Balance bal;       // balanced launches: how the tiles x units are dealt to bal.groups workgroups
   int CW;            // output columns per K step (<= 32, multiple of 4 unless WO itself is not)
   int chunks;        // column chunks per output row
   int vec;           // 1: rows of dy are contiguous and 16-byte aligned -> vector loads (generic path)
@@ -54,7 +56,18 @@ struct WgradArgs {
 constexpr int kKR = 32;              // dy positions per K step (a chunk of one output row)
 constexpr int kLDW = kKR + 2;        // staged x columns per row: chunk widened by the filter window
 constexpr int kPLX = 3 * kLDW + 3;
+constexpr int kWgradPanel = 4;       // output-channel tiles per panel of the tile order
 constexpr int kSlotFloats = 9 * 128 * 32;   // one partial tile in the workspace: [tap][128 co][32 ci]   // staged floats per input channel; odd -> 32 channels hit 32 banks
+
+// Tile number -> (input-channel tile, output-channel tile): panels of kWgradPanel output-channel tiles,
+// the output-channel tile fastest inside a panel.
+__host__ __device__ __forceinline__ void wgrad_decode_tile(int tile, int tiles_m, int tiles_n, int& tile_n, int& tile_m) {
+  const int panel_tiles = kWgradPanel * tiles_n;
+  const int panel = tile / panel_tiles, rem = tile - panel * panel_tiles;
+  const int rows = tiles_m - panel * kWgradPanel < kWgradPanel ? tiles_m - panel * kWgradPanel : kWgradPanel;
+  tile_n = rem / rows;
+  tile_m = panel * kWgradPanel + (rem - tile_n * rows);
+}
 
 // FAST: dy rows are whole aligned vectors (or one of the narrow-image forms below applies) and
 // every operand offset fits 32 bits.  Then each lane's staging addresses are fixed byte offsets,
@@ -91,14 +104,13 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  // consecutive workgroup numbers (which share tiles) stay on one XCD
-  const int per_xcd = (p.groups + 7) / 8;
+  // consecutive workgroup numbers (which share operand rows) stay on one XCD
+  const int total = BALANCED ? p.bal.groups : p.tiles_m * p.tiles_n;
+  const int per_xcd = (total + 7) / 8;
   const int g = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (g >= p.groups) return;
+  if (g >= total) return;
   const int HG = (p.HO + R - 1) / R;             // row groups (= units) per image: groups of R output rows
   const int UPT = p.NB * HG;                     // units per tile
-  const int64_t n_units = (int64_t)p.tiles_m * p.tiles_n * UPT;
-  const int64_t u_begin = g * n_units / p.groups, u_end = (g + 1) * n_units / p.groups;
   const int KP = (p.CW + 1) / 2;             // column pairs contracted per step
   const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dy, p.dy_bytes);
   // the x buffer starts plh rows and plw columns before the box, so that staged element (r, c) of a
@@ -108,19 +120,21 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int d_row = tid / (kKR / 4), d_q = tid % (kKR / 4);
   const int x_ci = tid / TPC, x_sub = tid % TPC;
 
-  // Segments are numbered in unit order but processed last to first: a workgroup's run of units
-  // is shorter than one tile's images in the balanced launches, so its last segment holds the
-  // low image numbers and its first the high ones; walking them in this order makes every
-  // workgroup sweep the images upwards, and the workgroups of a moment share image planes in L2.
-  if (u_begin >= u_end) return;
-  const int first_tile = (int)(u_begin / UPT), last_tile = (int)((u_end - 1) / UPT);
-  for (int segment = last_tile - first_tile; segment >= 0; --segment) {
+  BalanceWalk walk;
+  if (BALANCED) {
+    walk = balance_walk(p.bal, UPT, g);
+    if (walk.count == 0) return;
+  }
+  const int n_segments = BALANCED ? walk.count : 1;
+  for (int seg_i = 0; seg_i < n_segments; ++seg_i) {
   // ---- one segment: row groups [r_begin, r_end) of one tile, numbered image-major (image n, group h -> n * HG + h) ----
-  const int tile = first_tile + segment;
-  const int64_t t0 = (int64_t)tile * UPT;
-  const int r_begin = (int)(max(u_begin, t0) - t0);
-  const int r_end = (int)(min(u_end, t0 + UPT) - t0);
-  const int tile_n = tile / p.tiles_m, tile_m = tile % p.tiles_m;
+  int tile = g, r_begin = 0, r_end = UPT, slot = 0;
+  if (BALANCED) {
+    const BalanceSegment seg = balance_segment(walk, seg_i);
+    tile = seg.tile; r_begin = seg.begin; r_end = seg.end; slot = seg.slot;
+  }
+  int tile_n, tile_m;
+  wgrad_decode_tile(tile, p.tiles_m, p.tiles_n, tile_n, tile_m);
   const int m0 = tile_m * BM, c0 = tile_n * BCI;
   const int steps = (r_end - r_begin) * p.chunks;
 
@@ -343,7 +357,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 
   if (BALANCED) {
     // slot [tap][co_local][ci_local]: a lane row of 32 input channels is one 128-byte store
-    float* o = p.slots + ((int64_t)g * p.max_segments + segment) * kSlotFloats + (wave * 32 + 4 * half) * BCI + l32;
+    float* o = p.slots + (int64_t)slot * kSlotFloats + (wave * 32 + 4 * half) * BCI + l32;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
@@ -365,32 +379,28 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   }  // segments
 }
 
-// Sums every tile's segments (one to a few workspace slots) in workgroup order and writes
+// Sums every tile's pieces (workspace slots) in the order of their units and writes
 // dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine reads per slot are coalesced
 // across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
 __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
-                                                                 const float* __restrict__ slots, int groups, int max_segments, int UPT,
+                                                                 const float* __restrict__ slots, const Balance bal, int UPT,
                                                                  int tiles_m, int tiles_n, int CO, int CI, int accumulate) {
   constexpr int BM = 128, BCI = 32;
-  const int64_t n_units = (int64_t)tiles_m * tiles_n * UPT;   // UPT: units (row groups of all images) per tile
   const int64_t items = (int64_t)tiles_m * tiles_n * BM * BCI;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
     const int tile = (int)(i / (BM * BCI)), local = (int)(i % (BM * BCI)), co_l = local / BCI, ci_l = local % BCI;
-    const int tile_n = tile / tiles_m, tile_m = tile % tiles_m;
+    int tile_n, tile_m;
+    wgrad_decode_tile(tile, tiles_m, tiles_n, tile_n, tile_m);
     const int co = tile_m * BM + co_l, ci = tile_n * BCI + ci_l;
-    // workgroups whose unit ranges meet this tile: g(u) = floor(((u + 1) * G - 1) / N)
-    const int64_t u0 = (int64_t)tile * UPT, u1 = u0 + UPT - 1;
-    const int g_first = (int)(((u0 + 1) * groups - 1) / n_units), g_last = (int)(((u1 + 1) * groups - 1) / n_units);
     if (co >= CO || ci >= CI) continue;
     float acc[9];
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) acc[tap] = 0.f;
-    for (int g = g_first; g <= g_last; ++g) {
-      const int first_tile = (int)((g * n_units / groups) / UPT);   // tile of the workgroup's first unit = its segment 0
-      const float* sl = slots + ((int64_t)g * max_segments + (tile - first_tile)) * kSlotFloats + co_l * BCI + ci_l;
+    balance_for_each_slot(bal, UPT, tile, [&](int slot) {
+      const float* sl = slots + (int64_t)slot * kSlotFloats + co_l * BCI + ci_l;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
-    }
+    });
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       float* o = dw + co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw;
@@ -402,28 +412,26 @@ __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restric
 constexpr int gBM = 128, gBCI = 32;
 constexpr int kWgradSlots = 512;       // two resident workgroups on each of the 256 compute units
 
-// Number of workgroups and the most segments one of them can produce for a shard of
-// co x ci output channels and nb images; groups == tiles means whole tiles and no workspace.
-void wgrad_plan(int64_t co, int64_t ci, int64_t nb, int* groups, int* max_segments) {
-  const int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
-  const int64_t units = tiles * nb;
-  if (tiles >= 2 * kWgradSlots || nb < 2 || tiles % kWgradSlots == 0) {
-    *groups = (int)tiles;
-    *max_segments = 1;
-    return;
-  }
-  const int64_t g = units < kWgradSlots ? units : kWgradSlots;
-  *groups = (int)g;
-  // A workgroup's run of units is at most ceil(units / g) long, so it meets at most ceil(tiles / g) + 1 tiles --
-  // whatever the unit (images here; the kernels cut finer, into the row groups of their steps).
-  *max_segments = (int)((tiles + g - 1) / g + 1);
-}
+constexpr int kWgradSegmentCost = 1;   // units a workgroup loses per segment (set-up, pipeline fill, slot write)
 
-size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb) {
-  int groups, max_segments;
-  wgrad_plan(co, ci, nb, &groups, &max_segments);
+// Shards with very many tiles, tiles that fill whole waves, or a single image run one workgroup per tile.
+static bool wgrad_whole_tiles(int64_t tiles, int64_t nb) { return tiles >= 2 * kWgradSlots || nb < 2 || tiles % kWgradSlots == 0; }
+
+// Rows one step takes for an image of wo columns in the fastest form that may apply (see shard_wgrad).
+static int wgrad_max_rows_per_step(int64_t ho, int64_t wo) { return wo == 7 ? 4 : ((wo == 14 || wo == 16) && ho % 2 == 0) ? 2 : 1; }
+
+// Workspace for a shard of co x ci output channels, nb images of ho x wo outputs: enough for whichever
+// form of the kernel (rows per step) the operands' strides and alignment allow.
+size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb, int64_t ho, int64_t wo) {
   const int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
-  return groups == tiles ? 0 : (size_t)groups * max_segments * kSlotFloats * sizeof(float);
+  if (wgrad_whole_tiles(tiles, nb)) return 0;
+  int64_t slots = 0;
+  for (int rows = 1; rows <= wgrad_max_rows_per_step(ho, wo); rows *= 2) {
+    const int64_t upt = nb * ((ho + rows - 1) / rows);
+    const int64_t n = balance_slots(balance_plan(tiles, upt, kWgradSlots, kWgradSegmentCost), (int)upt);
+    if (n > slots) slots = n;
+  }
+  return (size_t)slots * kSlotFloats * sizeof(float);
 }
 
 static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int32_t nsplits, const tofu_tensor_t* x,
@@ -488,20 +496,22 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
   const bool fast = fast_row || fast_2x14 || fast_2x16 || fast_4x7;
   p.x_bytes = fast ? (uint32_t)(4 * x_span) : 0;
   p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
-  int groups, max_segments;
-  wgrad_plan(CO, CI, NB, &groups, &max_segments);
-  p.groups = groups;
-  p.max_segments = max_segments;
+  const int64_t rows_per_step = !fast ? 1 : (fast_2x14 || fast_2x16) ? 2 : fast_4x7 ? 4 : 1;   // the R of the kernel picked below
+  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n, UPT = NB * ((HO + rows_per_step - 1) / rows_per_step);
+  const bool balanced = !wgrad_whole_tiles(tiles, NB);
+  p.bal = Balance{0, 0, 0, 0, 0, 0};
+  if (balanced) p.bal = balance_plan(tiles, UPT, kWgradSlots, kWgradSegmentCost);
+  const int groups = balanced ? p.bal.groups : (int)tiles;
   p.out = dw_out;
   p.accumulate = accumulate ? 1 : 0;
   p.slots = static_cast<float*>(workspace);
-  const size_t need = wgrad_workspace_bytes(CO, CI, NB);
+  const size_t need = balanced ? (size_t)balance_slots(p.bal, (int)UPT) * kSlotFloats * sizeof(float) : 0;
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
   // fast shards of the common widths run the fully unrolled step (column pairs rounded up to even)
   const int kpe = ((p.CW + 1) / 2 + 1) & ~1;
   void (*kern)(const WgradArgs);
-  if (need > 0) {
+  if (balanced) {
     kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, true>
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, true, 14, 2, 4>
            : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, true, 16, 2, 4>
@@ -522,16 +532,15 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, false, 16>
                                  : wgrad_kernel<gBM, gBCI, true, false>;
   }
-  const int64_t rows_per_step = !fast ? 1 : (fast_2x14 || fast_2x16) ? 2 : fast_4x7 ? 4 : 1;   // the R of the kernel picked above
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
-  if (need > 0) {
+  if (balanced) {
     const int64_t items = (int64_t)p.tiles_m * p.tiles_n * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
     hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
-                       static_cast<const float*>(workspace), groups, max_segments, (int)(NB * ((HO + rows_per_step - 1) / rows_per_step)), p.tiles_m, p.tiles_n,
+                       static_cast<const float*>(workspace), p.bal, (int)UPT, p.tiles_m, p.tiles_n,
                        (int)CO, (int)CI, accumulate ? 1 : 0);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient segment sum launch failed: %s", hipGetErrorString(e));
