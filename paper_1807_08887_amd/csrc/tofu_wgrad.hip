@@ -20,8 +20,8 @@
 //     every workgroup the same number of steps to within a few, and the workgroups that run side
 //     by side at the same (image, row) at the same time.  Every piece goes tap-major to a workspace
 //     slot and a second kernel sums each tile's slots in the order of the units (fixed, no atomics)
-//     and restores the [co][ci][kh][kw] layout.  Shards with very many tiles, tiles that divide
-//     512, or a single image run one workgroup per tile and write dw directly.
+//     and restores the [co][ci][kh][kw] layout.  Whole waves of 512 tiles (and every tile of a
+//     single-image shard) run one workgroup per tile in a launch of their own and write dw directly.
 //   * Tile order: channel tile rows are numbered in panels of kWgradPanel, output channel tile fastest
 //     inside a panel, so that the 64 workgroups of one XCD are 4 output x 16 input channel tiles,
 //     which share 4 dy rows and 16 x rows per step through that XCD's L2.
@@ -46,7 +46,8 @@ struct WgradArgs {
   int IH, IW;        // rows / columns of the clipped input box
   int plh, plw;      // zero rows / columns in front of the input box
   int tiles_m, tiles_n;
-  Balance bal;       // balanced launches: how the tiles x units are dealt to bal.groups workgroups
+  int tile0, n_tiles;  // the launch covers the tiles [tile0, tile0 + n_tiles) of the tile order
+  Balance bal;       // balanced launches: how the units of those tiles are dealt to bal.groups workgroups
   int CW;            // output columns per K step (<= 32, multiple of 4 unless WO itself is not)
   int chunks;        // column chunks per output row
   int vec;           // 1: rows of dy are contiguous and 16-byte aligned -> vector loads (generic path)
@@ -105,7 +106,7 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   // consecutive workgroup numbers (which share operand rows) stay on one XCD
-  const int total = BALANCED ? p.bal.groups : p.tiles_m * p.tiles_n;
+  const int total = BALANCED ? p.bal.groups : p.n_tiles;
   const int per_xcd = (total + 7) / 8;
   const int g = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (g >= total) return;
@@ -128,10 +129,10 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
   const int n_segments = BALANCED ? walk.count : 1;
   for (int seg_i = 0; seg_i < n_segments; ++seg_i) {
   // ---- one segment: row groups [r_begin, r_end) of one tile, numbered image-major (image n, group h -> n * HG + h) ----
-  int tile = g, r_begin = 0, r_end = UPT, slot = 0;
+  int tile = p.tile0 + g, r_begin = 0, r_end = UPT, slot = 0;
   if (BALANCED) {
     const BalanceSegment seg = balance_segment(walk, seg_i);
-    tile = seg.tile; r_begin = seg.begin; r_end = seg.end; slot = seg.slot;
+    tile = p.tile0 + seg.tile; r_begin = seg.begin; r_end = seg.end; slot = seg.slot;
   }
   int tile_n, tile_m;
   wgrad_decode_tile(tile, p.tiles_m, p.tiles_n, tile_n, tile_m);
@@ -383,14 +384,14 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 // dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine reads per slot are coalesced
 // across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
 __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
-                                                                 const float* __restrict__ slots, const Balance bal, int UPT,
+                                                                 const float* __restrict__ slots, const Balance bal, int UPT, int tile0,
                                                                  int tiles_m, int tiles_n, int CO, int CI, int accumulate) {
   constexpr int BM = 128, BCI = 32;
-  const int64_t items = (int64_t)tiles_m * tiles_n * BM * BCI;
+  const int64_t items = (int64_t)bal.n * BM * BCI;   // the balanced tiles [tile0, tile0 + bal.n)
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
     const int tile = (int)(i / (BM * BCI)), local = (int)(i % (BM * BCI)), co_l = local / BCI, ci_l = local % BCI;
     int tile_n, tile_m;
-    wgrad_decode_tile(tile, tiles_m, tiles_n, tile_n, tile_m);
+    wgrad_decode_tile(tile0 + tile, tiles_m, tiles_n, tile_n, tile_m);
     const int co = tile_m * BM + co_l, ci = tile_n * BCI + ci_l;
     if (co >= CO || ci >= CI) continue;
     float acc[9];
@@ -414,8 +415,12 @@ constexpr int kWgradSlots = 512;       // two resident workgroups on each of the
 
 constexpr int kWgradSegmentCost = 1;   // units a workgroup loses per segment (set-up, pipeline fill, slot write)
 
-// Shards with very many tiles, tiles that fill whole waves, or a single image run one workgroup per tile.
-static bool wgrad_whole_tiles(int64_t tiles, int64_t nb) { return tiles >= 2 * kWgradSlots || nb < 2 || tiles % kWgradSlots == 0; }
+// Tiles of a shard that are launched one workgroup each (whole waves of kWgradSlots; all of them for a single
+// image or when the last wave is nearly full); the others, the last `tiles - whole`, are balanced.
+static int64_t wgrad_whole_tiles(int64_t tiles, int64_t nb) {
+  const int64_t rest = tiles % kWgradSlots;
+  return (nb < 2 || rest * 32 >= kWgradSlots * 31) ? tiles : tiles - rest;
+}
 
 // Rows one step takes for an image of wo columns in the fastest form that may apply (see shard_wgrad).
 static int wgrad_max_rows_per_step(int64_t ho, int64_t wo) { return wo == 7 ? 4 : ((wo == 14 || wo == 16) && ho % 2 == 0) ? 2 : 1; }
@@ -424,11 +429,12 @@ static int wgrad_max_rows_per_step(int64_t ho, int64_t wo) { return wo == 7 ? 4 
 // form of the kernel (rows per step) the operands' strides and alignment allow.
 size_t wgrad_workspace_bytes(int64_t co, int64_t ci, int64_t nb, int64_t ho, int64_t wo) {
   const int64_t tiles = ((co + gBM - 1) / gBM) * ((ci + gBCI - 1) / gBCI);
-  if (wgrad_whole_tiles(tiles, nb)) return 0;
+  const int64_t rest = tiles - wgrad_whole_tiles(tiles, nb);
+  if (rest == 0) return 0;
   int64_t slots = 0;
   for (int rows = 1; rows <= wgrad_max_rows_per_step(ho, wo); rows *= 2) {
     const int64_t upt = nb * ((ho + rows - 1) / rows);
-    const int64_t n = balance_slots(balance_plan(tiles, upt, kWgradSlots, kWgradSegmentCost), (int)upt);
+    const int64_t n = balance_slots(balance_plan(rest, upt, kWgradSlots, kWgradSegmentCost), (int)upt);
     if (n > slots) slots = n;
   }
   return (size_t)slots * kSlotFloats * sizeof(float);
@@ -498,21 +504,19 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
   p.dy_bytes = fast ? (uint32_t)(4 * d_span) : 0;
   const int64_t rows_per_step = !fast ? 1 : (fast_2x14 || fast_2x16) ? 2 : fast_4x7 ? 4 : 1;   // the R of the kernel picked below
   const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n, UPT = NB * ((HO + rows_per_step - 1) / rows_per_step);
-  const bool balanced = !wgrad_whole_tiles(tiles, NB);
+  const int64_t whole = wgrad_whole_tiles(tiles, NB), rest = tiles - whole;
   p.bal = Balance{0, 0, 0, 0, 0, 0};
-  if (balanced) p.bal = balance_plan(tiles, UPT, kWgradSlots, kWgradSegmentCost);
-  const int groups = balanced ? p.bal.groups : (int)tiles;
+  if (rest > 0) p.bal = balance_plan(rest, UPT, kWgradSlots, kWgradSegmentCost);
   p.out = dw_out;
   p.accumulate = accumulate ? 1 : 0;
   p.slots = static_cast<float*>(workspace);
-  const size_t need = balanced ? (size_t)balance_slots(p.bal, (int)UPT) * kSlotFloats * sizeof(float) : 0;
+  const size_t need = rest > 0 ? (size_t)balance_slots(p.bal, (int)UPT) * kSlotFloats * sizeof(float) : 0;
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(TOFU_ERR_WORKSPACE_TOO_SMALL, "conv2d weight-gradient shard needs %zu workspace bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
   // fast shards of the common widths run the fully unrolled step (column pairs rounded up to even)
   const int kpe = ((p.CW + 1) / 2 + 1) & ~1;
-  void (*kern)(const WgradArgs);
-  if (balanced) {
-    kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, true>
+  void (*kern_balanced)(const WgradArgs) =
+             !fast                 ? wgrad_kernel<gBM, gBCI, false, true>
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, true, 14, 2, 4>
            : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, true, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, true, 16, 4, 1>
@@ -521,8 +525,8 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, true, 14>
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, true, 16>
                                  : wgrad_kernel<gBM, gBCI, true, true>;
-  } else {
-    kern = !fast                 ? wgrad_kernel<gBM, gBCI, false, false>
+  void (*kern_whole)(const WgradArgs) =
+             !fast                 ? wgrad_kernel<gBM, gBCI, false, false>
            : fast_2x14           ? wgrad_kernel<gBM, gBCI, true, false, 14, 2, 4>
            : fast_2x16           ? wgrad_kernel<gBM, gBCI, true, false, 16, 2, 4>
            : fast_4x7            ? wgrad_kernel<gBM, gBCI, true, false, 16, 4, 1>
@@ -531,16 +535,23 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
            : kpe == 14           ? wgrad_kernel<gBM, gBCI, true, false, 14>
            : kpe == 16           ? wgrad_kernel<gBM, gBCI, true, false, 16>
                                  : wgrad_kernel<gBM, gBCI, true, false>;
-  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(kern, dim3((groups + 7) / 8 * 8), dim3(NT), 0, s, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
-  if (balanced) {
-    const int64_t items = (int64_t)p.tiles_m * p.tiles_n * gBM * gBCI;
+  hipError_t e;
+  if (whole > 0) {   // whole waves: one workgroup per tile, dw written directly
+    p.tile0 = 0; p.n_tiles = (int)whole;
+    hipLaunchKernelGGL(kern_whole, dim3((unsigned)((whole + 7) / 8 * 8)), dim3(NT), 0, s, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
+  }
+  if (rest > 0) {    // the last, partial wave: balanced over all workgroup slots, pieces summed by a second kernel
+    p.tile0 = (int)whole; p.n_tiles = (int)rest;
+    hipLaunchKernelGGL(kern_balanced, dim3((p.bal.groups + 7) / 8 * 8), dim3(NT), 0, s, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
+    const int64_t items = rest * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
     hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
-                       static_cast<const float*>(workspace), p.bal, (int)UPT, p.tiles_m, p.tiles_n,
+                       static_cast<const float*>(workspace), p.bal, (int)UPT, (int)whole, p.tiles_m, p.tiles_n,
                        (int)CO, (int)CI, accumulate ? 1 : 0);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient segment sum launch failed: %s", hipGetErrorString(e));
