@@ -43,7 +43,7 @@ LEG_KERNELS = {"conv_cout": "conv2d_kernel<64,256,4,1,4,8,balanced,3,3> + conv2d
                "conv_cout_h": "conv2d_kernel<64,256,4,1,4,8,balanced,3,3> + conv2d_segment_sum_kernel",
                "wgrad_batch": "wgrad_kernel<128,32,fast,balanced,14,1,4> + wgrad_segment_sum_kernel",
                "gemm_ksplit": "matmul_kernel<KG=2,TA=false,TB=false,GUARDED=false>", "gemm_nsplit": "matmul_kernel<KG=2,TA=false,TB=false,GUARDED=false> + slice_sum_kernel"}
-EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h",
+EXTRA_NOTES = {"conv_cout_h_fused": "replaces fetch_halo + conv_cout_h; reads the halo row out of the neighbour's whole 7-row block (no copy of it exists)",
                "gemm_ksplit_accumulate": "gemm_ksplit adding into a resident [128,32768] buffer (reduction fused into the epilogue)",
                "conv1d_cout": "the paper's conv1d (Fig. 1): 2048 channels, window 3, 512 outputs per row, batch 64, C_out/8 shard; filters [ci][co][dx] re-ordered inside the call",
                "wgrad_batch_accumulate": "wgrad_batch adding into a resident dW (reduction fused into the segment sum)",

@@ -105,8 +105,14 @@ struct ConvCfg {
   static size_t lds_floats(int PL) { return 2 * ((size_t)WB + (size_t)xb(PL)); }
 };
 
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool MULTI, bool BALANCED, int KH = 3, int KW = 3>
+// SRC: where the input region lives.  0: one buffer, addressed with 32-bit buffer offsets.  1: several
+// blocks, each staging item keeps a 64-bit address and its own increment per channel step.  2: several
+// blocks that share their channel stride and lie within one 2 GiB window of addresses: the window is one
+// buffer and an item's offset points into whichever block holds its element, so the step loop is that of
+// form 0 (the blocks of a halo exchange are usually allocated alike and close together).
+template <int BM, int BN, int CK, int WM, int WN, int XJ, int SRC, bool BALANCED, int KH = 3, int KW = 3>
 __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources* srcs) {
+  constexpr bool MULTI = SRC == 1;
   using Cfg = ConvCfg<BM, BN, CK, WM, WN, XJ, KH, KW>;
   constexpr int NT = Cfg::kThreads, FM = Cfg::FM, FN = Cfg::FN, KK = Cfg::KK, LDM = Cfg::LDM, WV = Cfg::WV, T = Cfg::T;
   constexpr uint32_t kNone = kNoOffset;
@@ -184,6 +190,13 @@ __device__ __forceinline__ void conv2d_body(const ConvArgs& p, const ConvSources
           x_ptr[j] = S.base + ((int64_t)img * S.s[0] + (int64_t)ci_l * S.s[1] + (int64_t)ih * S.s[2] + (int64_t)iw * S.s[3]);
           x_inc[j] = CK * (int)S.s[1];
         }
+      }
+    } else if constexpr (SRC == 2) {
+      x_voff[j] = kNone;
+      for (int b = 0; b < srcs->n; ++b) {     // the blocks tile the region: at most one of them holds the coordinate
+        const ConvSrc& S = srcs->src[b];
+        if (valid && img >= S.lo[0] && img < S.hi[0] && ih >= S.lo[1] && ih < S.hi[1] && iw >= S.lo[2] && iw < S.hi[2])
+          x_voff[j] = 4u * (uint32_t)((S.base - p.x) + (int64_t)img * S.s[0] + (int64_t)ci_l * S.s[1] + (int64_t)ih * S.s[2] + (int64_t)iw * S.s[3]);
       }
     } else {
       x_voff[j] = valid ? 4u * (uint32_t)((int64_t)img * p.xs[0] + (int64_t)ci_l * p.xs[1] + (int64_t)ih * p.xs[2] + (int64_t)iw * p.xs[3]) : kNone;
@@ -417,13 +430,13 @@ __global__ void __launch_bounds__(64 * WM * WN) conv2d_segment_sum_kernel(const 
 // input region in one buffer
 template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED, int KH = 3, int KW = 3>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_kernel(const ConvArgs p) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, false, BALANCED, KH, KW>(p, nullptr);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, 0, BALANCED, KH, KW>(p, nullptr);
 }
 
 // input region read from the blocks that hold it
-template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED, int KH = 3, int KW = 3>
+template <int BM, int BN, int CK, int WM, int WN, int XJ, bool BALANCED, bool WINDOW, int KH = 3, int KW = 3>
 __global__ void __launch_bounds__(64 * WM * WN, 2) conv2d_multi_kernel(const ConvArgs p, const ConvSources srcs) {
-  conv2d_body<BM, BN, CK, WM, WN, XJ, true, BALANCED, KH, KW>(p, &srcs);
+  conv2d_body<BM, BN, CK, WM, WN, XJ, WINDOW ? 2 : 1, BALANCED, KH, KW>(p, &srcs);
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;   // dynamic LDS a launch may ask for without raising the kernel's limit; the plans stay below it
@@ -536,8 +549,11 @@ static int launch_conv(ConvArgs p, const ConvSources* srcs, const ConvPlan& pl, 
     const dim3 grid((wgs + 7) / 8 * 8), block(Cfg::kThreads);
     if (srcs) {
       if constexpr (KH == 3 && KW == 3) {   // the multi-block form exists for the 3 x 3 shapes only (the caller checked)
-        if (balanced) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true>), grid, block, lds_bytes, stream, p, *srcs);
-        else hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false>), grid, block, lds_bytes, stream, p, *srcs);
+        const bool window = p.x != nullptr;   // the blocks lie in one window of addresses that starts at p.x
+        if (balanced && window) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true, true>), grid, block, lds_bytes, stream, p, *srcs);
+        else if (balanced) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, true, false>), grid, block, lds_bytes, stream, p, *srcs);
+        else if (window) hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false, true>), grid, block, lds_bytes, stream, p, *srcs);
+        else hipLaunchKernelGGL((conv2d_multi_kernel<BM, BN, CK, WM, WN, XJ, false, false>), grid, block, lds_bytes, stream, p, *srcs);
       }
     } else {
       if (balanced) hipLaunchKernelGGL((conv2d_kernel<BM, BN, CK, WM, WN, XJ, true, KH, KW>), grid, block, lds_bytes, stream, p);
@@ -568,6 +584,7 @@ struct ConvProblem {
   const float* x;            // element at in_box's low corner in the single input buffer, or NULL ...
   int64_t xs[4];
   const ConvSources* srcs;   // ... when the box is read from several blocks
+  int64_t window_bytes = 0;  // > 0: the blocks share their channel stride (xs[1]) and lie in [x, x + window_bytes)
   const float* w;            // element (m_lo, k_lo, 0, 0); strides (m, k, kh, kw)
   int64_t ws[4];
   float* y;                  // element at out_box's low corner
@@ -598,7 +615,7 @@ static int conv_core(const ConvProblem& q, hipStream_t stream) {
   }
   if (x_span >= ((int64_t)1 << 29) || w_span >= ((int64_t)1 << 29))
     return fail(TOFU_ERR_UNSUPPORTED, "conv2d: an operand region spans 2 GiB or more");
-  p.x_bytes = q.srcs ? 0u : (uint32_t)(4 * x_span);
+  p.x_bytes = q.srcs ? (uint32_t)q.window_bytes : (uint32_t)(4 * x_span);
   p.w_bytes = (uint32_t)(4 * w_span);
   p.NB = (int)NB; p.CO = (int)CO; p.CI = (int)CI; p.BH = (int)BH; p.BW = (int)BW; p.P = (int)P;
   p.IH = (int)(q.in_box.hi[2] - q.in_box.lo[2]);
@@ -707,6 +724,27 @@ static int shard_conv2d(const tofu_op_desc_t* op, const tofu_split_t* splits, in
       }
     }
     q.srcs = &srcs;
+    // Blocks with one channel stride whose held parts lie within 2 GiB of each other are read as one buffer.
+    const char* lo = nullptr;
+    const char* hi = nullptr;
+    bool alike = srcs.n > 0;
+    int idx = 0;
+    for (int j = 0; j < nsrc && alike; ++j) {
+      if (volume(&inter[j]) == 0) continue;
+      const ConvSrc& S = srcs.src[idx++];
+      for (int d = 0; d < 4; ++d) alike = alike && S.s[d] >= 0;
+      alike = alike && S.s[1] == srcs.src[0].s[1];
+      int64_t st[4] = {S.s[0], S.s[1], S.s[2], S.s[3]};
+      const char *blo, *bhi;
+      box_byte_span(&x_srcs[j], st, &inter[j], &blo, &bhi);
+      if (!lo || blo < lo) lo = blo;
+      if (!hi || bhi > hi) hi = bhi;
+    }
+    if (alike && hi - lo < ((int64_t)1 << 31)) {
+      q.x = reinterpret_cast<const float*>(lo);
+      q.xs[1] = srcs.src[0].s[1];
+      q.window_bytes = hi - lo;
+    }
   } else {
     effective_strides(x, q.xs);
     q.x = element_ptr(x, q.xs, in_boxes[0].lo);

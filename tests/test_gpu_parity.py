@@ -380,31 +380,38 @@ def test_conv2d_on_fetched_halo_region():
     assert e.value.status == -2
 
 
-def blocks_of(x, cuts):
+def blocks_of(x, cuts, views=False):
     """Cut the global array x into blocks along (N, H, W) at the given cut points; returns
-    [(device block, low corner)] in row-major block order (every block spans all channels)."""
+    [(device block, low corner)] in row-major block order (every block spans all channels).
+    views: the blocks are strided views of one device copy of x (all with the same strides, close
+    together in memory) instead of separately allocated dense copies."""
     out = []
     n_cuts, h_cuts, w_cuts = cuts
+    whole = dev(x) if views else None
     for (n0, n1), (h0, h1), (w0, w1) in itertools.product(zip(n_cuts, n_cuts[1:]), zip(h_cuts, h_cuts[1:]), zip(w_cuts, w_cuts[1:])):
-        out.append((dev(x[n0:n1, :, h0:h1, w0:w1].copy()), [n0, 0, h0, w0]))
+        out.append((whole[n0:n1, :, h0:h1, w0:w1] if views else dev(x[n0:n1, :, h0:h1, w0:w1].copy()), [n0, 0, h0, w0]))
     return out
 
 
-@pytest.mark.parametrize("shape,cuts", [
-    ((5, 16, 64, 14, 14), ([0, 5], [0, 7, 14], [0, 14])),             # the halo case: two row blocks
-    ((4, 9, 70, 12, 10), ([0, 1, 4], [0, 5, 6, 12], [0, 3, 10])),     # blocks cut along N, H and W, one row high
-    ((3, 7, 33, 9, 30), ([0, 3], [0, 9], [0, 11, 30])),               # ragged channel tail, 128-position tiles
+@pytest.mark.parametrize("shape,cuts,views", [
+    ((5, 16, 64, 14, 14), ([0, 5], [0, 7, 14], [0, 14]), False),             # the halo case: two row blocks allocated alike
+    ((4, 9, 70, 12, 10), ([0, 1, 4], [0, 5, 6, 12], [0, 3, 10]), False),     # blocks cut along N, H and W, one row high, all strides differ
+    ((3, 7, 33, 9, 30), ([0, 3], [0, 9], [0, 11, 30]), False),               # ragged channel tail, 128-position tiles
+    ((4, 9, 70, 12, 10), ([0, 1, 4], [0, 5, 6, 12], [0, 3, 10]), True),      # the same cuts as views with one channel stride
+    ((6, 10, 96, 14, 14), ([0, 2, 6], [0, 7, 14], [0, 14]), True),           # halo blocks of two image groups, one channel stride
 ])
-def test_conv2d_fused_fetch_matches_oracle_and_the_assembled_region(shape, cuts):
+def test_conv2d_fused_fetch_matches_oracle_and_the_assembled_region(shape, cuts, views):
     """The convolution that reads its region straight from the blocks holding it: against the
     oracle on the global tensor, and bit for bit against fetch-then-convolve, for every shard
-    of a <CO/2, H/2> plan and for the unpartitioned operator."""
+    of a <CO/2, H/2> plan and for the unpartitioned operator.  Blocks with differing channel
+    strides are read through per-item addresses; blocks that share it (dense blocks of one shape,
+    views of one array) through one buffer window."""
     batch, c_in, c_out, H, W = shape
     opd = dict(kind="conv2d", batch=batch, c_in=c_in, c_out=c_out, H=H, W=W, KH=3, KW=3, stride=1, pad=1)
     x = synth.normal(47, 0, (batch, c_in, H, W), 1.0)
     w = synth.normal(47, 1, (c_out, c_in, 3, 3), 0.3)
     val, absum = oracle.conv2d_box(x, w, pad=1)
-    blocks = blocks_of(x, cuts)
+    blocks = blocks_of(x, cuts, views)
     srcs = [tofu.tensor(t, lo) for t, lo in blocks]
     dw = dev(w)
     op = tofu.conv2d_desc(batch, c_in, c_out, H, W)

@@ -9,7 +9,7 @@ Builds, from the seeded generator, the device buffers of the four large workload
   conv_cout     3x3 conv 2560->2560 @14x14, batch 128: shard 3 of an 8-way C_out split
   fetch_halo    input region of the <C_out/8, H/2> shard: own 7 rows + 1 halo row  (region fetch)
   conv_cout_h   the <C_out/8, H/2> shard computed from the fetched region
-  conv_cout_h_fused  (extra, built only when named) the same shard reading the two blocks directly
+  conv_cout_h_fused  (extra, built only when named) the same shard reading its own block and the neighbour's whole block directly
   lstm_cell_nsplit   (extra) element-wise LSTM cell update on the N-split worker's 1024 hidden units (28 bytes per element)
   dgrad_cout         (extra) backward of conv_cout: partial dx from the worker's C_out/8 block of dy and of the filters
   gemm_dx_nsplit     (extra) backward of the N-split gate GEMM: partial dX = dY_s . W_s^T, W_s read transposed in place
@@ -208,7 +208,7 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True, cold_copies: 
         box = reg2["in_boxes"][0]                                       # rows [0,8) of the input
         _, h_cut = tofu.shard_range(H, cfg["k_h"], cfg["shard_h"])           # rows [0, h_cut) are this worker's own block
         own = dx[:, :, :h_cut].contiguous()                               # rows this worker owns
-        halo = dx[:, :, h_cut:h_cut + 1].contiguous()                     # the neighbour's block (only its first row is needed)
+        halo = dx[:, :, h_cut:h_cut + 1].contiguous()                     # the halo row as a dense block of its own (a received row)
         region = torch.zeros([hi - lo for lo, hi in box], dtype=torch.float32, device=dev)
         t_region = tofu.tensor(region, [lo for lo, _ in box])
         srcs = [tofu.tensor(own, [0, 0, 0, 0]), tofu.tensor(halo, [0, 0, h_cut, 0])]
@@ -233,12 +233,15 @@ def build(dev: str = "cuda:0", which=None, keep_host: bool = True, cold_copies: 
                             dict(host_common, box=reg2["out_box"], keep=(region, dw, own, halo)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
         if extra("conv_cout_h_fused"):
+            # the fused form needs no copy of the halo row at all: it reads it out of the neighbour's whole block, rows [h_cut, H)
+            other = dx[:, :, h_cut:].contiguous()
+            srcs = [tofu.tensor(own, [0, 0, 0, 0]), tofu.tensor(other, [0, 0, h_cut, 0])]
             (h0, h1) = reg2["out_box"][2]
             y3 = torch.zeros(NB, co1 - co0, h1 - h0, W, dtype=torch.float32, device=dev)
             taps = _conv_valid_taps(h0, h1, 0, W, H, W)
             legs.append(Leg("conv_cout_h_fused", "mfma", 2.0 * NB * (co1 - co0) * C * taps,
                             _call(tofu.shard_conv2d_fused, op, sp, srcs, tw, tofu.tensor(y3, [0, co0, h0, 0]), _ws(op, sp, dev)), y3,
-                            dict(host_common, box=reg2["out_box"], keep=(dw, own, halo)),
+                            dict(host_common, box=reg2["out_box"], keep=(dw, own, other)),
                             conventional_flop=2.0 * NB * (co1 - co0) * C * 9 * (h1 - h0) * W))
 
     if extra("dgrad_cout"):
