@@ -144,6 +144,48 @@ def test_conv_output_channels_with_a_short_last_tile_row(c_out, batch, hw):
     close(gx.cpu().numpy(), val, absum, f"dgrad ci{c_out}")
 
 
+@pytest.mark.parametrize("batch,c_in,c_out,slots", [(8, 1024, 320, 14 * 35 + 1 * 22 + 2 * 22), (32, 128, 704, 275 + 1 * 237 + 2 * 237)])
+def test_conv_balanced_launch_with_own_pieces_and_tails(batch, c_in, c_out, slots):
+    """Mid-size shards whose tiles do not fill the workgroup slots and whose reductions are long enough for the
+    balanced launch to use all of its forms, every output checked: 35 tiles x 256 channel steps (14 workgroups of
+    their own per tile, one round of whole tails, the last 13 tails shared out step by step) and 275 tiles x 32
+    steps (one own workgroup per tile, 237 tail workgroups).  The accumulating form must add exactly the same sum."""
+    hw = 14
+    x = synth.normal(900 + batch, 0, (batch, c_in, hw, hw), 1.0)
+    w = synth.normal(900 + batch, 1, (c_out, c_in, 3, 3), 0.05)
+    dx_, dw_ = dev(x), dev(w)
+    op = tofu.conv2d_desc(batch, c_in, c_out, hw, hw)
+    # own pieces + whole tails + two slots per tail workgroup for its share of the last tails, 64 x 256 floats each
+    assert tofu.workspace_bytes(op, []) == slots * 64 * 256 * 4, "the shape is meant to take every form of the balanced launch"
+    y = torch.full((batch, c_out, hw, hw), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_conv2d(op, [], tofu.tensor(dx_), tofu.tensor(dw_), tofu.tensor(y), ws(op, []))
+    val, absum = oracle.conv2d_box(x, w, pad=1)
+    close(y.cpu().numpy(), val, absum, f"conv2d b{batch} ci{c_in} co{c_out}")
+    base = torch.full_like(y, 0.5)
+    acc = base.clone()
+    tofu.shard_conv2d_accumulate(op, [], tofu.tensor(dx_), tofu.tensor(dw_), tofu.tensor(acc), ws(op, []))
+    assert torch.equal(acc, base + y), "accumulate differs from add-after"
+
+
+def test_wgrad_balanced_launch_with_own_pieces_and_tails():
+    """40 weight-gradient tiles x 112 row steps on 512 workgroups: 12 own workgroups per tile, 32 tail workgroups
+    with one whole tail each and a share of the last eight; every output checked, and the accumulating form."""
+    batch, c_in, c_out, hw = 4, 320, 512, 28
+    x = synth.normal(950, 0, (batch, c_in, hw, hw), 1.0)
+    dy = synth.normal(950, 1, (batch, c_out, hw, hw), 1.0)
+    d_x, d_dy = dev(x), dev(dy)
+    op = tofu.wgrad_desc(batch, c_in, c_out, hw, hw)
+    assert tofu.workspace_bytes(op, []) == (12 * 40 + 1 * 32 + 2 * 32) * 9 * 128 * 32 * 4, "the shape is meant to take every form of the balanced launch"
+    g = torch.full((c_out, c_in, 3, 3), float("nan"), dtype=torch.float32, device=DEV)
+    tofu.shard_conv2d_wgrad(op, [], tofu.tensor(d_x), tofu.tensor(d_dy), tofu.tensor(g), ws(op, []))
+    val, absum = oracle.wgrad_box(x, dy, 3, 3, pad=1)
+    close(g.cpu().numpy(), val, absum, "wgrad 40 tiles")
+    base = torch.full_like(g, -2.0)
+    acc = base.clone()
+    tofu.shard_conv2d_wgrad_accumulate(op, [], tofu.tensor(d_x), tofu.tensor(d_dy), tofu.tensor(acc), ws(op, []))
+    assert torch.equal(acc, base + g), "accumulate differs from add-after"
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_matmul_and_conv1d(seed):
     rng = random.Random(2000 + seed)
