@@ -17,10 +17,11 @@
 //     the virtual rows [T_a, T_b] its positions need.
 //   * One MFMA contracts the same tap of two adjacent input channels (lanes 0-31: ci, lanes
 //     32-63: ci+1); the B operand of a lane is one LDS read at (its position's row/col) + tap.
-//   * Launch: full waves of 512 tiles run one workgroup per tile.  The tiles of the last, partial
-//     wave are cut into (tile, channel step) units dealt evenly to 512 workgroups -- the same
-//     even split as a shard range -- whose runs inside one tile (segments) go to workspace slots;
-//     a second kernel sums each tile's slots in workgroup order (fixed, no atomics).
+//   * Launch: full waves of 512 tiles run one workgroup per tile.  The channel steps of the last,
+//     partial wave's tiles are dealt to 512 workgroups as tofu_balance.h describes (the same work
+//     for every workgroup, neighbours at the same steps at the same time); every piece of a tile
+//     goes to a workspace slot and a second kernel sums each tile's slots in the order of the
+//     channel steps (fixed, no atomics).
 // The same kernel serves the variant that reads its input region from several blocks (the fetch
 // fused into the consumer, Sec. 6) and, on reversed filters, the data gradient.
 #include <hip/hip_runtime.h>
@@ -589,7 +590,7 @@ struct ConvProblem {
   int64_t ws[4];
   float* y;                  // element at out_box's low corner
   int64_t ys[4];
-  void* workspace;           // segment slots of a balanced launch (conv_workspace_bytes), may be NULL when none are needed
+  void* workspace;           // piece slots of a balanced launch (conv_workspace_bytes), may be NULL when none are needed
   size_t workspace_bytes;
   bool accumulate;           // add to the output box instead of overwriting it
   int KH = 3, KW = 3;        // filter rows / columns: 3 x 3 or 1 x 3

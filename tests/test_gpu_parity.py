@@ -520,8 +520,8 @@ def test_wgrad_pnr_invariant_bit_exact(k):
 
 
 def test_wgrad_many_tiles_few_images():
-    """960 output tiles x 2 images over 512 workgroups: a workgroup's unit range then spans up
-    to three tiles (partial, whole, partial), every tile is summed from workspace slots."""
+    """960 output tiles x 2 images: the first 512 tiles run one workgroup each and write dw directly,
+    the other 448 are balanced over the workgroup slots and summed from workspace slots."""
     co, ci, nb = 640, 6144, 2
     opd = dict(kind="conv2d_wgrad", batch=nb, c_in=ci, c_out=co, H=4, W=4, KH=3, KW=3, stride=1, pad=1)
     x = synth.normal(53, 0, (nb, ci, 4, 4), 1.0)
@@ -532,6 +532,21 @@ def test_wgrad_many_tiles_few_images():
     val, absum = oracle.wgrad_pts(x, dy, 3, 3, pts, pad=1)
     assert not np.isnan(got).any()
     assert_close(got[tuple(pts.T)], val, absum, "wgrad 960 tiles x 2 images")
+
+
+def test_wgrad_whole_waves_then_a_balanced_rest_on_the_two_row_form():
+    """640 tiles of a 14 x 14 layer (two output rows per step): one whole wave of 512 tiles, then 128 tiles
+    with four workgroups each; sampled outputs of both parts, the seam between them and the corners."""
+    co, ci, nb = 1280, 2048, 4
+    opd = dict(kind="conv2d_wgrad", batch=nb, c_in=ci, c_out=co, H=14, W=14, KH=3, KW=3, stride=1, pad=1)
+    x = synth.normal(54, 0, (nb, ci, 14, 14), 1.0)
+    dy = synth.normal(54, 1, (nb, co, 14, 14), 1.0)
+    got = run_wgrad(opd, [], dev(x), dev(dy)).cpu().numpy()
+    pts = np.concatenate([synth.coords(54, 2, 6000, got.shape),
+                          np.array([[0, 0, 0, 0], [co - 1, ci - 1, 2, 2], [1023, 2047, 1, 1], [1024, 0, 0, 2], [1279, 31, 2, 0], [896, 2016, 1, 2]])])   # incl. the last whole and the first balanced tile
+    val, absum = oracle.wgrad_pts(x, dy, 3, 3, pts, pad=1)
+    assert not np.isnan(got).any()
+    assert_close(got[tuple(pts.T)], val, absum, "wgrad 640 tiles, two-row steps")
 
 
 def test_runs_are_bit_identical():
