@@ -381,31 +381,66 @@ __global__ void __launch_bounds__(64 * (BM / 32), FAST ? 2 : 1) wgrad_kernel(con
 }
 
 // Sums every tile's pieces (workspace slots) in the order of their units and writes
-// dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine reads per slot are coalesced
-// across lanes (ci fastest); its nine writes cover 36 contiguous bytes of a dense dw.
+// dw[co][ci][kh][kw], or with `accumulate` adds that sum to what dw holds.  One thread per (co, ci): its nine
+// reads per slot are coalesced across lanes (ci fastest).  A workgroup handles eight output-channel rows of a
+// tile at a time.  DENSE (dw rows of a (co) are contiguous over (ci, kh, kw) and 16-byte aligned): the sums
+// go through LDS and leave as 16-byte vectors, 1152 contiguous bytes per row; otherwise every thread writes
+// its nine values where the strides put them.
+template <bool DENSE>
 __global__ void __launch_bounds__(256) wgrad_segment_sum_kernel(float* __restrict__ dw, int64_t s_co, int64_t s_ci, int64_t s_kh, int64_t s_kw,
                                                                  const float* __restrict__ slots, const Balance bal, int UPT, int tile0,
                                                                  int tiles_m, int tiles_n, int CO, int CI, int accumulate) {
-  constexpr int BM = 128, BCI = 32;
-  const int64_t items = (int64_t)bal.n * BM * BCI;   // the balanced tiles [tile0, tile0 + bal.n)
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (int64_t)gridDim.x * blockDim.x) {
+  constexpr int BM = 128, BCI = 32, ROWS = 256 / BCI, ROW = BCI * 9;
+  __shared__ __align__(16) float tile_s[DENSE ? ROWS * (ROW + 4) : 4];
+  const int64_t items = (int64_t)bal.n * BM * BCI;   // the balanced tiles [tile0, tile0 + bal.n): a multiple of the block size
+  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x; i0 < items; i0 += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = i0 + threadIdx.x;
     const int tile = (int)(i / (BM * BCI)), local = (int)(i % (BM * BCI)), co_l = local / BCI, ci_l = local % BCI;
     int tile_n, tile_m;
     wgrad_decode_tile(tile0 + tile, tiles_m, tiles_n, tile_n, tile_m);
     const int co = tile_m * BM + co_l, ci = tile_n * BCI + ci_l;
-    if (co >= CO || ci >= CI) continue;
+    const bool live = co < CO && ci < CI;
     float acc[9];
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) acc[tap] = 0.f;
-    balance_for_each_slot(bal, UPT, tile, [&](int slot) {
-      const float* sl = slots + (int64_t)slot * kSlotFloats + co_l * BCI + ci_l;
+    if (live)
+      balance_for_each_slot(bal, UPT, tile, [&](int slot) {
+        const float* sl = slots + (int64_t)slot * kSlotFloats + co_l * BCI + ci_l;
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
-    });
+        for (int tap = 0; tap < 9; ++tap) acc[tap] += sl[tap * BM * BCI];
+      });
+    if constexpr (DENSE) {
+      const int r = threadIdx.x / BCI;
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-      float* o = dw + co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw;
-      *o = accumulate ? *o + acc[tap] : acc[tap];
+      for (int tap = 0; tap < 9; ++tap) tile_s[r * (ROW + 4) + ci_l * 9 + tap] = acc[tap];
+      __syncthreads();
+      // the block's eight rows start at output channel co - r; every row holds the tile's input channels x 9 taps
+      const int co0 = co - r, c0 = tile_n * BCI;
+      const int valid = (CI - c0 < BCI ? CI - c0 : BCI) * 9;            // floats of a row that lie inside the box
+      for (int v = threadIdx.x; v < ROWS * (ROW / 4); v += 256) {
+        const int row = v / (ROW / 4), q = v - row * (ROW / 4);
+        if (co0 + row >= CO || 4 * q >= valid) continue;
+        const float* src = &tile_s[row * (ROW + 4) + 4 * q];
+        float* o = dw + (int64_t)(co0 + row) * s_co + (int64_t)c0 * 9 + 4 * q;
+        if (4 * q + 3 < valid) {
+          v4f32 val = *reinterpret_cast<const v4f32*>(src);
+          if (accumulate) {
+            const v4f32 old = *reinterpret_cast<const v4f32*>(o);
+            val = old + val;
+          }
+          *reinterpret_cast<v4f32*>(o) = val;
+        } else {
+          for (int e = 0; 4 * q + e < valid; ++e) o[e] = accumulate ? o[e] + src[e] : src[e];
+        }
+      }
+      __syncthreads();
+    } else {
+      if (!live) continue;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        float* o = dw + co * s_co + ci * s_ci + (tap / 3) * s_kh + (tap % 3) * s_kw;
+        *o = accumulate ? *o + acc[tap] : acc[tap];
+      }
     }
   }
 }
@@ -550,7 +585,8 @@ static int shard_wgrad(const tofu_op_desc_t* op, const tofu_split_t* splits, int
     if (e != hipSuccess) return fail(TOFU_ERR_HIP, "conv2d weight-gradient launch failed: %s", hipGetErrorString(e));
     const int64_t items = rest * gBM * gBCI;
     const int blocks = (int)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
-    hipLaunchKernelGGL(wgrad_segment_sum_kernel, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
+    const bool dense = os[3] == 1 && os[2] == 3 && os[1] == 9 && os[0] % 4 == 0 && (reinterpret_cast<uintptr_t>(dw_out) & 15) == 0;
+    hipLaunchKernelGGL(dense ? wgrad_segment_sum_kernel<true> : wgrad_segment_sum_kernel<false>, dim3(blocks), dim3(256), 0, s, dw_out, os[0], os[1], os[2], os[3],
                        static_cast<const float*>(workspace), p.bal, (int)UPT, (int)whole, p.tiles_m, p.tiles_n,
                        (int)CO, (int)CI, accumulate ? 1 : 0);
     e = hipGetLastError();
