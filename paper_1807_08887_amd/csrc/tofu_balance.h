@@ -158,12 +158,23 @@ inline Balance balance_plan(int64_t n, int64_t steps, int max_groups, int segmen
   if (g2 > 0) {
     const int rounds = (int)(n / g2);
     const int64_t left = n - (int64_t)rounds * g2;
-    // the shortest piece whose tails keep the tail workgroups no longer busy than the others
-    for (int piece = units / b.groups > 0 ? (int)(units / b.groups) : 1; piece < full; ++piece) {
+    // the shortest piece whose tails keep the tail workgroups no longer busy than the others; a longer piece
+    // means shorter tails, so the condition is monotone and the shortest piece is found by bisection
+    auto fits = [&](int64_t piece) {
       const int64_t tail = steps - (int64_t)b.per_tile * piece;
       const int64_t per = rounds * tail + (left * tail + g2 - 1) / g2;
       const int64_t segments = rounds + (left > 0 ? 2 : 0);
-      if (per + segments * segment_cost <= piece + segment_cost) { b.piece = piece; b.rounds = rounds; break; }
+      return per + segments * segment_cost <= piece + segment_cost;
+    };
+    int64_t lo = units / b.groups > 0 ? units / b.groups : 1, hi = full;   // pieces in [lo, full) leave a tail; `full` none
+    if (lo < hi && fits(hi - 1)) {
+      int64_t bad = lo - 1, good = hi - 1;                                 // fits(good), and bad is below the range or does not fit
+      while (good - bad > 1) {
+        const int64_t mid = bad + (good - bad) / 2;
+        if (fits(mid)) good = mid; else bad = mid;
+      }
+      b.piece = (int)good;
+      b.rounds = rounds;
     }
   }
   const int64_t covered = (int64_t)b.per_tile * b.piece;

@@ -75,6 +75,19 @@ int main() {
     printf("n=%d steps=%d: groups=%d per_tile=%d piece=%d tail0=%d rounds=%d slots=%lld busiest/even=%.4f\n", c.first, c.second, b.groups, b.per_tile,
            b.piece, b.tail0, b.rounds, (long long)balance_slots(b, c.second), w);
   }
+  {  // a very long reduction: the plan is found by bisection (no loop over the steps), and the segments still add up
+    const int64_t n = 400, steps = (int64_t)1 << 28;
+    const Balance b = balance_plan(n, steps, 512, 2);
+    int64_t total = 0, busiest = 0;
+    for (int wg = 0; wg < b.groups; ++wg) {
+      const BalanceWalk w = balance_walk(b, (int)steps, wg);
+      int64_t work = 0;
+      for (int i = 0; i < w.count; ++i) { const BalanceSegment sg = balance_segment(w, i); work += sg.end - sg.begin; }
+      total += work;
+      if (work > busiest) busiest = work;
+    }
+    if (total != n * steps || busiest > (n * steps / 512) * 1.001 + 64) { printf("long reduction: total %lld busiest %lld\n", (long long)total, (long long)busiest); return 1; }
+  }
   printf("cases=%d worst busiest/(even + 2 cost)=%.3f, with 80 or more steps %.3f\n", cases, worst, worst_long);
   // long reductions (the case the scheme is for) must stay within 5 % of the even share
   return worst_long <= 1.05 ? 0 : 2;
